@@ -1,0 +1,208 @@
+"""Seeded synthetic inputs for the TEAM MoE-layer hot path.
+
+This module only *draws numbers*: Gaussian hidden states, Gaussian weights, the
+row normalisation applied to hidden states before an MoE layer, rounding to
+bfloat16 storage, and the activated-expert masks the workloads use.  It holds
+none of the layer's arithmetic (no router, no top-k, no expert FFN, no combine)
+so that both the HIP path and the CPU oracle can be fed from it without sharing
+any code of the method.
+
+Shapes follow the model the paper evaluates (Section "Experiments", setup: SDAR
+30B-A3B with 128 experts, 8 experts per token, 48 layers, blocks of 32 tokens,
+4 speculative branches); the paper's own benchmarks and weights are not used,
+every tensor here is synthetic.
+
+Reproducibility: every tensor is drawn from a counter-based Philox stream keyed
+by ``(seed, tag, layer, sub)`` so any slice (one expert of one layer) can be
+regenerated on its own, in any order, on any number of threads.
+"""
+from __future__ import annotations
+
+import os
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass, replace
+from typing import Dict, Optional
+
+import numpy as np
+
+# tensor tags of the Philox key
+TAG_X_BASE, TAG_X_NOISE, TAG_W_ROUTER, TAG_W_GATE, TAG_W_UP, TAG_W_DOWN, TAG_MASK, TAG_PERM = range(1, 9)
+
+WEIGHT_STD = 0.02          # "weights ~ N(0, 0.02)" read as standard deviation 0.02
+RMS_EPS = 1e-6
+
+
+@dataclass(frozen=True)
+class MoEShape:
+    """Sizes of one MoE layer call. dtype is the storage type of x, weights and y."""
+    name: str
+    T: int          # tokens in the call
+    H: int          # hidden size
+    E: int          # number of experts
+    k: int          # experts per token
+    I: int          # expert SwiGLU intermediate size
+    dtype: str      # "f32" | "bf16"
+    renormalize: int = 1
+    normed_x: bool = True
+
+    @property
+    def bytes_per_expert(self) -> int:
+        return 3 * self.H * self.I * (4 if self.dtype == "f32" else 2)
+
+
+# The five workload shapes (one entry per benchmark configuration).
+CFG1 = MoEShape("cfg1_tiny_f32", T=8, H=256, E=16, k=2, I=128, dtype="f32", normed_x=False)
+CFG2 = MoEShape("cfg2_30b_a3b_block32", T=32, H=2048, E=128, k=8, I=768, dtype="bf16")
+CFG3 = MoEShape("cfg3_speculative_4x32", T=128, H=2048, E=128, k=8, I=768, dtype="bf16")
+CFG4 = MoEShape("cfg4_stack48_block32", T=32, H=2048, E=128, k=8, I=768, dtype="bf16")
+CFG5 = MoEShape("cfg5_fine_grained_256", T=256, H=2048, E=256, k=8, I=512, dtype="bf16")
+CONFIGS = {c.name: c for c in (CFG1, CFG2, CFG3, CFG4, CFG5)}
+
+
+def scaled(shape: MoEShape, **kw) -> MoEShape:
+    """A copy of a shape with some sizes replaced (reduced test cases)."""
+    return replace(shape, **kw)
+
+
+# --------------------------------------------------------------------------- rng
+def _stream(seed: int, tag: int, layer: int = 0, sub: int = 0) -> np.random.Generator:
+    key = np.array([np.uint64(seed), (np.uint64(tag) << np.uint64(48)) | (np.uint64(layer) << np.uint64(24))
+                    | np.uint64(sub)], dtype=np.uint64)
+    return np.random.Generator(np.random.Philox(key=key))
+
+
+def normal(seed: int, tag: int, layer: int, sub: int, n: int, std: float = 1.0) -> np.ndarray:
+    """n fp32 draws of N(0, std^2) from stream (seed, tag, layer, sub)."""
+    a = _stream(seed, tag, layer, sub).standard_normal(n, dtype=np.float32)
+    if std != 1.0:
+        a *= np.float32(std)
+    return a
+
+
+# --------------------------------------------------------------------------- bf16 storage
+def bf16_round(a: np.ndarray) -> np.ndarray:
+    """fp32 -> bfloat16 bit patterns (uint16), round to nearest even. Finite inputs only."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    r = (u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_widen(bits: np.ndarray) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) -> the exactly equal fp32 values."""
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def store(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Round fp32 draws to the storage dtype: float32 array for "f32", uint16 bit patterns for "bf16"."""
+    return np.ascontiguousarray(a, dtype=np.float32) if dtype == "f32" else bf16_round(a)
+
+
+def as_f32(stored: np.ndarray) -> np.ndarray:
+    """Exact fp32 view of a stored tensor (what the CPU oracle consumes)."""
+    return bf16_widen(stored) if stored.dtype == np.uint16 else np.asarray(stored, dtype=np.float32)
+
+
+# --------------------------------------------------------------------------- hidden states
+def rms_normalise(x: np.ndarray) -> np.ndarray:
+    """Unit-gain RMS normalisation of each row, fp32 (the pre-MoE norm of the model; input recipe only)."""
+    x = x.astype(np.float32)
+    ms = np.mean(x.astype(np.float64) ** 2, axis=1, keepdims=True)
+    return (x / np.sqrt(ms + RMS_EPS)).astype(np.float32)
+
+
+def make_x(shape: MoEShape, seed: int = 0, layer: int = 0, step: int = 0, kind: str = "iid",
+           noise_std: float = 0.0) -> np.ndarray:
+    """Hidden states [T,H] in storage dtype.
+
+    kind="iid":        rows ~ N(0,1) (RMS-normalised when shape.normed_x).
+    kind="candidates": T = C*32 rows; a shared 32-row base ~N(0,1) plus per-candidate noise of std
+                       ``noise_std`` (speculative branches whose hidden states are highly similar;
+                       Section "Speculative Exploration for Hot Tokens").
+    kind="drift":      base ~N(0,1) for the layer plus per-step noise of std ``noise_std`` (hidden states of
+                       the same block at successive denoising steps; Section "Temporal Consistency").
+    """
+    T, H = shape.T, shape.H
+    if kind == "iid":
+        x = normal(seed, TAG_X_BASE, layer, step, T * H).reshape(T, H)
+    elif kind == "candidates":
+        L = 32
+        assert T % L == 0
+        base = normal(seed, TAG_X_BASE, layer, 0, L * H).reshape(L, H)
+        parts = [base + normal(seed, TAG_X_NOISE, layer, c, L * H, noise_std).reshape(L, H) for c in range(T // L)]
+        x = np.concatenate(parts, axis=0)
+    elif kind == "drift":
+        base = normal(seed, TAG_X_BASE, layer, 0, T * H).reshape(T, H)
+        x = base + normal(seed, TAG_X_NOISE, layer, step, T * H, noise_std).reshape(T, H)
+    else:
+        raise ValueError(kind)
+    if shape.normed_x:
+        x = rms_normalise(x)
+    return store(x, shape.dtype)
+
+
+# --------------------------------------------------------------------------- weights
+def _expert_matrix(seed: int, tag: int, layer: int, e: int, n: int, dtype: str) -> np.ndarray:
+    return store(normal(seed, tag, layer, e + 1, n, WEIGHT_STD), dtype)
+
+
+def make_router(shape: MoEShape, seed: int = 0, layer: int = 0) -> np.ndarray:
+    return store(normal(seed, TAG_W_ROUTER, layer, 0, shape.E * shape.H, WEIGHT_STD), shape.dtype).reshape(shape.E, shape.H)
+
+
+def make_expert(shape: MoEShape, e: int, seed: int = 0, layer: int = 0) -> Dict[str, np.ndarray]:
+    """Weights of one expert: gate [I,H], up [I,H], down [H,I] (out-features major, reduction dim contiguous)."""
+    H, I = shape.H, shape.I
+    return {
+        "gate": _expert_matrix(seed, TAG_W_GATE, layer, e, I * H, shape.dtype).reshape(I, H),
+        "up": _expert_matrix(seed, TAG_W_UP, layer, e, I * H, shape.dtype).reshape(I, H),
+        "down": _expert_matrix(seed, TAG_W_DOWN, layer, e, H * I, shape.dtype).reshape(H, I),
+    }
+
+
+def make_weights(shape: MoEShape, seed: int = 0, layer: int = 0, threads: Optional[int] = None) -> Dict[str, np.ndarray]:
+    """All weights of one layer: router [E,H], gate/up [E,I,H], down [E,H,I] in storage dtype."""
+    E, H, I = shape.E, shape.H, shape.I
+    np_dt = np.float32 if shape.dtype == "f32" else np.uint16
+    out = {"router": make_router(shape, seed, layer),
+           "gate": np.empty((E, I, H), np_dt), "up": np.empty((E, I, H), np_dt), "down": np.empty((E, H, I), np_dt)}
+
+    def fill(e):
+        w = make_expert(shape, e, seed, layer)
+        out["gate"][e], out["up"][e], out["down"][e] = w["gate"], w["up"], w["down"]
+
+    threads = threads or min(16, os.cpu_count() or 1)
+    if threads > 1 and E > 1:
+        with ThreadPoolExecutor(threads) as ex:
+            list(ex.map(fill, range(E)))
+    else:
+        for e in range(E):
+            fill(e)
+    return out
+
+
+# --------------------------------------------------------------------------- activated-expert sets
+def random_mask(E: int, M: int, seed: int = 0, layer: int = 0) -> np.ndarray:
+    """Byte mask [E] with exactly M ones at seeded random positions."""
+    perm = _stream(seed, TAG_MASK, layer, M).permutation(E)
+    m = np.zeros(E, np.uint8)
+    m[perm[:M]] = 1
+    return m
+
+
+def activated_set_by_summed_probability(logits: np.ndarray, M: int) -> np.ndarray:
+    """Workload recipe for the activated-expert set of a call: the M experts with the largest router
+    probability summed over all tokens of the call (ties to the lower id).  ``logits`` [T,E] are handed in by
+    the caller (the oracle's in the tests); this is how the *input* mask is drawn, not a step of the layer."""
+    z = logits.astype(np.float64)
+    z = z - z.max(axis=1, keepdims=True)
+    p = np.exp(z)
+    p /= p.sum(axis=1, keepdims=True)
+    score = p.sum(axis=0)
+    order = np.lexsort((np.arange(score.size), -score))
+    m = np.zeros(score.size, np.uint8)
+    m[order[:M]] = 1
+    return m
+
+
+def token_permutation(T: int, seed: int = 0) -> np.ndarray:
+    return _stream(seed, TAG_PERM, 0, T).permutation(T)

@@ -1,0 +1,327 @@
+"""Pins of the CPU oracle (no GPU).
+
+The paper prints no worked numerical example of a MoE layer, so the oracle is pinned by what the paper's
+Algorithm 1 and the mathematics fix: a hand-worked example, special cases that reduce to textbook routines,
+invariants (superset invariance is the premise of Algorithm 1's two-round routing), brute force on tiny
+inputs, and a second implementation written independently in NumPy.
+"""
+import itertools
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import c_oracle as orc
+from oracle.moe_numpy import moe_layer_numpy
+from paper_2602_08404_amd import inputs as gen
+
+
+def tiny(T=6, H=16, E=8, I=12, seed=0, std_w=0.3):
+    r = np.random.default_rng(seed)
+    x = r.standard_normal((T, H)).astype(np.float32)
+    wr = (r.standard_normal((E, H)) * std_w).astype(np.float32)
+    wg = (r.standard_normal((E, I, H)) * std_w).astype(np.float32)
+    wu = (r.standard_normal((E, I, H)) * std_w).astype(np.float32)
+    wd = (r.standard_normal((E, H, I)) * std_w).astype(np.float32)
+    return x, wr, wg, wu, wd
+
+
+def sigmoid(z):
+    return 1.0 / (1.0 + np.exp(-z))
+
+
+# ----------------------------------------------------------------------------- P9 hand-worked example
+def test_hand_example(golden_dir):
+    fx = json.load(open(os.path.join(golden_dir, "hand_example.json")))
+    x, wr = np.array(fx["x"], np.float32), np.array(fx["w_router"], np.float32)
+    wg, wu, wd = (np.array(fx[n], np.float32) for n in ("w_gate", "w_up", "w_down"))
+    for case in fx["cases"]:
+        mask = None if case["mask"] is None else np.array(case["mask"], np.uint8)
+        y, idx, gate = orc.moe_layer(x, wr, wg, wu, wd, case["k"], 1, mask)
+        assert idx.tolist() == case["idx"]
+        np.testing.assert_allclose(gate, np.array(case["gate"]), rtol=0, atol=1e-15)
+        np.testing.assert_allclose(y, np.array(case["y"]), rtol=1e-14, atol=0)
+        y2, idx2, gate2 = moe_layer_numpy(x, wr, wg, wu, wd, case["k"], 1, mask)
+        assert idx2.tolist() == case["idx"]
+        np.testing.assert_allclose(y2, np.array(case["y"]), rtol=1e-14, atol=0)
+
+
+# ----------------------------------------------------------------------------- P2 one expert == dense SwiGLU
+def test_single_expert_is_dense_swiglu():
+    x, wr, wg, wu, wd = tiny(T=5, H=24, E=1, I=10, seed=1)
+    y, idx, gate = orc.moe_layer(x, wr, wg, wu, wd, 1, 1, None)
+    assert (idx == 0).all() and np.allclose(gate, 1.0)
+    x64 = x.astype(np.float64)
+    g = x64 @ wg[0].astype(np.float64).T
+    u = x64 @ wu[0].astype(np.float64).T
+    ref = (g * sigmoid(g) * u) @ wd[0].astype(np.float64).T          # textbook SwiGLU FFN
+    np.testing.assert_allclose(y, ref, rtol=1e-12, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------- P1 all-ones / NULL mask == plain top-k MoE
+def plain_topk_moe(x, wr, wg, wu, wd, k):
+    """A mask-free top-k MoE written separately: full softmax, top-k by probability, renormalise."""
+    x = x.astype(np.float64)
+    T, H = x.shape
+    y = np.zeros((T, H))
+    logits = (x @ wr.astype(np.float64).T).astype(np.float32).astype(np.float64)
+    for t in range(T):
+        p = np.exp(logits[t] - logits[t].max())
+        p /= p.sum()
+        chosen = sorted(range(len(p)), key=lambda e: (-p[e], e))[:k]
+        w = np.array([p[e] for e in chosen])
+        w /= w.sum()
+        for e, we in zip(chosen, w):
+            g = wg[e].astype(np.float64) @ x[t]
+            u = wu[e].astype(np.float64) @ x[t]
+            y[t] += we * (wd[e].astype(np.float64) @ (g * sigmoid(g) * u))
+    return y
+
+
+@pytest.mark.parametrize("k", [1, 2, 3])
+def test_full_mask_equals_plain_topk_moe(k):
+    x, wr, wg, wu, wd = tiny(seed=2)
+    y_null, idx_null, gate_null = orc.moe_layer(x, wr, wg, wu, wd, k, 1, None)
+    y_ones, idx_ones, gate_ones = orc.moe_layer(x, wr, wg, wu, wd, k, 1, np.ones(8, np.uint8))
+    assert (idx_null == idx_ones).all()
+    np.testing.assert_array_equal(y_null, y_ones)
+    np.testing.assert_allclose(y_null, plain_topk_moe(x, wr, wg, wu, wd, k), rtol=1e-11, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- P3 token-permutation equivariance
+def test_permutation_equivariance():
+    x, wr, wg, wu, wd = tiny(T=9, seed=3)
+    mask = gen.random_mask(8, 5, seed=3)
+    perm = gen.token_permutation(9, seed=3)
+    y, idx, gate = orc.moe_layer(x, wr, wg, wu, wd, 2, 1, mask)
+    yp, idxp, gatep = orc.moe_layer(x[perm], wr, wg, wu, wd, 2, 1, mask)
+    np.testing.assert_array_equal(yp, y[perm])
+    np.testing.assert_array_equal(idxp, idx[perm])
+
+
+# ----------------------------------------------------------------------------- P4 gates
+@pytest.mark.parametrize("M", [8, 5, 2])
+def test_gates_normalised_positive_descending(M):
+    x, wr, wg, wu, wd = tiny(T=12, seed=4)
+    mask = gen.random_mask(8, M, seed=4)
+    idx, gate, logits = orc.route(x, wr, 3, 1, mask)
+    k_eff = min(3, M)
+    np.testing.assert_allclose(gate.sum(axis=1), 1.0, rtol=0, atol=1e-12)
+    assert (gate[:, :k_eff] > 0).all() and (gate[:, k_eff:] == 0).all()
+    assert (np.diff(gate[:, :k_eff], axis=1) <= 0).all()
+    assert (idx[:, k_eff:] == -1).all()
+    assert mask[idx[:, :k_eff]].all()                 # strictly confined to the activated set
+    for t in range(12):
+        assert len(set(idx[t, :k_eff].tolist())) == k_eff
+
+
+def test_gates_without_renormalisation_are_full_softmax_entries():
+    x, wr, wg, wu, wd = tiny(T=7, seed=5)
+    mask = gen.random_mask(8, 4, seed=5)
+    idx, gate, logits = orc.route(x, wr, 2, 0, mask)
+    z = logits.astype(np.float64)
+    p = np.exp(z - z.max(1, keepdims=True))
+    p /= p.sum(1, keepdims=True)
+    np.testing.assert_allclose(gate, np.take_along_axis(p, idx, 1), rtol=1e-13)
+    assert (gate.sum(1) < 1).all()
+
+
+# ----------------------------------------------------------------------------- P5 brute-force selection
+@pytest.mark.parametrize("seed", range(4))
+def test_topk_matches_subset_enumeration_and_full_sort(seed):
+    E, k = 10, 3
+    r = np.random.default_rng(100 + seed)
+    logits = r.standard_normal((20, E)).astype(np.float32)
+    mask = gen.random_mask(E, 6, seed=seed)
+    idx, gate = orc.route_from_logits(logits, k, 1, mask)
+    allowed = [e for e in range(E) if mask[e]]
+    for t in range(20):
+        best = max(itertools.combinations(allowed, k), key=lambda c: sum(float(logits[t, e]) for e in c))
+        assert set(best) == set(idx[t].tolist())
+        full = sorted(allowed, key=lambda e: (-logits[t, e], e))[:k]
+        assert full == idx[t].tolist()
+
+
+def test_ties_go_to_lower_id_and_zero_router_gives_uniform_gates():
+    x, wr, wg, wu, wd = tiny(T=4, seed=6)
+    mask = np.array([0, 1, 0, 1, 1, 0, 1, 1], np.uint8)
+    idx, gate, logits = orc.route(x, np.zeros_like(wr), 3, 1, mask)
+    assert (idx == np.array([1, 3, 4])).all()
+    np.testing.assert_allclose(gate, 1.0 / 3.0, rtol=0, atol=1e-15)
+    logits = np.array([[0.5, 2.0, 2.0, -1.0, 2.0]], np.float32)
+    idx, gate = orc.route_from_logits(logits, 2, 1, None)
+    assert idx.tolist() == [[1, 2]]
+
+
+# ----------------------------------------------------------------------------- P6 superset invariance (Algorithm 1)
+@pytest.mark.parametrize("renorm", [1, 0])
+def test_superset_invariance(renorm):
+    """Algorithm 1 routes first-round tokens over all experts and defines E_A as the union of their picks;
+    confining those same tokens to any superset of their picks must change nothing (both gate modes)."""
+    x, wr, wg, wu, wd = tiny(T=5, E=8, seed=7)
+    y0, idx0, gate0 = orc.moe_layer(x, wr, wg, wu, wd, 2, renorm, None)
+    union = np.zeros(8, np.uint8)
+    union[np.unique(idx0)] = 1
+    assert union.sum() < 8
+    y1, idx1, gate1 = orc.moe_layer(x, wr, wg, wu, wd, 2, renorm, union)
+    np.testing.assert_array_equal(idx0, idx1)
+    np.testing.assert_array_equal(gate0, gate1)
+    np.testing.assert_array_equal(y0, y1)
+    # second round: tokens confined to E_A only pick inside it
+    x2 = tiny(T=11, E=8, seed=70)[0]
+    _, idx2, _ = orc.moe_layer(x2, wr, wg, wu, wd, 2, renorm, union)
+    assert union[idx2].all()
+
+
+# ----------------------------------------------------------------------------- P7 sub-model equivalence
+def test_masked_layer_equals_compacted_model():
+    x, wr, wg, wu, wd = tiny(T=7, E=8, seed=8)
+    mask = gen.random_mask(8, 5, seed=8)
+    keep = np.nonzero(mask)[0]
+    y, idx, gate = orc.moe_layer(x, wr, wg, wu, wd, 2, 1, mask)
+    ys, idxs, gates = orc.moe_layer(x, wr[keep], wg[keep], wu[keep], wd[keep], 2, 1, None)
+    np.testing.assert_array_equal(keep[idxs], idx)
+    np.testing.assert_array_equal(gates, gate)
+    np.testing.assert_array_equal(ys, y)
+
+
+# ----------------------------------------------------------------------------- P8 closed forms
+def test_closed_forms():
+    x, wr, wg, wu, wd = tiny(seed=9)
+    mask = gen.random_mask(8, 4, seed=9)
+    y, idx, gate = orc.moe_layer(np.zeros_like(x), wr, wg, wu, wd, 2, 1, mask)
+    assert (y == 0).all()                                               # silu(0)*0 = 0
+    y, _, _ = orc.moe_layer(x, wr, wg, wu, np.zeros_like(wd), 2, 1, mask)
+    assert (y == 0).all()
+    y, _, _ = orc.moe_layer(x, wr, wg, wu, wd, 2, 1, np.zeros(8, np.uint8))
+    assert (y == 0).all()                                               # empty activated set
+    # linear in one expert's down projection
+    y0, idx, gate = orc.moe_layer(x, wr, wg, wu, wd, 2, 1, mask)
+    e = int(idx[0, 0])
+    wd2 = wd.copy()
+    wd2[e] *= 4.0                                                       # exact in floating point
+    y1, _, _ = orc.moe_layer(x, wr, wg, wu, wd2, 2, 1, mask)
+    o = orc.expert_rows(x, wg, wu, wd, idx)
+    contrib = np.where((idx == e)[:, :, None], gate[:, :, None] * o, 0.0).sum(1)
+    np.testing.assert_allclose(y1 - y0, 3.0 * contrib, rtol=1e-9, atol=1e-13)
+    # swapping gate and up projections changes the result (silu is applied to the gate branch only)
+    y2, _, _ = orc.moe_layer(x, wr, wu, wg, wd, 2, 1, mask)
+    assert np.abs(y2 - y0).max() > 1e-3
+
+
+def test_known_silu_values():
+    # H=1: g = x*wg; u = x*wu; y = wd * silu(g) * u, with silu(2) = 2/(1+e^-2)
+    y, _, _ = orc.moe_layer(np.array([[2.0]], np.float32), np.array([[1.0]], np.float32), np.array([[[1.0]]], np.float32),
+                            np.array([[[0.5]]], np.float32), np.array([[[3.0]]], np.float32), 1, 1, None)
+    assert abs(y[0, 0] - 3.0 * (2.0 / (1.0 + np.exp(-2.0))) * 1.0) < 1e-15
+
+
+# ----------------------------------------------------------------------------- P10 dispatch invariants
+@pytest.mark.parametrize("seed", range(3))
+def test_dispatch_invariants(seed):
+    E, k, T = 12, 3, 17
+    r = np.random.default_rng(200 + seed)
+    logits = r.standard_normal((T, E)).astype(np.float32)
+    mask = gen.random_mask(E, 7 if seed else 2, seed=seed)
+    idx, gate = orc.route_from_logits(logits, k, 1, mask)
+    offsets, sorted_token, inv_pos, active, n_active = orc.dispatch(idx, E)
+    k_eff = min(k, int(mask.sum()))
+    A = T * k_eff
+    assert offsets[0] == 0 and offsets[E] == A and (np.diff(offsets) >= 0).all()
+    counts = np.diff(offsets)
+    assert (counts[mask == 0] == 0).all()
+    for e in range(E):
+        rows = sorted_token[offsets[e]:offsets[e + 1]]
+        assert (np.diff(rows) > 0).all()                                 # token ids strictly increasing
+        assert counts[e] == (idx == e).sum()
+    valid = inv_pos[idx >= 0]
+    assert sorted(valid.tolist()) == list(range(A))                      # bijection onto [0,A)
+    assert (inv_pos[idx < 0] == -1).all()
+    for t in range(T):
+        for s in range(k):
+            if idx[t, s] >= 0:
+                p = inv_pos[t, s]
+                assert sorted_token[p] == t and offsets[idx[t, s]] <= p < offsets[idx[t, s] + 1]
+    assert active[:n_active].tolist() == [e for e in range(E) if counts[e] > 0]
+    assert (active[n_active:] == -1).all()
+    assert (sorted_token[A:] == -1).all()
+
+
+def test_dispatch_brute_force_sort():
+    E, k, T = 6, 2, 9
+    r = np.random.default_rng(5)
+    idx, _ = orc.route_from_logits(r.standard_normal((T, E)).astype(np.float32), k, 1, None)
+    offsets, sorted_token, inv_pos, active, n_active = orc.dispatch(idx, E)
+    pairs = sorted((int(idx[t, s]), t) for t in range(T) for s in range(k))
+    assert [p[1] for p in pairs] == sorted_token.tolist()
+
+
+# ----------------------------------------------------------------------------- P11 second implementation
+@pytest.mark.parametrize("renorm", [1, 0])
+@pytest.mark.parametrize("M", [None, 6, 1])
+def test_c_oracle_agrees_with_numpy_oracle_cfg1(renorm, M):
+    shape = gen.CFG1
+    w = gen.make_weights(shape, seed=0)
+    x = gen.make_x(shape, seed=0)
+    mask = None if M is None else gen.random_mask(shape.E, M, seed=0)
+    y, idx, gate = orc.moe_layer(x, w["router"], w["gate"], w["up"], w["down"], shape.k, renorm, mask)
+    y2, idx2, gate2 = moe_layer_numpy(x, w["router"], w["gate"], w["up"], w["down"], shape.k, renorm, mask)
+    np.testing.assert_array_equal(idx, idx2)
+    np.testing.assert_allclose(gate, gate2, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(y, y2, rtol=1e-9, atol=1e-15)
+
+
+def test_c_oracle_agrees_with_numpy_oracle_bf16_shape():
+    shape = gen.scaled(gen.CFG2, E=16, I=64, H=256, T=12, k=4)
+    w = {n: gen.as_f32(a) for n, a in gen.make_weights(shape, seed=1).items()}
+    x = gen.as_f32(gen.make_x(shape, seed=1))
+    mask = gen.random_mask(shape.E, 7, seed=1)
+    y, idx, gate = orc.moe_layer(x, w["router"], w["gate"], w["up"], w["down"], shape.k, 1, mask)
+    y2, idx2, gate2 = moe_layer_numpy(x, w["router"], w["gate"], w["up"], w["down"], shape.k, 1, mask)
+    np.testing.assert_array_equal(idx, idx2)
+    np.testing.assert_allclose(y, y2, rtol=1e-9, atol=1e-16)
+
+
+def test_staged_calls_equal_whole_layer():
+    """route -> expert_rows -> combine (the decomposition the GPU boundary exposes) equals the per-token layer."""
+    x, wr, wg, wu, wd = tiny(T=8, seed=11)
+    mask = gen.random_mask(8, 5, seed=11)
+    y, idx, gate = orc.moe_layer(x, wr, wg, wu, wd, 3, 1, mask, threads=2)
+    idx2, gate2, _ = orc.route(x, wr, 3, 1, mask)
+    o = orc.expert_rows(x, wg, wu, wd, idx2, threads=2)
+    y2 = orc.combine(o, gate2, idx2)
+    np.testing.assert_array_equal(idx, idx2)
+    np.testing.assert_allclose(y, y2, rtol=1e-13, atol=1e-16)
+
+
+# ----------------------------------------------------------------------------- input generator sanity
+def test_bf16_round_trip_and_rne():
+    a = np.array([1.0, 1.00390625, 1.0078125, 1.01171875, -3.14159, 0.02, 1e-3], np.float32)
+    b = gen.bf16_widen(gen.bf16_round(a))
+    assert b[0] == 1.0
+    assert b[1] == 1.0            # 1 + 2^-8 is a tie between 1 and 1+2^-7: even mantissa wins
+    assert b[2] == 1.0078125
+    assert b[3] == 1.015625       # 1 + 3*2^-8 ties up to 1 + 2^-6
+    assert np.all(np.abs(b - a) <= np.abs(a) * 2.0 ** -8)
+    np.testing.assert_array_equal(gen.bf16_round(b), gen.bf16_round(a))
+
+
+def test_generator_is_reproducible_and_sliceable():
+    shape = gen.scaled(gen.CFG2, E=4, I=32, H=64)
+    w = gen.make_weights(shape, seed=3, layer=2, threads=1)
+    w2 = gen.make_weights(shape, seed=3, layer=2, threads=4)
+    for n in w:
+        np.testing.assert_array_equal(w[n], w2[n])
+    e2 = gen.make_expert(shape, 2, seed=3, layer=2)
+    np.testing.assert_array_equal(e2["down"], w["down"][2])
+    assert abs(gen.as_f32(w["gate"]).std() - 0.02) < 2e-3
+    x = gen.as_f32(gen.make_x(shape, seed=3))
+    np.testing.assert_allclose((x.astype(np.float64) ** 2).mean(1), 1.0, atol=5e-3)
+
+
+def test_summed_probability_mask():
+    logits = np.array([[5.0, 0.0, 0.0, 1.0], [0.0, 0.0, 5.0, 1.0]], np.float32)
+    assert gen.activated_set_by_summed_probability(logits, 2).tolist() == [1, 0, 1, 0]
+    assert gen.activated_set_by_summed_probability(logits, 3).tolist() == [1, 0, 1, 1]
+    assert gen.activated_set_by_summed_probability(np.zeros((3, 4), np.float32), 2).tolist() == [1, 1, 0, 0]
