@@ -1,0 +1,137 @@
+/*
+ * team_moe.h - C ABI of the MI355X (gfx950) MoE-layer forward used by TEAM-style block-diffusion decoding.
+ *
+ * One call of team_moe_layer_forward is one MoE layer of one denoising step over the live tokens of a
+ * diffusion block (and of its speculative branches), with expert routing confined to a per-step
+ * activated-expert set E_A.  The operation is the one TEAM's Algorithm 1 ("Limited Activation for cold
+ * tokens") hands to the model: Router(tokens, E_A) -> routing weights W, then the experts of E_A applied to
+ * their tokens and summed with W (Section "Limited Activation for Cold Tokens (LAC)"; the per-token top-k
+ * gating of a MoE layer is the standard one the paper assumes in Section "Related work / Mixture-of-Experts").
+ * The paper targets the memory-bound regime of block decoding (Section "Delayed Caching for Decoded Tokens")
+ * where each activated expert serves few tokens (Section "Speculative Exploration for Hot Tokens"), so the
+ * cost of a call is the bytes of the experts that receive at least one token; experts outside E_A, and
+ * experts of E_A no token selects, are never read.
+ *
+ * Conventions for every entry point
+ *   - `cfg` and `bytes` are HOST pointers.  Every other pointer is a DEVICE pointer owned by the caller
+ *     (hipMalloc / PyTorch-ROCm storage), 16-byte aligned.  The library never allocates, frees or keeps
+ *     them.  Scratch comes from the caller's `workspace` (>= team_moe_workspace_size bytes, 256-B aligned).
+ *   - `stream` is a hipStream_t (NULL = default stream).  Calls only enqueue kernels and return; there is no
+ *     host synchronisation and no host read of device data.
+ *   - Tensors are row-major and dense.  x [T,H], w_router [E,H], w_gate and w_up [E,I,H], w_down [E,H,I],
+ *     y [T,H]: all in cfg->dtype (TEAM_BF16: bfloat16 bit patterns; TEAM_F32: float).  Accumulation, router
+ *     logits, gates and expert_out are always float.
+ *   - Return value is a team_status.  Arguments are validated on the host before anything is launched:
+ *     NULL required pointer, T < 1, T > cfg->max_tokens, sizes out of range -> TEAM_ERR_INVALID_ARG;
+ *     shapes the kernels do not tile -> TEAM_ERR_UNSUPPORTED; workspace too small -> TEAM_ERR_WORKSPACE;
+ *     a launch the runtime rejects -> TEAM_ERR_HIP.  On error nothing has been enqueued.
+ *   - Results are deterministic: same inputs give bit-identical outputs (no floating-point atomics).
+ *   - Calls that share a workspace must be ordered on one stream (or otherwise serialised).
+ *
+ * Limits: 1 <= top_k <= 16, top_k <= num_experts <= 256, max_tokens <= 1024.
+ *   TEAM_BF16: hidden in {256,512,1024,2048}, inter a multiple of 128 with inter <= 1024.
+ *   TEAM_F32 : hidden and inter multiples of 4.
+ */
+#ifndef TEAM_MOE_H
+#define TEAM_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TEAM_OK = 0,
+    TEAM_ERR_INVALID_ARG = -1,
+    TEAM_ERR_UNSUPPORTED = -2,
+    TEAM_ERR_WORKSPACE = -3,
+    TEAM_ERR_HIP = -4
+} team_status;
+
+typedef enum { TEAM_F32 = 0, TEAM_BF16 = 1 } team_dtype;
+
+typedef struct {
+    int32_t hidden;       /* H */
+    int32_t inter;        /* I, SwiGLU intermediate size of one expert */
+    int32_t num_experts;  /* E = |E_0| */
+    int32_t top_k;        /* k, experts per token */
+    int32_t dtype;        /* team_dtype of x, weights and y */
+    int32_t renormalize;  /* 1: gates = softmax over the selected logits (sum to 1);
+                             0: gates = the selected entries of the softmax over all E experts */
+    int32_t max_tokens;   /* largest T any call with this cfg will pass (sizes the workspace) */
+    int32_t reserved;     /* must be 0 */
+} team_moe_config;
+
+/* Bytes of workspace that team_moe_layer_forward (and every other entry point) needs for `cfg`. */
+int team_moe_workspace_size(const team_moe_config* cfg, size_t* bytes);
+
+/*
+ * Router restricted to the activated-expert set (Algorithm 1, "Router(C, E_A)"; with expert_mask == NULL it
+ * is the first-round router over all experts E_0).
+ *   logit[t,e] = sum_h x[t,h] * w_router[e,h]               (float accumulation)
+ *   S = { e : expert_mask == NULL or expert_mask[e] != 0 },  k_eff = min(top_k, |S|)
+ *   topk_idx[t, 0..k_eff)  = the k_eff experts of S with the largest logit, largest first, ties to the lower
+ *                            id; remaining slots are -1
+ *   topk_gate[t, s]        = routing weight of slot s (see cfg->renormalize); 0 in padded slots
+ *   logits_out [T,E]       = optional copy of the logits (NULL to skip)
+ * An all-zero mask gives topk_idx = -1 and gates 0 everywhere.
+ */
+int team_moe_route(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router,
+                   const uint8_t* expert_mask /* [E] bytes or NULL */, int32_t* topk_idx /* [T,k] */,
+                   float* topk_gate /* [T,k] */, float* logits_out /* [T,E] or NULL */, void* stream);
+
+/*
+ * Token-to-expert grouping of the routing table (the paper leaves this implicit: "each activated expert is
+ * typically responsible for only a small number of tokens", Section "Speculative Exploration for Hot
+ * Tokens").  Integer only, bit-exact.
+ *   expert_offsets[E+1]  exclusive prefix sum of the number of (token,slot) pairs assigned to each expert
+ *   sorted_token[T*k]    token id of every row, rows of one expert contiguous and in ascending token id;
+ *                        entries beyond expert_offsets[E] are -1
+ *   inv_pos[T,k]         row of pair (t,s) in that order, -1 for padded slots
+ *   active_experts[E]    ids of the experts with at least one row, ascending, padded with -1
+ *   n_active[1]          their number
+ * Entries of topk_idx outside [0,E) are treated as padding.  `workspace` is not used (may be NULL).
+ */
+int team_moe_build_dispatch(const team_moe_config* cfg, const int32_t* topk_idx, int32_t T,
+                            int32_t* expert_offsets, int32_t* sorted_token, int32_t* inv_pos,
+                            int32_t* active_experts, int32_t* n_active, void* workspace, size_t ws_bytes,
+                            void* stream);
+
+/*
+ * Grouped SwiGLU expert FFN over the experts listed in active_experts only.
+ * For every row p in [expert_offsets[e], expert_offsets[e+1]) of an active expert e, with t = sorted_token[p]:
+ *   g = w_gate[e] x[t],  u = w_up[e] x[t],  h = silu(g) * u  (silu(z) = z / (1 + exp(-z))),
+ *   expert_out[p,:] = w_down[e] h                              (float, [T*k, H]; rows >= expert_offsets[E]
+ *                                                               are left untouched)
+ * TEAM_BF16: products on bf16 MFMA with float accumulation; h is rounded to bf16 between the two GEMMs.
+ * Weights of experts that are not listed are not read.
+ */
+int team_moe_expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, const int32_t* expert_offsets,
+                        const int32_t* sorted_token, const int32_t* active_experts, const int32_t* n_active,
+                        const void* w_gate, const void* w_up, const void* w_down, float* expert_out,
+                        void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * Gate-weighted combine: y[t,:] = sum_{s ascending, inv_pos[t,s] >= 0} topk_gate[t,s] * expert_out[inv_pos[t,s],:]
+ * in float, then cast to cfg->dtype (round to nearest even).  Tokens with no valid slot get y = 0.
+ */
+int team_moe_combine(const team_moe_config* cfg, const float* expert_out, const float* topk_gate,
+                     const int32_t* inv_pos, int32_t T, void* y, void* stream);
+
+/*
+ * The whole layer on one stream: route -> build_dispatch -> expert_ffn -> combine, all intermediates in
+ * `workspace`.  y [T,H] in cfg->dtype.
+ */
+int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router,
+                           const void* w_gate, const void* w_up, const void* w_down,
+                           const uint8_t* expert_mask, void* y, void* workspace, size_t ws_bytes, void* stream);
+
+/* Static, NUL-terminated description of a team_status value. */
+const char* team_moe_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TEAM_MOE_H */

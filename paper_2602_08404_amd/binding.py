@@ -1,0 +1,120 @@
+"""Thin ctypes binding of libteam_moe.so (include/team_moe.h).
+
+Argument marshalling only: every function takes PyTorch-ROCm device tensors (used purely as device memory),
+passes their pointers and the current HIP stream to the C entry point of the same name, and raises on a
+non-zero status.  There is no Python or PyTorch fallback: if the library is missing, import of this module's
+``lib()`` fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libteam_moe.so")
+
+TEAM_F32, TEAM_BF16 = 0, 1
+STATUS_OK = 0
+
+EXPORTS = ["team_moe_workspace_size", "team_moe_route", "team_moe_build_dispatch", "team_moe_expert_ffn",
+           "team_moe_combine", "team_moe_layer_forward", "team_moe_status_string"]
+
+
+class TeamMoeError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: status {status} ({status_string(status)})")
+        self.status = status
+
+
+class Config(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("inter", C.c_int32), ("num_experts", C.c_int32), ("top_k", C.c_int32),
+                ("dtype", C.c_int32), ("renormalize", C.c_int32), ("max_tokens", C.c_int32), ("reserved", C.c_int32)]
+
+
+def make_config(hidden: int, inter: int, num_experts: int, top_k: int, dtype: str, renormalize: int = 1,
+                max_tokens: int = 256) -> Config:
+    return Config(hidden, inter, num_experts, top_k, {"f32": TEAM_F32, "bf16": TEAM_BF16}[dtype], renormalize, max_tokens, 0)
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2602_08404_amd.build` "
+                              "(there is no fallback implementation)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+        cfgp = C.POINTER(Config)
+        L.team_moe_workspace_size.argtypes = [cfgp, C.POINTER(sz)]
+        L.team_moe_route.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp]
+        L.team_moe_build_dispatch.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.team_moe_expert_ffn.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.team_moe_combine.argtypes = [cfgp, vp, vp, vp, i32, vp, vp]
+        L.team_moe_layer_forward.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.team_moe_status_string.argtypes = [C.c_int]
+        L.team_moe_status_string.restype = C.c_char_p
+        for name in EXPORTS[:-1]:
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().team_moe_status_string(int(status)).decode()
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status: int, what: str) -> None:
+    if status != STATUS_OK:
+        raise TeamMoeError(status, what)
+
+
+def team_moe_workspace_size(cfg: Config) -> int:
+    n = C.c_size_t(0)
+    _check(lib().team_moe_workspace_size(C.byref(cfg), C.byref(n)), "team_moe_workspace_size")
+    return int(n.value)
+
+
+def team_moe_route(cfg: Config, x, T: int, w_router, expert_mask, topk_idx, topk_gate, logits_out=None, stream=None) -> None:
+    _check(lib().team_moe_route(C.byref(cfg), _ptr(x), T, _ptr(w_router), _ptr(expert_mask), _ptr(topk_idx), _ptr(topk_gate),
+                                _ptr(logits_out), stream if stream is not None else _stream()), "team_moe_route")
+
+
+def team_moe_build_dispatch(cfg: Config, topk_idx, T: int, expert_offsets, sorted_token, inv_pos, active_experts, n_active,
+                            workspace=None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().team_moe_build_dispatch(C.byref(cfg), _ptr(topk_idx), T, _ptr(expert_offsets), _ptr(sorted_token), _ptr(inv_pos),
+                                         _ptr(active_experts), _ptr(n_active), _ptr(workspace), ws_bytes,
+                                         stream if stream is not None else _stream()), "team_moe_build_dispatch")
+
+
+def team_moe_expert_ffn(cfg: Config, x, T: int, expert_offsets, sorted_token, active_experts, n_active, w_gate, w_up, w_down,
+                        expert_out, workspace, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().team_moe_expert_ffn(C.byref(cfg), _ptr(x), T, _ptr(expert_offsets), _ptr(sorted_token), _ptr(active_experts),
+                                     _ptr(n_active), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(expert_out), _ptr(workspace),
+                                     ws_bytes, stream if stream is not None else _stream()), "team_moe_expert_ffn")
+
+
+def team_moe_combine(cfg: Config, expert_out, topk_gate, inv_pos, T: int, y, stream=None) -> None:
+    _check(lib().team_moe_combine(C.byref(cfg), _ptr(expert_out), _ptr(topk_gate), _ptr(inv_pos), T, _ptr(y),
+                                  stream if stream is not None else _stream()), "team_moe_combine")
+
+
+def team_moe_layer_forward(cfg: Config, x, T: int, w_router, w_gate, w_up, w_down, expert_mask, y, workspace, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().team_moe_layer_forward(C.byref(cfg), _ptr(x), T, _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+                                        _ptr(expert_mask), _ptr(y), _ptr(workspace), ws_bytes,
+                                        stream if stream is not None else _stream()), "team_moe_layer_forward")

@@ -1,0 +1,195 @@
+// C-ABI boundary of the MoE layer (declared in include/team_moe.h): argument validation on the host,
+// workspace carving, and kernel launches on the caller's stream.  No allocation, no synchronisation.
+#include "../../include/team_moe.h"
+
+#include "kernels.hpp"
+
+#include <stdio.h>
+#include <stdlib.h>
+
+namespace {
+
+using team::Dims;
+
+constexpr int MAX_TOKENS = 1024;
+constexpr int MAX_EXPERTS = 256;
+constexpr int MAX_TOPK = 16;
+
+inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_cfg(const team_moe_config* c) {
+    if (!c) return TEAM_ERR_INVALID_ARG;
+    if (c->dtype != TEAM_F32 && c->dtype != TEAM_BF16) return TEAM_ERR_INVALID_ARG;
+    if (c->reserved != 0) return TEAM_ERR_INVALID_ARG;
+    if (c->renormalize != 0 && c->renormalize != 1) return TEAM_ERR_INVALID_ARG;
+    if (c->hidden < 1 || c->inter < 1 || c->num_experts < 1 || c->top_k < 1 || c->max_tokens < 1) return TEAM_ERR_INVALID_ARG;
+    if (c->top_k > c->num_experts) return TEAM_ERR_INVALID_ARG;
+    if (c->top_k > MAX_TOPK || c->num_experts > MAX_EXPERTS || c->max_tokens > MAX_TOKENS) return TEAM_ERR_UNSUPPORTED;
+    if (c->dtype == TEAM_BF16) {
+        if (!team::ffn_bf16_supported(c->hidden, c->inter)) return TEAM_ERR_UNSUPPORTED;
+    } else {
+        if (c->hidden % 4 != 0 || c->inter % 4 != 0) return TEAM_ERR_UNSUPPORTED;
+    }
+    return TEAM_OK;
+}
+
+int check_T(const team_moe_config* c, int32_t T) { return (T < 1 || T > c->max_tokens) ? TEAM_ERR_INVALID_ARG : TEAM_OK; }
+
+Dims dims_of(const team_moe_config* c, int32_t T) {
+    Dims d;
+    d.T = T; d.H = c->hidden; d.I = c->inter; d.E = c->num_experts; d.k = c->top_k;
+    d.bf16 = c->dtype == TEAM_BF16;
+    d.renormalize = c->renormalize;
+    return d;
+}
+
+// Workspace layout, sized for max_tokens.  The expert FFN's scratch (h) comes first so that
+// team_moe_expert_ffn and team_moe_layer_forward agree on where it is.
+struct Layout {
+    size_t h, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, total;
+};
+Layout layout_of(const team_moe_config* c) {
+    const size_t A = (size_t)c->max_tokens * c->top_k;
+    const size_t elem = c->dtype == TEAM_BF16 ? 2 : 4;
+    Layout L;
+    size_t off = 0;
+    L.h = off;            off += align256(A * c->inter * elem);
+    L.topk_idx = off;     off += align256(A * 4);
+    L.topk_gate = off;    off += align256(A * 4);
+    L.offsets = off;      off += align256(((size_t)c->num_experts + 1) * 4);
+    L.sorted_token = off; off += align256(A * 4);
+    L.inv_pos = off;      off += align256(A * 4);
+    L.active = off;       off += align256((size_t)c->num_experts * 4);
+    L.n_active = off;     off += 256;
+    L.expert_out = off;   off += align256(A * c->hidden * 4);
+    L.total = off;
+    return L;
+}
+
+// Launch errors are read with hipGetLastError(), which also reports errors left behind by earlier, unrelated
+// runtime calls of the process; every entry point clears that state before its first launch.
+inline void clear_stale_error() { (void)hipGetLastError(); }
+inline int hip_status(hipError_t e) {
+    if (e == hipSuccess) return TEAM_OK;
+    if (getenv("TEAM_MOE_DEBUG")) fprintf(stderr, "team_moe: HIP error %d (%s)\n", (int)e, hipGetErrorString(e));
+    return TEAM_ERR_HIP;
+}
+
+int run_ffn(const team_moe_config* cfg, const Dims& d, const void* x, const int32_t* offsets, const int32_t* sorted_token,
+            const int32_t* active, const int32_t* n_active, const void* wg, const void* wu, const void* wd, float* expert_out,
+            void* h_ws, hipStream_t s) {
+    if (cfg->dtype == TEAM_BF16)
+        return hip_status(team::launch_ffn_bf16(d, (const uint16_t*)x, offsets, sorted_token, active, n_active, (const uint16_t*)wg,
+                                                (const uint16_t*)wu, (const uint16_t*)wd, (uint16_t*)h_ws, expert_out, s));
+    return hip_status(team::launch_ffn_f32(d, (const float*)x, offsets, sorted_token, active, n_active, (const float*)wg,
+                                           (const float*)wu, (const float*)wd, (float*)h_ws, expert_out, s));
+}
+
+}  // namespace
+
+extern "C" {
+
+int team_moe_workspace_size(const team_moe_config* cfg, size_t* bytes) {
+    if (!bytes) return TEAM_ERR_INVALID_ARG;
+    int st = check_cfg(cfg);
+    if (st != TEAM_OK) return st;
+    *bytes = layout_of(cfg).total;
+    return TEAM_OK;
+}
+
+int team_moe_route(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const uint8_t* expert_mask,
+                   int32_t* topk_idx, float* topk_gate, float* logits_out, void* stream) {
+    int st = check_cfg(cfg);
+    if (st != TEAM_OK) return st;
+    if ((st = check_T(cfg, T)) != TEAM_OK) return st;
+    if (!x || !w_router || !topk_idx || !topk_gate) return TEAM_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(w_router)) return TEAM_ERR_INVALID_ARG;
+    if (cfg->hidden % (cfg->dtype == TEAM_BF16 ? 8 : 4) != 0) return TEAM_ERR_UNSUPPORTED;
+    clear_stale_error();
+    return hip_status(team::launch_route(dims_of(cfg, T), x, w_router, expert_mask, topk_idx, topk_gate, logits_out, (hipStream_t)stream));
+}
+
+int team_moe_build_dispatch(const team_moe_config* cfg, const int32_t* topk_idx, int32_t T, int32_t* expert_offsets,
+                            int32_t* sorted_token, int32_t* inv_pos, int32_t* active_experts, int32_t* n_active, void* workspace,
+                            size_t ws_bytes, void* stream) {
+    (void)workspace; (void)ws_bytes;
+    int st = check_cfg(cfg);
+    if (st != TEAM_OK) return st;
+    if ((st = check_T(cfg, T)) != TEAM_OK) return st;
+    if (!topk_idx || !expert_offsets || !sorted_token || !inv_pos || !active_experts || !n_active) return TEAM_ERR_INVALID_ARG;
+    clear_stale_error();
+    return hip_status(team::launch_dispatch(dims_of(cfg, T), topk_idx, expert_offsets, sorted_token, inv_pos, active_experts, n_active,
+                                            (hipStream_t)stream));
+}
+
+int team_moe_expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, const int32_t* expert_offsets,
+                        const int32_t* sorted_token, const int32_t* active_experts, const int32_t* n_active, const void* w_gate,
+                        const void* w_up, const void* w_down, float* expert_out, void* workspace, size_t ws_bytes, void* stream) {
+    int st = check_cfg(cfg);
+    if (st != TEAM_OK) return st;
+    if ((st = check_T(cfg, T)) != TEAM_OK) return st;
+    if (!x || !expert_offsets || !sorted_token || !active_experts || !n_active || !w_gate || !w_up || !w_down || !expert_out)
+        return TEAM_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) || !aligned16(expert_out))
+        return TEAM_ERR_INVALID_ARG;
+    const Layout L = layout_of(cfg);
+    if (!workspace || !aligned16(workspace) || ws_bytes < L.topk_idx /* = size of the h segment */) return TEAM_ERR_WORKSPACE;
+    clear_stale_error();
+    return run_ffn(cfg, dims_of(cfg, T), x, expert_offsets, sorted_token, active_experts, n_active, w_gate, w_up, w_down, expert_out,
+                   (char*)workspace + L.h, (hipStream_t)stream);
+}
+
+int team_moe_combine(const team_moe_config* cfg, const float* expert_out, const float* topk_gate, const int32_t* inv_pos, int32_t T,
+                     void* y, void* stream) {
+    int st = check_cfg(cfg);
+    if (st != TEAM_OK) return st;
+    if ((st = check_T(cfg, T)) != TEAM_OK) return st;
+    if (!expert_out || !topk_gate || !inv_pos || !y) return TEAM_ERR_INVALID_ARG;
+    if (!aligned16(expert_out) || !aligned16(y)) return TEAM_ERR_INVALID_ARG;
+    clear_stale_error();
+    return hip_status(team::launch_combine(dims_of(cfg, T), expert_out, topk_gate, inv_pos, y, (hipStream_t)stream));
+}
+
+int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const void* w_gate,
+                           const void* w_up, const void* w_down, const uint8_t* expert_mask, void* y, void* workspace,
+                           size_t ws_bytes, void* stream) {
+    int st = check_cfg(cfg);
+    if (st != TEAM_OK) return st;
+    if ((st = check_T(cfg, T)) != TEAM_OK) return st;
+    if (!x || !w_router || !w_gate || !w_up || !w_down || !y) return TEAM_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(w_router) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) || !aligned16(y))
+        return TEAM_ERR_INVALID_ARG;
+    const Layout L = layout_of(cfg);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || ws_bytes < L.total) return TEAM_ERR_WORKSPACE;
+    char* ws = (char*)workspace;
+    int32_t* topk_idx = (int32_t*)(ws + L.topk_idx);
+    float* topk_gate = (float*)(ws + L.topk_gate);
+    int32_t* offsets = (int32_t*)(ws + L.offsets);
+    int32_t* sorted_token = (int32_t*)(ws + L.sorted_token);
+    int32_t* inv_pos = (int32_t*)(ws + L.inv_pos);
+    int32_t* active = (int32_t*)(ws + L.active);
+    int32_t* n_active = (int32_t*)(ws + L.n_active);
+    float* expert_out = (float*)(ws + L.expert_out);
+    const Dims d = dims_of(cfg, T);
+    hipStream_t s = (hipStream_t)stream;
+    clear_stale_error();
+    if ((st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, nullptr, s))) != TEAM_OK) return st;
+    if ((st = hip_status(team::launch_dispatch(d, topk_idx, offsets, sorted_token, inv_pos, active, n_active, s))) != TEAM_OK) return st;
+    if ((st = run_ffn(cfg, d, x, offsets, sorted_token, active, n_active, w_gate, w_up, w_down, expert_out, ws + L.h, s)) != TEAM_OK)
+        return st;
+    return hip_status(team::launch_combine(d, expert_out, topk_gate, inv_pos, y, s));
+}
+
+const char* team_moe_status_string(int status) {
+    switch (status) {
+        case TEAM_OK: return "ok";
+        case TEAM_ERR_INVALID_ARG: return "invalid argument";
+        case TEAM_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+        case TEAM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case TEAM_ERR_HIP: return "HIP runtime rejected a launch";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

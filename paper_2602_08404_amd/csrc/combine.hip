@@ -1,0 +1,44 @@
+// Gate-weighted combine of the expert outputs: y[t,:] = sum_s gate[t,s] * expert_out[inv_pos[t,s],:].
+// These gates are the routing weights W that Algorithm 1 returns.  Slots are summed in ascending order in
+// float by one thread per output element group, so the result does not depend on scheduling.
+#include "device_utils.hpp"
+#include "kernels.hpp"
+
+namespace team {
+
+constexpr int COMBINE_THREADS = 256;
+
+template <bool BF16>
+__global__ __launch_bounds__(COMBINE_THREADS) void combine_kernel(const float* __restrict__ expert_out, const float* __restrict__ gate,
+                                                                  const int32_t* __restrict__ inv_pos, void* __restrict__ y, int H, int k) {
+    const int t = blockIdx.y;
+    const int h4 = (blockIdx.x * COMBINE_THREADS + threadIdx.x) * 4;
+    if (h4 >= H) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < k; ++s) {
+        int p = inv_pos[(size_t)t * k + s];
+        if (p < 0) continue;
+        float g = gate[(size_t)t * k + s];
+        float4 o = *reinterpret_cast<const float4*>(expert_out + (size_t)p * H + h4);
+        acc.x = fmaf(g, o.x, acc.x); acc.y = fmaf(g, o.y, acc.y); acc.z = fmaf(g, o.z, acc.z); acc.w = fmaf(g, o.w, acc.w);
+    }
+    if (BF16) {
+        uint2 packed;
+        packed.x = f32_to_bf16_bits(acc.x) | (f32_to_bf16_bits(acc.y) << 16);
+        packed.y = f32_to_bf16_bits(acc.z) | (f32_to_bf16_bits(acc.w) << 16);
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(y) + (size_t)t * H + h4) = packed;
+    } else {
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(y) + (size_t)t * H + h4) = acc;
+    }
+}
+
+hipError_t launch_combine(const Dims& d, const float* expert_out, const float* gate, const int32_t* inv_pos, void* y, hipStream_t s) {
+    dim3 grid((d.H / 4 + COMBINE_THREADS - 1) / COMBINE_THREADS, d.T), block(COMBINE_THREADS);
+    if (d.bf16)
+        hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, s, expert_out, gate, inv_pos, y, d.H, d.k);
+    else
+        hipLaunchKernelGGL(combine_kernel<false>, grid, block, 0, s, expert_out, gate, inv_pos, y, d.H, d.k);
+    return hipGetLastError();
+}
+
+}  // namespace team

@@ -1,0 +1,31 @@
+// Host-side launchers of the MoE-layer kernels (internal; the public boundary is include/team_moe.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace team {
+
+struct Dims {
+    int T, H, I, E, k;
+    int bf16;          // 1: bf16 storage, 0: float storage
+    int renormalize;
+};
+
+hipError_t launch_route(const Dims& d, const void* x, const void* w_router, const uint8_t* mask, int32_t* topk_idx,
+                        float* topk_gate, float* logits_out, hipStream_t s);
+hipError_t launch_dispatch(const Dims& d, const int32_t* topk_idx, int32_t* offsets, int32_t* sorted_token,
+                           int32_t* inv_pos, int32_t* active, int32_t* n_active, hipStream_t s);
+hipError_t launch_combine(const Dims& d, const float* expert_out, const float* gate, const int32_t* inv_pos, void* y,
+                          hipStream_t s);
+// fp32 storage: plain-ALU grouped FFN.
+hipError_t launch_ffn_f32(const Dims& d, const float* x, const int32_t* offsets, const int32_t* sorted_token,
+                          const int32_t* active, const int32_t* n_active, const float* wg, const float* wu,
+                          const float* wd, float* h_ws, float* expert_out, hipStream_t s);
+// bf16 storage: MFMA grouped FFN streaming the weights of the active experts.
+bool ffn_bf16_supported(int H, int I);
+hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offsets, const int32_t* sorted_token,
+                           const int32_t* active, const int32_t* n_active, const uint16_t* wg, const uint16_t* wu,
+                           const uint16_t* wd, uint16_t* h_ws, float* expert_out, hipStream_t s);
+
+}  // namespace team

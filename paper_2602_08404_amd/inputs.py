@@ -89,7 +89,9 @@ def bf16_round(a: np.ndarray) -> np.ndarray:
 
 def bf16_widen(bits: np.ndarray) -> np.ndarray:
     """bfloat16 bit patterns (uint16) -> the exactly equal fp32 values."""
-    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    out = np.zeros(bits.shape, np.uint32)
+    out.view(np.uint16).reshape(bits.shape + (2,))[..., 1] = bits      # little-endian: high half-word
+    return out.view(np.float32)
 
 
 def store(a: np.ndarray, dtype: str) -> np.ndarray:

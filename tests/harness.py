@@ -1,0 +1,239 @@
+"""Shared helpers of the GPU parity tests: upload seeded inputs, call the C-ABI through the binding, and compare
+with the CPU oracle under the documented bars.
+
+Bars (stated here, used by every parity test):
+  * integer outputs (dispatch tables) are bit-exact;
+  * top-k indices are bit-exact for every token whose oracle gap between the k-th and (k+1)-th allowed logit
+    exceeds GAP = 1e-4 (compared as sets; as ordered lists when all adjacent gaps among the top k+1 exceed GAP);
+  * floating-point outputs: per row, max|gpu - ref| / max|ref| <= 2e-2 for bf16 storage, 1e-5 for fp32 storage;
+  * tokens inside the gap band are checked against the oracle's FFN + combine run on the GPU's own selection.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+import paper_2602_08404_amd as tm
+from oracle import c_oracle as orc
+from paper_2602_08404_amd import inputs as gen
+
+GAP = 1e-4
+TOL = {"bf16": 2e-2, "f32": 1e-5}
+DEV = "cuda:0"
+
+
+def to_dev(a: Optional[np.ndarray]):
+    """Host array in storage dtype -> device tensor (uint16 bit patterns become torch.bfloat16)."""
+    if a is None:
+        return None
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def y_to_host(y: torch.Tensor) -> np.ndarray:
+    return y.float().cpu().numpy().astype(np.float64)
+
+
+@dataclass
+class Case:
+    shape: gen.MoEShape
+    x: np.ndarray                 # storage dtype
+    w: Dict[str, np.ndarray]      # storage dtype
+    xf: np.ndarray                # fp32 views for the oracle
+    wf: Dict[str, np.ndarray]
+    d_x: torch.Tensor
+    d_w: Dict[str, torch.Tensor]
+    cfg: tm.Config
+
+    @staticmethod
+    def make(shape: gen.MoEShape, x: np.ndarray, w: Dict[str, np.ndarray], wf=None, d_w=None, max_tokens=None) -> "Case":
+        wf = wf or {n: gen.as_f32(a) for n, a in w.items()}
+        d_w = d_w or {n: to_dev(a) for n, a in w.items()}
+        cfg = tm.make_config(shape.H, shape.I, shape.E, shape.k, shape.dtype, shape.renormalize, max_tokens or shape.T)
+        return Case(shape, x, w, gen.as_f32(x), wf, to_dev(x), d_w, cfg)
+
+    def with_x(self, shape: gen.MoEShape, x: np.ndarray) -> "Case":
+        return Case.make(shape, x, self.w, self.wf, self.d_w)
+
+
+def out_dtype(shape):
+    return torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+
+
+# ----------------------------------------------------------------------------- GPU calls
+def gpu_route(case: Case, mask: Optional[np.ndarray], want_logits=True):
+    s = case.shape
+    idx = torch.full((s.T, s.k), -7, dtype=torch.int32, device=DEV)
+    gate = torch.full((s.T, s.k), -7.0, dtype=torch.float32, device=DEV)
+    logits = torch.empty((s.T, s.E), dtype=torch.float32, device=DEV) if want_logits else None
+    d_mask = None if mask is None else torch.from_numpy(mask).to(DEV)
+    tm.team_moe_route(case.cfg, case.d_x, s.T, case.d_w["router"], d_mask, idx, gate, logits)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), gate.cpu().numpy(), (logits.cpu().numpy() if want_logits else None)
+
+
+def gpu_dispatch(case: Case, idx: np.ndarray):
+    s = case.shape
+    A = s.T * s.k
+    d_idx = torch.from_numpy(np.ascontiguousarray(idx, np.int32)).to(DEV)
+    offsets = torch.full((s.E + 1,), -7, dtype=torch.int32, device=DEV)
+    sorted_token = torch.full((A,), -7, dtype=torch.int32, device=DEV)
+    inv_pos = torch.full((s.T, s.k), -7, dtype=torch.int32, device=DEV)
+    active = torch.full((s.E,), -7, dtype=torch.int32, device=DEV)
+    n_active = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+    tm.team_moe_build_dispatch(case.cfg, d_idx, s.T, offsets, sorted_token, inv_pos, active, n_active)
+    torch.cuda.synchronize()
+    return (offsets.cpu().numpy(), sorted_token.cpu().numpy(), inv_pos.cpu().numpy(), active.cpu().numpy(),
+            int(n_active.cpu().numpy()[0]))
+
+
+def gpu_expert_ffn(case: Case, offsets, sorted_token, active, n_active):
+    s = case.shape
+    A = s.T * s.k
+    ws = torch.empty(tm.team_moe_workspace_size(case.cfg), dtype=torch.uint8, device=DEV)
+    out = torch.full((A, s.H), float("nan"), dtype=torch.float32, device=DEV)
+    tm.team_moe_expert_ffn(case.cfg, case.d_x, s.T, torch.from_numpy(offsets).to(DEV), torch.from_numpy(sorted_token).to(DEV),
+                           torch.from_numpy(active).to(DEV), torch.tensor([n_active], dtype=torch.int32, device=DEV),
+                           case.d_w["gate"], case.d_w["up"], case.d_w["down"], out, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def gpu_combine(case: Case, expert_out: np.ndarray, gate: np.ndarray, inv_pos: np.ndarray):
+    s = case.shape
+    y = torch.empty((s.T, s.H), dtype=out_dtype(s), device=DEV)
+    tm.team_moe_combine(case.cfg, torch.from_numpy(np.ascontiguousarray(expert_out, np.float32)).to(DEV),
+                        torch.from_numpy(np.ascontiguousarray(gate, np.float32)).to(DEV),
+                        torch.from_numpy(np.ascontiguousarray(inv_pos, np.int32)).to(DEV), s.T, y)
+    torch.cuda.synchronize()
+    return y_to_host(y)
+
+
+def gpu_layer(case: Case, mask: Optional[np.ndarray], ws=None) -> np.ndarray:
+    s = case.shape
+    if ws is None:
+        ws = torch.empty(tm.team_moe_workspace_size(case.cfg), dtype=torch.uint8, device=DEV)
+    y = torch.empty((s.T, s.H), dtype=out_dtype(s), device=DEV)
+    d_mask = None if mask is None else torch.from_numpy(mask).to(DEV)
+    tm.team_moe_layer_forward(case.cfg, case.d_x, s.T, case.d_w["router"], case.d_w["gate"], case.d_w["up"], case.d_w["down"],
+                              d_mask, y, ws)
+    torch.cuda.synchronize()
+    return y_to_host(y), y
+
+
+# ----------------------------------------------------------------------------- oracle side
+def oracle_layer(case: Case, mask, threads=0):
+    s = case.shape
+    return orc.moe_layer(case.xf, case.wf["router"], case.wf["gate"], case.wf["up"], case.wf["down"], s.k, s.renormalize, mask,
+                         threads=threads)
+
+
+def oracle_logits(case: Case):
+    return orc.router_logits(case.xf, case.wf["router"])
+
+
+def safe_tokens(logits: np.ndarray, mask: Optional[np.ndarray], k: int):
+    """Per token: (set_safe, order_safe) from the oracle's allowed logits.
+    set_safe: gap between the k-th and (k+1)-th allowed logit > GAP (or fewer than k+1 allowed experts).
+    order_safe: all adjacent gaps among the top min(k+1, |S|) allowed logits > GAP."""
+    T, E = logits.shape
+    allowed = np.ones(E, bool) if mask is None else mask != 0
+    z = np.sort(logits[:, allowed].astype(np.float64), axis=1)[:, ::-1]
+    n = z.shape[1]
+    k_eff = min(k, n)
+    if n == 0:
+        return np.ones(T, bool), np.ones(T, bool)
+    top = z[:, :min(k_eff + 1, n)]
+    gaps = top[:, :-1] - top[:, 1:] if top.shape[1] > 1 else np.full((T, 1), np.inf)
+    set_safe = np.ones(T, bool) if n <= k_eff else (z[:, k_eff - 1] - z[:, k_eff]) > GAP
+    order_safe = (gaps > GAP).all(axis=1)
+    return set_safe, order_safe & set_safe
+
+
+def row_rel_err(got: np.ndarray, ref: np.ndarray) -> np.ndarray:
+    """Per row: max|got-ref| / max|ref| (rows whose reference is all zero must match exactly -> 0 or inf)."""
+    num = np.abs(got - ref).max(axis=1)
+    den = np.abs(ref).max(axis=1)
+    out = np.where(den > 0, num / np.where(den > 0, den, 1.0), np.where(num == 0, 0.0, np.inf))
+    return out
+
+
+def check_route(case: Case, mask, g_idx, g_gate, g_logits, o_idx, o_gate, o_logits):
+    s = case.shape
+    set_safe, order_safe = safe_tokens(o_logits, mask, s.k)
+    if g_logits is not None:
+        assert np.abs(g_logits.astype(np.float64) - o_logits).max() <= 2e-5 * max(1.0, np.abs(o_logits).max())
+    for t in range(s.T):
+        if order_safe[t]:
+            assert g_idx[t].tolist() == o_idx[t].tolist(), (t, g_idx[t], o_idx[t])
+            assert np.abs(g_gate[t] - o_gate[t]).max() <= 2e-6, (t, g_gate[t], o_gate[t])
+        elif set_safe[t]:
+            assert sorted(g_idx[t].tolist()) == sorted(o_idx[t].tolist()), (t, g_idx[t], o_idx[t])
+    # properties that hold for every token, safe or not
+    allowed = np.ones(s.E, bool) if mask is None else mask != 0
+    k_eff = min(s.k, int(allowed.sum()))
+    assert (g_idx[:, k_eff:] == -1).all() and (g_gate[:, k_eff:] == 0).all()
+    if k_eff:
+        assert allowed[g_idx[:, :k_eff]].all()
+        assert all(len(set(r[:k_eff].tolist())) == k_eff for r in g_idx)
+        if s.renormalize:
+            assert np.abs(g_gate.sum(1) - 1.0).max() <= 1e-5
+    return set_safe, order_safe
+
+
+def check_layer(case: Case, mask, y_gpu: np.ndarray, g_idx, g_gate, o_y, o_idx, set_safe):
+    """Rows with the oracle's selection: compare with the oracle's y.  Rows in the gap band: compare with the
+    oracle's FFN + combine evaluated on the GPU's own selection and gates."""
+    s = case.shape
+    tol = TOL[s.dtype]
+    same = np.array([sorted(g_idx[t].tolist()) == sorted(o_idx[t].tolist()) for t in range(s.T)])
+    assert same[set_safe].all()
+    ref = o_y.copy()
+    if (~same).any():
+        rows = np.nonzero(~same)[0]
+        o = orc.expert_rows(case.xf[rows], case.wf["gate"], case.wf["up"], case.wf["down"], g_idx[rows])
+        ref[rows] = orc.combine(o, g_gate[rows].astype(np.float64), g_idx[rows])
+    err = row_rel_err(y_gpu, ref)
+    assert err.max() <= tol, (err.max(), int(err.argmax()))
+    return float(err.max()), int((~same).sum())
+
+
+def full_parity(case: Case, mask, threads=0):
+    """All five entry points against the oracle for one (inputs, mask). Returns a small report dict."""
+    s = case.shape
+    tol = TOL[s.dtype]
+    o_y, o_idx, o_gate = oracle_layer(case, mask, threads)
+    o_logits = oracle_logits(case)
+    # route
+    g_idx, g_gate, g_logits = gpu_route(case, mask)
+    set_safe, order_safe = check_route(case, mask, g_idx, g_gate, g_logits, o_idx, o_gate, o_logits)
+    # dispatch on the oracle's routing table: bit-exact
+    o_disp = orc.dispatch(o_idx, s.E)
+    g_disp = gpu_dispatch(case, o_idx)
+    for a, b, name in zip(g_disp, o_disp, ("offsets", "sorted_token", "inv_pos", "active", "n_active")):
+        assert np.array_equal(np.asarray(a), np.asarray(b)), name
+    # expert FFN on the oracle's tables
+    offsets, sorted_token, inv_pos, active, n_active = o_disp
+    g_out = gpu_expert_ffn(case, offsets, sorted_token, active, n_active)
+    o_rows = orc.expert_rows(case.xf, case.wf["gate"], case.wf["up"], case.wf["down"], o_idx, threads)     # [T,k,H]
+    valid = inv_pos >= 0
+    ref_out = np.zeros((s.T * s.k, s.H))
+    ref_out[inv_pos[valid]] = o_rows[valid]
+    n_rows = int(offsets[s.E])
+    ffn_err = row_rel_err(g_out[:n_rows].astype(np.float64), ref_out[:n_rows]).max() if n_rows else 0.0
+    assert ffn_err <= tol, ffn_err
+    assert np.isnan(g_out[n_rows:]).all()                      # rows beyond the table are left untouched
+    # combine on the oracle's expert outputs (as float) and gates
+    y_c = gpu_combine(case, ref_out.astype(np.float32), o_gate.astype(np.float32), inv_pos)
+    ref_c = orc.combine(o_rows.astype(np.float32).astype(np.float64), o_gate.astype(np.float32).astype(np.float64), o_idx)
+    comb_tol = 2.0 ** -8 if s.dtype == "bf16" else 1e-6
+    assert row_rel_err(y_c, ref_c).max() <= comb_tol
+    # whole layer
+    y_gpu, _ = gpu_layer(case, mask)
+    layer_err, n_band = check_layer(case, mask, y_gpu, g_idx, g_gate, o_y, o_idx, set_safe)
+    return {"ffn_err": float(ffn_err), "layer_err": layer_err, "band_tokens": n_band, "unsafe": int((~set_safe).sum()),
+            "n_active": n_active}

@@ -1,0 +1,99 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments on the host
+(no GPU needed: validation happens before anything is launched)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2602_08404_amd as tm
+from paper_2602_08404_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "team_moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(team_moe_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.lib()
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    assert tm.status_string(0) == "ok"
+    for s in (-1, -2, -3, -4, 99):
+        assert isinstance(tm.status_string(s), str) and tm.status_string(s)
+
+
+def test_workspace_size_grows_with_tokens_and_covers_intermediates():
+    small = tm.team_moe_workspace_size(tm.make_config(2048, 768, 128, 8, "bf16", 1, 32))
+    big = tm.team_moe_workspace_size(tm.make_config(2048, 768, 128, 8, "bf16", 1, 128))
+    assert big > small
+    A = 32 * 8
+    assert small >= A * 768 * 2 + A * 2048 * 4 + 4 * A * 4 + 129 * 4 + 128 * 4 + 4
+    assert small % 256 == 0
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(hidden=2048, inter=768, num_experts=128, top_k=0), -1),
+    (dict(hidden=2048, inter=768, num_experts=4, top_k=8), -1),
+    (dict(hidden=2048, inter=768, num_experts=512, top_k=8), -2),
+    (dict(hidden=2048, inter=768, num_experts=128, top_k=32), -2),
+    (dict(hidden=2000, inter=768, num_experts=128, top_k=8), -2),
+    (dict(hidden=2048, inter=700, num_experts=128, top_k=8), -2),
+    (dict(hidden=2048, inter=768, num_experts=128, top_k=8, max_tokens=4096), -2),
+    (dict(hidden=2048, inter=768, num_experts=128, top_k=8, max_tokens=0), -1),
+])
+def test_bad_configs_are_rejected(kw, status):
+    kw = dict(dict(dtype="bf16", renormalize=1, max_tokens=32), **kw)
+    cfg = tm.make_config(**kw)
+    with pytest.raises(tm.TeamMoeError) as e:
+        tm.team_moe_workspace_size(cfg)
+    assert e.value.status == status
+
+
+def test_bad_call_arguments_are_rejected_before_any_launch():
+    lib = binding.lib()
+    cfg = tm.make_config(2048, 768, 128, 8, "bf16", 1, 32)
+    fake = C.c_void_p(0x1000)          # aligned, never dereferenced: every call below fails validation first
+    odd = C.c_void_p(0x1004)
+    st = 0
+    # NULL required pointers
+    assert lib.team_moe_route(C.byref(cfg), None, 8, fake, None, fake, fake, None, st) == -1
+    assert lib.team_moe_build_dispatch(C.byref(cfg), None, 8, fake, fake, fake, fake, fake, None, 0, st) == -1
+    assert lib.team_moe_combine(C.byref(cfg), fake, fake, None, 8, fake, st) == -1
+    assert lib.team_moe_expert_ffn(C.byref(cfg), fake, 8, fake, fake, fake, fake, fake, fake, None, fake, fake, 1 << 30, st) == -1
+    assert lib.team_moe_layer_forward(C.byref(cfg), fake, 8, fake, fake, fake, fake, None, None, fake, 1 << 30, st) == -1
+    # token count out of range
+    assert lib.team_moe_route(C.byref(cfg), fake, 0, fake, None, fake, fake, None, st) == -1
+    assert lib.team_moe_route(C.byref(cfg), fake, 33, fake, None, fake, fake, None, st) == -1
+    # misaligned tensor
+    assert lib.team_moe_route(C.byref(cfg), odd, 8, fake, None, fake, fake, None, st) == -1
+    # workspace missing / too small / misaligned
+    assert lib.team_moe_layer_forward(C.byref(cfg), fake, 8, fake, fake, fake, fake, None, fake, None, 0, st) == -3
+    assert lib.team_moe_layer_forward(C.byref(cfg), fake, 8, fake, fake, fake, fake, None, fake, fake, 1024, st) == -3
+    assert lib.team_moe_layer_forward(C.byref(cfg), fake, 8, fake, fake, fake, fake, None, fake, odd, 1 << 30, st) == -3
+    assert lib.team_moe_expert_ffn(C.byref(cfg), fake, 8, fake, fake, fake, fake, fake, fake, fake, fake, fake, 16, st) == -3
+    # NULL cfg / NULL size pointer
+    assert lib.team_moe_workspace_size(None, C.byref(C.c_size_t())) == -1
+    assert lib.team_moe_workspace_size(C.byref(cfg), None) == -1
+    bad = tm.make_config(2048, 768, 128, 8, "bf16", 1, 32)
+    bad.dtype = 7
+    assert lib.team_moe_route(C.byref(bad), fake, 8, fake, None, fake, fake, None, st) == -1
+
+
+def test_product_package_does_not_use_the_oracle():
+    """No file of the product package imports, includes, loads or names a path of the oracle."""
+    pkg = os.path.join(ROOT, "paper_2602_08404_amd")
+    pat = re.compile(r"(import\s+oracle|from\s+oracle|from\s+\.\.?\s*oracle|#include\s+\"[^\"]*oracle|libteam_moe_oracle|oracle/)")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                assert not pat.search(open(os.path.join(dirpath, f)).read()), f
