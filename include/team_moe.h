@@ -92,7 +92,10 @@ int team_moe_route(const team_moe_config* cfg, const void* x, int32_t T, const v
  *   inv_pos[T,k]         row of pair (t,s) in that order, -1 for padded slots
  *   active_experts[E]    ids of the experts with at least one row, ascending, padded with -1
  *   n_active[1]          their number
- * Entries of topk_idx outside [0,E) are treated as padding.  `workspace` is not used (may be NULL).
+ * Entries of topk_idx outside [0,E) are treated as padding.
+ * `workspace` may be NULL.  If it is given (same buffer and size rules as for team_moe_expert_ffn), the call also
+ * prepares in it the small control block team_moe_expert_ffn starts from; one preparation serves one
+ * team_moe_expert_ffn call.
  */
 int team_moe_build_dispatch(const team_moe_config* cfg, const int32_t* topk_idx, int32_t T,
                             int32_t* expert_offsets, int32_t* sorted_token, int32_t* inv_pos,
@@ -107,6 +110,8 @@ int team_moe_build_dispatch(const team_moe_config* cfg, const int32_t* topk_idx,
  *                                                               are left untouched)
  * TEAM_BF16: products on bf16 MFMA with float accumulation; h is rounded to bf16 between the two GEMMs.
  * Weights of experts that are not listed are not read.
+ * `workspace` must be the buffer that the team_moe_build_dispatch call which produced these tables was given
+ * (it prepared the control block this call consumes); TEAM_F32 needs no preparation.
  */
 int team_moe_expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, const int32_t* expert_offsets,
                         const int32_t* sorted_token, const int32_t* active_experts, const int32_t* n_active,

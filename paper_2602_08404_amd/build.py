@@ -9,16 +9,19 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libteam_moe.so")
-SOURCES = ["api.hip", "route.hip", "dispatch.hip", "combine.hip", "ffn_f32.hip", "ffn_bf16.hip"]
+# (source, object suffix, extra defines); the FFN kernel file is compiled once per supported hidden size
+SOURCES = [("api.hip", "", []), ("route.hip", "", []), ("dispatch.hip", "", []), ("combine.hip", "", []), ("ffn_f32.hip", "", []),
+           ("ffn_bf16.hip", "", [])] + [("ffn_bf16_kernel.hip", f"_ksa{ksa}", [f"-DFFN_KSA_THIS_FILE={ksa}"]) for ksa in (16, 8, 4, 2)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 ops are switched off for device code: some forms have produced wrong results on this hardware.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-command-line-argument",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    subprocess.run([HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
+def _compile(job) -> str:
+    src, suffix, defines = job
+    obj = os.path.join(OBJ, src.replace(".hip", suffix + ".o"))
+    subprocess.run([HIPCC, *FLAGS, *defines, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
     return obj
 
 

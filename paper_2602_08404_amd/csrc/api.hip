@@ -44,16 +44,17 @@ Dims dims_of(const team_moe_config* c, int32_t T) {
     return d;
 }
 
-// Workspace layout, sized for max_tokens.  The expert FFN's scratch (h) comes first so that
+// Workspace layout, sized for max_tokens.  The expert FFN's scratch (control block, h) comes first so that
 // team_moe_expert_ffn and team_moe_layer_forward agree on where it is.
 struct Layout {
-    size_t h, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, total;
+    size_t ctrl, h, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, total;
 };
 Layout layout_of(const team_moe_config* c) {
     const size_t A = (size_t)c->max_tokens * c->top_k;
     const size_t elem = c->dtype == TEAM_BF16 ? 2 : 4;
     Layout L;
     size_t off = 0;
+    L.ctrl = off;         off += align256(team::ffn_ctrl_bytes());
     L.h = off;            off += align256(A * c->inter * elem);
     L.topk_idx = off;     off += align256(A * 4);
     L.topk_gate = off;    off += align256(A * 4);
@@ -78,10 +79,10 @@ inline int hip_status(hipError_t e) {
 
 int run_ffn(const team_moe_config* cfg, const Dims& d, const void* x, const int32_t* offsets, const int32_t* sorted_token,
             const int32_t* active, const int32_t* n_active, const void* wg, const void* wu, const void* wd, float* expert_out,
-            void* h_ws, hipStream_t s) {
+            void* ctrl, void* h_ws, hipStream_t s) {
     if (cfg->dtype == TEAM_BF16)
         return hip_status(team::launch_ffn_bf16(d, (const uint16_t*)x, offsets, sorted_token, active, n_active, (const uint16_t*)wg,
-                                                (const uint16_t*)wu, (const uint16_t*)wd, (uint16_t*)h_ws, expert_out, s));
+                                                (const uint16_t*)wu, (const uint16_t*)wd, ctrl, (uint16_t*)h_ws, expert_out, s));
     return hip_status(team::launch_ffn_f32(d, (const float*)x, offsets, sorted_token, active, n_active, (const float*)wg,
                                            (const float*)wu, (const float*)wd, (float*)h_ws, expert_out, s));
 }
@@ -113,14 +114,20 @@ int team_moe_route(const team_moe_config* cfg, const void* x, int32_t T, const v
 int team_moe_build_dispatch(const team_moe_config* cfg, const int32_t* topk_idx, int32_t T, int32_t* expert_offsets,
                             int32_t* sorted_token, int32_t* inv_pos, int32_t* active_experts, int32_t* n_active, void* workspace,
                             size_t ws_bytes, void* stream) {
-    (void)workspace; (void)ws_bytes;
     int st = check_cfg(cfg);
     if (st != TEAM_OK) return st;
     if ((st = check_T(cfg, T)) != TEAM_OK) return st;
     if (!topk_idx || !expert_offsets || !sorted_token || !inv_pos || !active_experts || !n_active) return TEAM_ERR_INVALID_ARG;
+    // With a workspace, the same kernel also prepares (clears) the control block the expert FFN starts from.
+    team::CtrlZero cz{nullptr, 0, 0};
+    if (workspace) {
+        const Layout L = layout_of(cfg);
+        if (!aligned16(workspace) || ws_bytes < L.topk_idx) return TEAM_ERR_WORKSPACE;
+        if (cfg->dtype == TEAM_BF16) cz = team::ffn_ctrl_zero((char*)workspace + L.ctrl);
+    }
     clear_stale_error();
     return hip_status(team::launch_dispatch(dims_of(cfg, T), topk_idx, expert_offsets, sorted_token, inv_pos, active_experts, n_active,
-                                            (hipStream_t)stream));
+                                            cz, (hipStream_t)stream));
 }
 
 int team_moe_expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, const int32_t* expert_offsets,
@@ -134,10 +141,10 @@ int team_moe_expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, co
     if (!aligned16(x) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) || !aligned16(expert_out))
         return TEAM_ERR_INVALID_ARG;
     const Layout L = layout_of(cfg);
-    if (!workspace || !aligned16(workspace) || ws_bytes < L.topk_idx /* = size of the h segment */) return TEAM_ERR_WORKSPACE;
+    if (!workspace || !aligned16(workspace) || ws_bytes < L.topk_idx /* = end of the control block + h segments */) return TEAM_ERR_WORKSPACE;
     clear_stale_error();
     return run_ffn(cfg, dims_of(cfg, T), x, expert_offsets, sorted_token, active_experts, n_active, w_gate, w_up, w_down, expert_out,
-                   (char*)workspace + L.h, (hipStream_t)stream);
+                   (char*)workspace + L.ctrl, (char*)workspace + L.h, (hipStream_t)stream);
 }
 
 int team_moe_combine(const team_moe_config* cfg, const float* expert_out, const float* topk_gate, const int32_t* inv_pos, int32_t T,
@@ -175,8 +182,12 @@ int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T,
     hipStream_t s = (hipStream_t)stream;
     clear_stale_error();
     if ((st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, nullptr, s))) != TEAM_OK) return st;
-    if ((st = hip_status(team::launch_dispatch(d, topk_idx, offsets, sorted_token, inv_pos, active, n_active, s))) != TEAM_OK) return st;
-    if ((st = run_ffn(cfg, d, x, offsets, sorted_token, active, n_active, w_gate, w_up, w_down, expert_out, ws + L.h, s)) != TEAM_OK)
+    // the dispatch kernel also clears the FFN's control block
+    const team::CtrlZero cz = cfg->dtype == TEAM_BF16 ? team::ffn_ctrl_zero(ws + L.ctrl) : team::CtrlZero{nullptr, 0, 0};
+    if ((st = hip_status(team::launch_dispatch(d, topk_idx, offsets, sorted_token, inv_pos, active, n_active, cz, s))) != TEAM_OK)
+        return st;
+    if ((st = run_ffn(cfg, d, x, offsets, sorted_token, active, n_active, w_gate, w_up, w_down, expert_out, ws + L.ctrl,
+                      ws + L.h, s)) != TEAM_OK)
         return st;
     return hip_status(team::launch_combine(d, expert_out, topk_gate, inv_pos, y, s));
 }

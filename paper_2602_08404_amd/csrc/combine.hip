@@ -7,6 +7,7 @@
 namespace team {
 
 constexpr int COMBINE_THREADS = 256;
+constexpr int C_MAX_K = 16;      // top_k limit of the library
 
 template <bool BF16>
 __global__ __launch_bounds__(COMBINE_THREADS) void combine_kernel(const float* __restrict__ expert_out, const float* __restrict__ gate,
@@ -14,13 +15,24 @@ __global__ __launch_bounds__(COMBINE_THREADS) void combine_kernel(const float* _
     const int t = blockIdx.y;
     const int h4 = (blockIdx.x * COMBINE_THREADS + threadIdx.x) * 4;
     if (h4 >= H) return;
+    // all slot indices and gates first, then all expert rows, then the sum in slot order: the loads of the
+    // k rows are in flight together
+    int p[C_MAX_K];
+    float g[C_MAX_K];
+    float4 o[C_MAX_K];
+#pragma unroll
+    for (int s = 0; s < C_MAX_K; ++s) {
+        p[s] = s < k ? inv_pos[(size_t)t * k + s] : -1;
+        g[s] = s < k ? gate[(size_t)t * k + s] : 0.f;
+    }
+#pragma unroll
+    for (int s = 0; s < C_MAX_K; ++s)
+        o[s] = p[s] >= 0 ? *reinterpret_cast<const float4*>(expert_out + (size_t)p[s] * H + h4) : make_float4(0.f, 0.f, 0.f, 0.f);
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = 0; s < k; ++s) {
-        int p = inv_pos[(size_t)t * k + s];
-        if (p < 0) continue;
-        float g = gate[(size_t)t * k + s];
-        float4 o = *reinterpret_cast<const float4*>(expert_out + (size_t)p * H + h4);
-        acc.x = fmaf(g, o.x, acc.x); acc.y = fmaf(g, o.y, acc.y); acc.z = fmaf(g, o.z, acc.z); acc.w = fmaf(g, o.w, acc.w);
+#pragma unroll
+    for (int s = 0; s < C_MAX_K; ++s) {
+        if (p[s] < 0) continue;
+        acc.x = fmaf(g[s], o[s].x, acc.x); acc.y = fmaf(g[s], o[s].y, acc.y); acc.z = fmaf(g[s], o[s].z, acc.z); acc.w = fmaf(g[s], o[s].w, acc.w);
     }
     if (BF16) {
         uint2 packed;

@@ -18,15 +18,66 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Cross-lane moves inside a row of 16 lanes (data-parallel primitives, no LDS traffic).
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+}
+constexpr int DPP_XOR1 = 0xB1;          // quad_perm [1,0,3,2]
+constexpr int DPP_XOR2 = 0x4E;          // quad_perm [2,3,0,1]
+constexpr int DPP_HALF_MIRROR = 0x141;  // lane i <-> 7-i inside 8 lanes
+constexpr int DPP_MIRROR = 0x140;       // lane i <-> 15-i inside 16 lanes
+
+// Sum over the 64 lanes, returned in every lane.  Fixed order: pairs, quads, 8, 16 lanes, then the four rows.
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, WAVE);
-    return v;
+    v += dpp_f32<DPP_XOR1>(v);
+    v += dpp_f32<DPP_XOR2>(v);
+    v += dpp_f32<DPP_HALF_MIRROR>(v);
+    v += dpp_f32<DPP_MIRROR>(v);
+    const float a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float b = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float c = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (a + b) + (c + d);
 }
 __device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, dpp_f32<DPP_XOR1>(v));
+    v = fmaxf(v, dpp_f32<DPP_XOR2>(v));
+    v = fmaxf(v, dpp_f32<DPP_HALF_MIRROR>(v));
+    v = fmaxf(v, dpp_f32<DPP_MIRROR>(v));
+    const float a = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float b = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float c = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float d = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return fmaxf(fmaxf(a, b), fmaxf(c, d));
+}
+// Maximum of a 64-bit key over the 64 lanes, returned in every lane.
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long key) {
+    uint32_t hi = (uint32_t)(key >> 32), lo = (uint32_t)key;
+#define TEAM_STEP(CTRL)                                                              \
+    {                                                                                \
+        const uint32_t ohi = dpp_u32<CTRL>(hi), olo = dpp_u32<CTRL>(lo);             \
+        const bool take = ohi > hi || (ohi == hi && olo > lo);                       \
+        hi = take ? ohi : hi;                                                        \
+        lo = take ? olo : lo;                                                        \
+    }
+    TEAM_STEP(DPP_XOR1)
+    TEAM_STEP(DPP_XOR2)
+    TEAM_STEP(DPP_HALF_MIRROR)
+    TEAM_STEP(DPP_MIRROR)
+#undef TEAM_STEP
+    unsigned long long best = 0;
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, WAVE));
-    return v;
+    for (int r = 0; r < 64; r += 16) {
+        const unsigned long long k = ((unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)hi, r) << 32) |
+                                     (uint32_t)__builtin_amdgcn_readlane((int)lo, r);
+        best = k > best ? k : best;
+    }
+    return best;
 }
 
 // Element loaders: N consecutive elements of storage type -> float.

@@ -16,7 +16,7 @@ constexpr int D_MAX_WORDS = 32;          // 32 words x 32 bits = 1024 tokens
 __global__ __launch_bounds__(DISPATCH_THREADS) void dispatch_kernel(const int32_t* __restrict__ topk_idx, int T, int k, int E,
                                                                     int32_t* __restrict__ offsets, int32_t* __restrict__ sorted_token,
                                                                     int32_t* __restrict__ inv_pos, int32_t* __restrict__ active,
-                                                                    int32_t* __restrict__ n_active) {
+                                                                    int32_t* __restrict__ n_active, CtrlZero ctrl) {
     __shared__ uint32_t s_bits[D_MAX_E * D_MAX_WORDS];
     __shared__ unsigned long long s_scan[2][D_MAX_E];   // low 32 bits: rows, high 32 bits: 1 if the expert has rows
     __shared__ int32_t s_off[D_MAX_E + 1];
@@ -24,6 +24,10 @@ __global__ __launch_bounds__(DISPATCH_THREADS) void dispatch_kernel(const int32_
     const int words = (T + 31) / 32;
     const int A = T * k;
 
+    if (ctrl.words) {                           // control block of the expert FFN that follows
+        if (tid < ctrl.header) ctrl.words[tid] = 0;
+        if (tid < E) ctrl.words[ctrl.header + tid * ctrl.stride] = 0;
+    }
     for (int i = tid; i < E * words; i += DISPATCH_THREADS) s_bits[i] = 0u;
     __syncthreads();
     for (int r = tid; r < A; r += DISPATCH_THREADS) {
@@ -90,9 +94,9 @@ __global__ __launch_bounds__(DISPATCH_THREADS) void dispatch_kernel(const int32_
 }
 
 hipError_t launch_dispatch(const Dims& d, const int32_t* topk_idx, int32_t* offsets, int32_t* sorted_token, int32_t* inv_pos,
-                           int32_t* active, int32_t* n_active, hipStream_t s) {
+                           int32_t* active, int32_t* n_active, CtrlZero ctrl, hipStream_t s) {
     hipLaunchKernelGGL(dispatch_kernel, dim3(1), dim3(DISPATCH_THREADS), 0, s, topk_idx, d.T, d.k, d.E, offsets, sorted_token,
-                       inv_pos, active, n_active);
+                       inv_pos, active, n_active, ctrl);
     return hipGetLastError();
 }
 

@@ -1,0 +1,50 @@
+// Internal declarations shared by the host side (ffn_bf16.hip) and the kernel instantiations
+// (ffn_bf16_kernel.hip, compiled once per hidden size) of the bf16 grouped expert FFN.
+#pragma once
+#include "device_utils.hpp"
+#include "kernels.hpp"
+
+namespace team {
+
+constexpr int FFN_THREADS = 256;
+constexpr int FFN_WAVES = 4;
+constexpr int FFN_MAX_E = 256;
+constexpr int FFN_DONE_STRIDE = 64;      // one counter per 256 bytes: polled counters sit in different memory channels
+
+// Control block of one FFN launch (in the caller's workspace); must be all zero when the kernel starts.
+struct FfnCtrl {
+    int32_t reserved0;
+    int32_t error;              // set if a bounded wait gave up (never in correct operation)
+    int32_t pad[14];
+    int32_t done[FFN_MAX_E][FFN_DONE_STRIDE];   // [slot][0]: gate/up items of the slot that have published their part of h
+};
+
+struct FfnArgs {
+    const uint16_t* x;
+    const int32_t* offsets;
+    const int32_t* sorted_token;
+    const int32_t* active;
+    const int32_t* n_active;
+    const uint16_t* wg;
+    const uint16_t* wu;
+    const uint16_t* wd;
+    uint16_t* h;
+    float* out;
+    FfnCtrl* ctrl;
+    int T, k, E;
+    int n_cu;                   // compute units of the current device
+    int grid_override;          // > 0: use a smaller grid than the resident maximum (tuning aid)
+    int spin_limit;
+    hipStream_t stream;
+};
+
+// KSA = hidden / 128; dispatches on ksb = inter / 128.
+template <int KSA>
+hipError_t launch_ffn_fused_ksa(const FfnArgs& p, int ksb);
+
+extern template hipError_t launch_ffn_fused_ksa<2>(const FfnArgs&, int);
+extern template hipError_t launch_ffn_fused_ksa<4>(const FfnArgs&, int);
+extern template hipError_t launch_ffn_fused_ksa<8>(const FfnArgs&, int);
+extern template hipError_t launch_ffn_fused_ksa<16>(const FfnArgs&, int);
+
+}  // namespace team

@@ -1,0 +1,392 @@
+// Grouped SwiGLU expert FFN over the activated experts, bf16 storage, gfx950 MFMA, HBM-streaming design.
+//
+// Paper context: block-level decoding is memory-bound (Section "Delayed Caching for Decoded Tokens"), latency
+// is dominated by the feed-forward layers and every activated expert serves only a few tokens (Section
+// "Speculative Exploration for Hot Tokens").  So the cost of this step is reading the weights of the experts
+// that received tokens, once, at HBM speed; the arithmetic rides along on the matrix cores.
+//
+// ONE persistent kernel does both GEMMs.  Work items:
+//   gate/up items : (active expert, 8 consecutive intermediate indices) = 8 rows of w_gate + 8 rows of w_up,
+//                   all H columns; h = silu(g) * u is formed in the epilogue and stored as bf16;
+//   down items    : (active expert, 16*RB consecutive output rows of w_down), all I columns; fp32 out.
+// The grid is exactly the number of workgroups the device holds at once.  Workgroup b owns the b-th of G
+// equal contiguous shares of the gate/up item list and then the b-th share of the down item list (lists in
+// expert-major order, computed on the device from n_active, so experts without tokens cost nothing and the
+// host never reads device data).  Consecutive items of a share belong to the same expert, so the token
+// operand stays in registers; and because both lists are cut at the same fractions, the down items of a
+// workgroup belong to the expert(s) whose gate/up items it and its neighbours have just finished.  A down
+// item waits (bounded spin on a per-expert counter) until every gate/up item of its expert has published h.
+// Gate/up items never wait and every workgroup is resident (the host sizes the grid from the occupancy the
+// runtime reports), so every wait ends.
+//
+// Inside a workgroup the reduction dimension is split over the 4 wavefronts.  Each wavefront pulls its
+// slice of the item's weight rows HBM -> LDS with 16-byte-per-lane direct-to-LDS loads (lanes consecutive
+// along the contiguous dimension), keeps the whole slice in flight at once, then feeds v_mfma_f32_16x16x32
+// bf16 with the weights as the 16-row operand and up to 32 token rows as the 16-column operand.  Partial
+// sums of the 4 wavefronts are added in a fixed order through LDS (deterministic, no float atomics).
+//
+// LDS slice layout: a wavefront's slice of a 16-row sub-tile is 16 rows x C chunks of 16 bytes
+// (C = 4 * K-steps).  Chunk (r, c) sits at position r*C + (c ^ (r >> (4 - V))), V = min(4, ctz(C)), which
+// makes the 16 rows of one MFMA operand read hit 16 different 16-byte bank groups.
+#include "ffn_bf16.hpp"
+
+namespace team {
+
+namespace {
+
+constexpr int NT = 2;                    // token tiles of 16 rows handled per pass (32 tokens)
+
+typedef const __attribute__((address_space(1))) void* gptr_t;
+typedef __attribute__((address_space(3))) void* lptr_t;
+
+// 64 lanes x 16 bytes, each lane from its own global address, land contiguously at lds_base + lane*16.
+__device__ __forceinline__ void slab_load(const void* gsrc, char* lds_base_uniform) {
+    __builtin_amdgcn_global_load_lds((gptr_t)gsrc, (lptr_t)lds_base_uniform, 16, 0, 0);
+}
+// Waits until every outstanding vector-memory operation of this wavefront (loads, direct-to-LDS loads and
+// stores: one counter on this architecture) has completed.
+__device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// h travels between workgroups that may sit on different XCDs (each with its own L2) inside one launch.
+// Both sides use device-scope accesses (the stores write through to the device-coherent level, the loads do
+// not use possibly stale cache lines), so no cache-wide write-back or invalidate is needed around the
+// per-expert counter: those cost far more than the item they would guard.
+__device__ __forceinline__ void store_coherent(uint32_t* p, uint32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bf16x8_t load_coherent_16(const uint16_t* p) {
+    union {
+        unsigned long long u[2];
+        bf16x8_t v;
+    } r;
+    const unsigned long long* p64 = reinterpret_cast<const unsigned long long*>(p);
+    r.u[0] = __hip_atomic_load(p64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    r.u[1] = __hip_atomic_load(p64 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return r.v;
+}
+// Returns v, but opaque to the optimiser: values derived from the result are recomputed where they are used
+// instead of being hoisted out of the item loop and kept in registers (the token operand needs those registers).
+__device__ __forceinline__ int opaque(int v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
+constexpr int ctz_cap4(int c) { return (c % 16 == 0) ? 4 : (c % 8 == 0) ? 3 : (c % 4 == 0) ? 2 : (c % 2 == 0) ? 1 : 0; }
+constexpr int cmax(int a, int b) { return a > b ? a : b; }
+
+template <int KS>
+struct Slice {
+    static constexpr int C = 4 * KS;                  // 16-byte chunks per row of the wavefront's slice
+    static constexpr int V = ctz_cap4(C);
+    static constexpr int SLABS = KS;                  // 1 KB slabs per 16-row sub-tile
+    static constexpr int BYTES = 16 * C * 16;         // bytes of one 16-row sub-tile slice
+    __device__ static __forceinline__ int phys(int r, int c) { return r * C + (c ^ (r >> (4 - V))); }
+};
+
+#ifdef TEAM_FFN_TRACE
+__device__ long long g_ffn_trace[2048][12];
+__device__ long long g_ffn_items[2048][3][12];   // per workgroup: start, end, item id of its first 12 items
+#define TRACE_NOW() wall_clock64()
+#else
+#define TRACE_NOW() 0ll
+#endif
+
+}  // namespace
+
+// KSA = H / 128 and KSB = I / 128: MFMA K-steps (of 32) per wavefront in the two GEMMs; RB = 16-row sub-tiles
+// of w_down per down item.
+template <int KSA, int KSB, int RB>
+__global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_t* __restrict__ x, const int32_t* __restrict__ offsets,
+                                                                   const int32_t* __restrict__ sorted_token,
+                                                                   const int32_t* __restrict__ active, const int32_t* __restrict__ n_active,
+                                                                   const uint16_t* __restrict__ wg, const uint16_t* __restrict__ wu,
+                                                                   const uint16_t* __restrict__ wd, uint16_t* __restrict__ h,
+                                                                   float* __restrict__ out, FfnCtrl* __restrict__ ctrl, int T, int k, int E,
+                                                                   int spin_limit) {
+    using SA = Slice<KSA>;
+    using SB = Slice<KSB>;
+    constexpr int H = KSA * 128, I = KSB * 128;
+    constexpr int KSLICE_A = KSA * 32, KSLICE_B = KSB * 32;       // columns per wavefront
+    constexpr int KSM = cmax(KSA, KSB);
+    constexpr int W_A = FFN_WAVES * SA::BYTES, W_B = FFN_WAVES * RB * SB::BYTES;
+    constexpr int RED_A = FFN_WAVES * NT * WAVE * 16, RED_B = FFN_WAVES * RB * NT * WAVE * 16;
+    constexpr int LDS_BYTES = cmax(W_A + RED_A, W_B + RED_B);
+    constexpr int TILES_A = I / 8, TILES_B = H / (16 * RB);
+    __shared__ __attribute__((aligned(1024))) char s_mem[LDS_BYTES];
+    __shared__ int32_t s_slot_e[FFN_MAX_E];
+    __shared__ int32_t s_off[FFN_MAX_E + 1];
+    typedef f32x4_t (*red_a_t)[NT][WAVE];
+    typedef f32x4_t (*red_b_t)[RB][NT][WAVE];
+    red_a_t red_a = reinterpret_cast<red_a_t>(s_mem + LDS_BYTES - RED_A);
+    red_b_t red_b = reinterpret_cast<red_b_t>(s_mem + LDS_BYTES - RED_B);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int A = T * k;
+    const int G = gridDim.x;
+
+    [[maybe_unused]] long long tr_t0 = TRACE_NOW(), tr_a = 0, tr_b = 0, tr_wait = 0, tr_last_a = 0, tr_first_b = 0, tr_na = 0, tr_nb = 0,
+                               tr_runs = 0;
+    // ---- tables into LDS (one global round trip)
+    const int n_act = min(max(*n_active, 0), E);
+    for (int i = tid; i < E; i += FFN_THREADS) s_slot_e[i] = active[i];
+    for (int i = tid; i <= E; i += FFN_THREADS) s_off[i] = min(max(offsets[i], 0), A);
+    const long long total_a = (long long)n_act * TILES_A, total_b = (long long)n_act * TILES_B;
+    const int a_begin = (int)(total_a * blockIdx.x / G), a_end = (int)(total_a * (blockIdx.x + 1) / G);
+    const int b_begin = (int)(total_b * blockIdx.x / G), b_end = (int)(total_b * (blockIdx.x + 1) / G);
+    const int n_a = a_end - a_begin, n_mine = n_a + (b_end - b_begin);
+    __syncthreads();
+
+    [[maybe_unused]] const long long tr_t1 = TRACE_NOW();
+    bf16x8_t opr[NT][KSM];                   // token operand (x rows for gate/up items, h rows for down items)
+    int cur_key = -1;                        // (phase, slot) the operand registers hold; -1: nothing
+    int ready_slot = -1;                     // slot whose h this workgroup has already acquired
+
+    int pend = 0;                            // finished gate/up items of the current slot not yet published
+    {
+        for (int step = 0; step < n_mine; ++step) {   // this workgroup's gate/up items, then its down items
+            [[maybe_unused]] const long long tr_i0 = TRACE_NOW();
+#ifdef TEAM_FFN_TRACE
+            const int tr_k = (int)(tr_na + tr_nb);
+            if (tid == 0 && blockIdx.x < 2048 && tr_k < 12) { g_ffn_items[blockIdx.x][0][tr_k] = tr_i0; g_ffn_items[blockIdx.x][2][tr_k] = (step < n_a) ? (step < n_a ? a_begin + step : b_begin + step - n_a) : 1000000 + (step < n_a ? a_begin + step : b_begin + step - n_a); }
+#endif
+            const bool is_a = step < n_a;
+            const int li = is_a ? a_begin + step : b_begin + (step - n_a);
+            const int tiles = is_a ? TILES_A : TILES_B;
+            const int a = li / tiles, it = li - a * tiles;
+            const int e = s_slot_e[a];
+            const bool e_ok = e >= 0 && e < E;
+            const int r0 = e_ok ? s_off[e] : 0;
+            const int m = e_ok ? max(s_off[e + 1] - r0, 0) : 0;
+            const int key = (is_a ? 0 : 0x10000) | a;
+            const int ln = opaque(lane);
+            const int n = ln & 15, q = ln >> 4;
+            if (is_a) {
+                // =============================================================== gate/up item
+                char* region = s_mem + wave * SA::BYTES;
+                if (m > 0) {
+                    const size_t ebase = (size_t)e * I;
+#pragma unroll
+                    for (int j = 0; j < SA::SLABS; ++j) {
+                        const int P = 64 * j + ln;
+                        const int r = P / SA::C, cp = P % SA::C;
+                        const int c = cp ^ (r >> (4 - SA::V));
+                        // MFMA row r = 4*qq + j2: j2 in {0,1} -> gate rows, {2,3} -> up rows of intermediate index 2*qq + (j2 & 1)
+                        const uint16_t* mat = (r & 2) ? wu : wg;
+                        const int irow = it * 8 + 2 * (r >> 2) + (r & 1);
+                        slab_load(mat + (ebase + irow) * H + wave * KSLICE_A + c * 8, region + j * 1024);
+                    }
+                }
+                const int chunks = (m + 16 * NT - 1) / (16 * NT);
+                for (int ch = 0; ch < chunks; ++ch) {
+                    const int row_base = ch * 16 * NT;
+                    if (key != cur_key || chunks > 1) {
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) {
+                            const int row = row_base + nt * 16 + n;
+                            int tok = row < m ? sorted_token[r0 + row] : -1;
+                            if (tok >= T) tok = -1;
+                            const uint16_t* xp = x + (size_t)(tok < 0 ? 0 : tok) * H + wave * KSLICE_A + q * 8;
+                            if (tok >= 0) {
+#pragma unroll
+                                for (int s = 0; s < KSA; ++s) opr[nt][s] = *reinterpret_cast<const bf16x8_t*>(xp + s * 32);
+                            } else {
+#pragma unroll
+                                for (int s = 0; s < KSA; ++s) opr[nt][s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                            }
+                        }
+                        cur_key = chunks > 1 ? -1 : key;
+                    }
+                    wait_all_loads();
+                    const bool two = m - row_base > 16;
+                    f32x4_t acc[NT] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+                    for (int s = 0; s < KSA; ++s) {
+                        const bf16x8_t wv = *reinterpret_cast<const bf16x8_t*>(region + SA::phys(n, 4 * s + q) * 16);
+                        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, opr[0][s], acc[0], 0, 0, 0);
+                        if (two) acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, opr[1][s], acc[1], 0, 0, 0);
+                    }
+                    red_a[wave][0][ln] = acc[0];
+                    red_a[wave][1][ln] = acc[1];
+                    __syncthreads();
+                    if (wave < NT && (wave == 0 || two)) {        // wavefront nt finishes token tile nt
+                        f32x4_t v = red_a[0][wave][ln];
+#pragma unroll
+                        for (int w = 1; w < FFN_WAVES; ++w) v += red_a[w][wave][ln];
+                        const int row = row_base + wave * 16 + n;
+                        if (row < m) {
+                            // lane holds (g_a, g_b, u_a, u_b) of intermediate indices it*8 + 2*q, +1 for token row `row`
+                            const float h0 = silu_f32(v[0]) * v[2];
+                            const float h1 = silu_f32(v[1]) * v[3];
+                            const uint32_t packed = f32_to_bf16_bits(h0) | (f32_to_bf16_bits(h1) << 16);
+                            store_coherent(reinterpret_cast<uint32_t*>(h + (size_t)(r0 + row) * I + it * 8 + 2 * q), packed);
+                        }
+                    }
+                    wait_all_loads();     // vmcnt counts stores too: this wavefront's h stores have been acknowledged
+                    __syncthreads();      // h stores of this workgroup are complete; partial-sum buffer is free
+                }
+                // publish finished gate/up items, once per run of items of one slot.  The h stores above are
+                // device-coherent write-through stores and every wavefront has waited for its own before the barrier.
+                ++pend;
+                if (step + 1 >= n_a || (li + 1) / TILES_A != a) {
+                    if (tid == 0) __hip_atomic_fetch_add(&ctrl->done[a][0], pend, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    pend = 0;
+                }
+                tr_last_a = TRACE_NOW();
+                tr_a += tr_last_a - tr_i0;
+#ifdef TEAM_FFN_TRACE
+                if (tid == 0 && blockIdx.x < 2048 && tr_k < 12) g_ffn_items[blockIdx.x][1][tr_k] = tr_last_a;
+#endif
+                ++tr_na;
+            } else {
+                if (tr_first_b == 0) tr_first_b = tr_i0;
+                // =============================================================== down item
+                char* region = s_mem + wave * (RB * SB::BYTES);
+                if (m > 0) {
+                    const size_t ebase = (size_t)e * H + (size_t)it * 16 * RB;
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int j = 0; j < SB::SLABS; ++j) {
+                            const int P = 64 * j + ln;
+                            const int r = P / SB::C, cp = P % SB::C;
+                            const int c = cp ^ (r >> (4 - SB::V));
+                            slab_load(wd + (ebase + rb * 16 + r) * I + wave * KSLICE_B + c * 8, region + rb * SB::BYTES + j * 1024);
+                        }
+                }
+                if (a != ready_slot) {       // wait until every gate/up item of this expert has published h
+                    [[maybe_unused]] const long long tr_w0 = TRACE_NOW();
+                    if (tid == 0) {
+                        int spins = 0;
+                        while (__hip_atomic_load(&ctrl->done[a][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < TILES_A) {
+                            __builtin_amdgcn_s_sleep(32);     // ~1 us between polls: many workgroups poll the same few counters
+                            if (++spins > spin_limit) {          // cannot happen with a control block zeroed before the launch
+                                ctrl->error = 1;
+                                break;
+                            }
+                        }
+                    }
+                    __syncthreads();
+                    ready_slot = a;
+                    tr_wait += TRACE_NOW() - tr_w0;
+                }
+                const int chunks = (m + 16 * NT - 1) / (16 * NT);
+                for (int ch = 0; ch < chunks; ++ch) {
+                    const int row_base = ch * 16 * NT;
+                    if (key != cur_key || chunks > 1) {
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) {
+                            const int row = row_base + nt * 16 + n;
+                            const bool valid = row < m && sorted_token[r0 + row] >= 0;
+                            const uint16_t* hp = h + (size_t)(valid ? r0 + row : 0) * I + wave * KSLICE_B + q * 8;
+                            if (valid) {
+#pragma unroll
+                                for (int s = 0; s < KSB; ++s) opr[nt][s] = load_coherent_16(hp + s * 32);
+                            } else {
+#pragma unroll
+                                for (int s = 0; s < KSB; ++s) opr[nt][s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                            }
+                        }
+                        cur_key = chunks > 1 ? -1 : key;
+                    }
+                    wait_all_loads();
+                    const bool two = m - row_base > 16;
+                    f32x4_t acc[RB][NT];
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) acc[rb][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int s = 0; s < KSB; ++s) {
+#pragma unroll
+                        for (int rb = 0; rb < RB; ++rb) {
+                            const bf16x8_t wv = *reinterpret_cast<const bf16x8_t*>(region + rb * SB::BYTES + SB::phys(n, 4 * s + q) * 16);
+                            acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, opr[0][s], acc[rb][0], 0, 0, 0);
+                            if (two) acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, opr[1][s], acc[rb][1], 0, 0, 0);
+                        }
+                    }
+#pragma unroll
+                    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) red_b[wave][rb][nt][ln] = acc[rb][nt];
+                    __syncthreads();
+                    // (rb, nt) pairs are finished by wavefronts round-robin, partial sums added in wavefront order
+                    for (int pair = wave; pair < RB * NT; pair += FFN_WAVES) {
+                        const int rb = pair / NT, nt = pair % NT;
+                        const int row = row_base + nt * 16 + n;
+                        if (row < m) {
+                            f32x4_t v = red_b[0][rb][nt][ln];
+#pragma unroll
+                            for (int w = 1; w < FFN_WAVES; ++w) v += red_b[w][rb][nt][ln];
+                            // lane holds output rows it*16*RB + rb*16 + 4*q + (0..3) of token row `row`
+                            *reinterpret_cast<f32x4_t*>(out + (size_t)(r0 + row) * H + it * 16 * RB + rb * 16 + 4 * q) = v;
+                        }
+                    }
+                    __syncthreads();
+                }
+                tr_b += TRACE_NOW() - tr_i0;
+#ifdef TEAM_FFN_TRACE
+                if (tid == 0 && blockIdx.x < 2048 && tr_k < 12) g_ffn_items[blockIdx.x][1][tr_k] = TRACE_NOW();
+#endif
+                ++tr_nb;
+            }
+        }
+    }
+#ifdef TEAM_FFN_TRACE
+    if (tid == 0 && blockIdx.x < 2048) {
+        long long* t = g_ffn_trace[blockIdx.x];
+        t[0] = tr_t0; t[1] = tr_t1; t[2] = tr_a; t[3] = tr_na; t[4] = tr_b; t[5] = tr_nb; t[6] = tr_wait; t[7] = tr_last_a;
+        t[8] = tr_first_b; t[9] = TRACE_NOW(); t[10] = tr_runs; t[11] = (long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) | ((long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32);  /* HW_ID, XCC_ID */
+    }
+#endif
+}
+
+#ifdef TEAM_FFN_TRACE
+extern "C" int team_moe_debug_read_trace(void* host, size_t bytes) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_ffn_trace), bytes);
+}
+extern "C" int team_moe_debug_read_items(void* host, size_t bytes) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_ffn_items), bytes);
+}
+#endif
+
+// The kernel's waits need every workgroup of the grid to be resident at once, so the grid is what the runtime
+// says fits: (workgroups per compute unit for this instantiation) x (compute units), never more.
+template <int KSA, int KSB>
+hipError_t launch_ffn_fused(const FfnArgs& p) {
+    constexpr int RB = KSB <= 7 ? 2 : 1;
+    static int resident = 0;         // per instantiation; same value for every caller, so a benign race
+    if (resident == 0) {
+        int per_cu = 0;
+        hipError_t err = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, ffn_fused_kernel<KSA, KSB, RB>, FFN_THREADS, 0);
+        if (err != hipSuccess) return err;
+        if (per_cu < 1) return hipErrorLaunchOutOfResources;
+        resident = per_cu * p.n_cu;
+    }
+    const int grid = p.grid_override > 0 && p.grid_override < resident ? p.grid_override : resident;
+    hipLaunchKernelGGL((ffn_fused_kernel<KSA, KSB, RB>), dim3(grid), dim3(FFN_THREADS), 0, p.stream, p.x, p.offsets, p.sorted_token,
+                       p.active, p.n_active, p.wg, p.wu, p.wd, p.h, p.out, p.ctrl, p.T, p.k, p.E, p.spin_limit);
+    return hipGetLastError();
+}
+
+template <int KSA>
+hipError_t launch_ffn_fused_ksa(const FfnArgs& p, int ksb) {
+    switch (ksb) {
+        case 1: return launch_ffn_fused<KSA, 1>(p);
+        case 2: return launch_ffn_fused<KSA, 2>(p);
+        case 3: return launch_ffn_fused<KSA, 3>(p);
+        case 4: return launch_ffn_fused<KSA, 4>(p);
+        case 5: return launch_ffn_fused<KSA, 5>(p);
+        case 6: return launch_ffn_fused<KSA, 6>(p);
+        case 7: return launch_ffn_fused<KSA, 7>(p);
+        case 8: return launch_ffn_fused<KSA, 8>(p);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+#ifndef FFN_KSA_THIS_FILE
+#error "compile with -DFFN_KSA_THIS_FILE=<hidden/128>"
+#endif
+template hipError_t launch_ffn_fused_ksa<FFN_KSA_THIS_FILE>(const FfnArgs& p, int ksb);
+
+}  // namespace team

@@ -14,8 +14,15 @@ struct Dims {
 
 hipError_t launch_route(const Dims& d, const void* x, const void* w_router, const uint8_t* mask, int32_t* topk_idx,
                         float* topk_gate, float* logits_out, hipStream_t s);
+// Words of the FFN control block that must be zero before an FFN launch: `header` leading words, then one word
+// every `stride` words for each of the E expert slots.
+struct CtrlZero {
+    int32_t* words;     // nullptr: nothing to clear
+    int header, stride;
+};
+// ctrl: control block the dispatch kernel also clears for the expert FFN that follows (words == nullptr: none).
 hipError_t launch_dispatch(const Dims& d, const int32_t* topk_idx, int32_t* offsets, int32_t* sorted_token,
-                           int32_t* inv_pos, int32_t* active, int32_t* n_active, hipStream_t s);
+                           int32_t* inv_pos, int32_t* active, int32_t* n_active, CtrlZero ctrl, hipStream_t s);
 hipError_t launch_combine(const Dims& d, const float* expert_out, const float* gate, const int32_t* inv_pos, void* y,
                           hipStream_t s);
 // fp32 storage: plain-ALU grouped FFN.
@@ -23,9 +30,13 @@ hipError_t launch_ffn_f32(const Dims& d, const float* x, const int32_t* offsets,
                           const int32_t* active, const int32_t* n_active, const float* wg, const float* wu,
                           const float* wd, float* h_ws, float* expert_out, hipStream_t s);
 // bf16 storage: MFMA grouped FFN streaming the weights of the active experts.
+// ctrl: ffn_ctrl_bytes() of scratch for the kernel's per-expert counters; the words ffn_ctrl_zero() names must be
+// zero when the kernel starts (the dispatch kernel clears them).
 bool ffn_bf16_supported(int H, int I);
+size_t ffn_ctrl_bytes();
+CtrlZero ffn_ctrl_zero(void* ctrl);
 hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offsets, const int32_t* sorted_token,
                            const int32_t* active, const int32_t* n_active, const uint16_t* wg, const uint16_t* wu,
-                           const uint16_t* wd, uint16_t* h_ws, float* expert_out, hipStream_t s);
+                           const uint16_t* wd, void* ctrl, uint16_t* h_ws, float* expert_out, hipStream_t s);
 
 }  // namespace team

@@ -96,6 +96,9 @@ def gpu_expert_ffn(case: Case, offsets, sorted_token, active, n_active):
     A = s.T * s.k
     ws = torch.empty(tm.team_moe_workspace_size(case.cfg), dtype=torch.uint8, device=DEV)
     out = torch.full((A, s.H), float("nan"), dtype=torch.float32, device=DEV)
+    # staged use: the dispatch call that precedes an FFN call prepares the workspace for it
+    scratch = [torch.empty(n, dtype=torch.int32, device=DEV) for n in (s.E + 1, A, A, s.E, 1)]
+    tm.team_moe_build_dispatch(case.cfg, torch.full((s.T, s.k), -1, dtype=torch.int32, device=DEV), s.T, *scratch, workspace=ws)
     tm.team_moe_expert_ffn(case.cfg, case.d_x, s.T, torch.from_numpy(offsets).to(DEV), torch.from_numpy(sorted_token).to(DEV),
                            torch.from_numpy(active).to(DEV), torch.tensor([n_active], dtype=torch.int32, device=DEV),
                            case.d_w["gate"], case.d_w["up"], case.d_w["down"], out, ws)
