@@ -41,6 +41,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--copies", type=int, default=4, help="distinct weight sets rotated over")
+    ap.add_argument("--masks", type=str, default="128,64,32,16",
+                    help="activated-set sizes of the sweep (the headline size 32 is always measured); e.g. --masks 32 for a profile of the headline only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     args = ap.parse_args()
@@ -48,6 +50,9 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU (one process, one MI355X); --gpus must be 1. "
               "Nothing here uses a second GPU.", file=sys.stderr)
         return 2
+
+    global MASK_SIZES
+    MASK_SIZES = tuple(sorted({int(v) for v in args.masks.split(",") if v} | {HEADLINE_M}, reverse=True))
 
     import torch
 
@@ -102,7 +107,7 @@ def main() -> int:
         d_w, masks = copies[c]
         idx = torch.empty((T, k), dtype=torch.int32, device=dev)
         gate = torch.empty((T, k), dtype=torch.float32, device=dev)
-        tm.team_moe_route(cfg, d_x, T, d_w["router"], masks[M], idx, gate, None)
+        tm.team_moe_route(cfg, d_x, T, d_w["router"], masks[M], idx, gate, None, ws)
         torch.cuda.synchronize()
         v = idx.cpu().numpy()
         return int(np.unique(v[v >= 0]).size)
@@ -133,7 +138,7 @@ def main() -> int:
         evs = []
         for i in range(warmup + steps):
             d_w, masks = copies[i % args.copies]
-            tm.team_moe_route(cfg, d_x, T, d_w["router"], masks[M], st_idx, st_gate, None)
+            tm.team_moe_route(cfg, d_x, T, d_w["router"], masks[M], st_idx, st_gate, None, ws)
             tm.team_moe_build_dispatch(cfg, st_idx, T, st_off, st_sorted, st_inv, st_act, st_nact, ws)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)

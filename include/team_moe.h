@@ -75,12 +75,14 @@ int team_moe_workspace_size(const team_moe_config* cfg, size_t* bytes);
  *   topk_idx[t, 0..k_eff)  = the k_eff experts of S with the largest logit, largest first, ties to the lower
  *                            id; remaining slots are -1
  *   topk_gate[t, s]        = routing weight of slot s (see cfg->renormalize); 0 in padded slots
- *   logits_out [T,E]       = optional copy of the logits (NULL to skip)
- * An all-zero mask gives topk_idx = -1 and gates 0 everywhere.
+ *   logits_out [T,E]       = the logits, if the caller wants them; with NULL they are kept in `workspace`
+ *                            (required then: team_moe_workspace_size bytes; may be NULL when logits_out is given)
+ * An all-zero mask gives topk_idx = -1 and gates 0 everywhere.  A NaN logit is never selected.
  */
 int team_moe_route(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router,
                    const uint8_t* expert_mask /* [E] bytes or NULL */, int32_t* topk_idx /* [T,k] */,
-                   float* topk_gate /* [T,k] */, float* logits_out /* [T,E] or NULL */, void* stream);
+                   float* topk_gate /* [T,k] */, float* logits_out /* [T,E] or NULL */, void* workspace,
+                   size_t ws_bytes, void* stream);
 
 /*
  * Token-to-expert grouping of the routing table (the paper leaves this implicit: "each activated expert is

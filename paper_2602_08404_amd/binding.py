@@ -50,7 +50,7 @@ def lib() -> C.CDLL:
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         cfgp = C.POINTER(Config)
         L.team_moe_workspace_size.argtypes = [cfgp, C.POINTER(sz)]
-        L.team_moe_route.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp]
+        L.team_moe_route.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_build_dispatch.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_expert_ffn.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_combine.argtypes = [cfgp, vp, vp, vp, i32, vp, vp]
@@ -87,9 +87,12 @@ def team_moe_workspace_size(cfg: Config) -> int:
     return int(n.value)
 
 
-def team_moe_route(cfg: Config, x, T: int, w_router, expert_mask, topk_idx, topk_gate, logits_out=None, stream=None) -> None:
+def team_moe_route(cfg: Config, x, T: int, w_router, expert_mask, topk_idx, topk_gate, logits_out=None, workspace=None,
+                   stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().team_moe_route(C.byref(cfg), _ptr(x), T, _ptr(w_router), _ptr(expert_mask), _ptr(topk_idx), _ptr(topk_gate),
-                                _ptr(logits_out), stream if stream is not None else _stream()), "team_moe_route")
+                                _ptr(logits_out), _ptr(workspace), ws_bytes, stream if stream is not None else _stream()),
+           "team_moe_route")
 
 
 def team_moe_build_dispatch(cfg: Config, topk_idx, T: int, expert_offsets, sorted_token, inv_pos, active_experts, n_active,

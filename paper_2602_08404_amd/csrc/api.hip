@@ -47,7 +47,7 @@ Dims dims_of(const team_moe_config* c, int32_t T) {
 // Workspace layout, sized for max_tokens.  The expert FFN's scratch (control block, h) comes first so that
 // team_moe_expert_ffn and team_moe_layer_forward agree on where it is.
 struct Layout {
-    size_t ctrl, h, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, total;
+    size_t ctrl, h, logits, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, total;
 };
 Layout layout_of(const team_moe_config* c) {
     const size_t A = (size_t)c->max_tokens * c->top_k;
@@ -56,6 +56,7 @@ Layout layout_of(const team_moe_config* c) {
     size_t off = 0;
     L.ctrl = off;         off += align256(team::ffn_ctrl_bytes());
     L.h = off;            off += align256(A * c->inter * elem);
+    L.logits = off;       off += align256((size_t)c->max_tokens * c->num_experts * 4);
     L.topk_idx = off;     off += align256(A * 4);
     L.topk_gate = off;    off += align256(A * 4);
     L.offsets = off;      off += align256(((size_t)c->num_experts + 1) * 4);
@@ -100,15 +101,23 @@ int team_moe_workspace_size(const team_moe_config* cfg, size_t* bytes) {
 }
 
 int team_moe_route(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const uint8_t* expert_mask,
-                   int32_t* topk_idx, float* topk_gate, float* logits_out, void* stream) {
+                   int32_t* topk_idx, float* topk_gate, float* logits_out, void* workspace, size_t ws_bytes, void* stream) {
     int st = check_cfg(cfg);
     if (st != TEAM_OK) return st;
     if ((st = check_T(cfg, T)) != TEAM_OK) return st;
     if (!x || !w_router || !topk_idx || !topk_gate) return TEAM_ERR_INVALID_ARG;
     if (!aligned16(x) || !aligned16(w_router)) return TEAM_ERR_INVALID_ARG;
     if (cfg->hidden % (cfg->dtype == TEAM_BF16 ? 8 : 4) != 0) return TEAM_ERR_UNSUPPORTED;
+    float* logits = logits_out;
+    if (!logits) {                       // the scores live in the workspace when the caller does not want them
+        const Layout L = layout_of(cfg);
+        if (!workspace || !aligned16(workspace) || ws_bytes < L.topk_idx) return TEAM_ERR_WORKSPACE;
+        logits = (float*)((char*)workspace + L.logits);
+    } else if (!aligned16(logits)) {
+        return TEAM_ERR_INVALID_ARG;
+    }
     clear_stale_error();
-    return hip_status(team::launch_route(dims_of(cfg, T), x, w_router, expert_mask, topk_idx, topk_gate, logits_out, (hipStream_t)stream));
+    return hip_status(team::launch_route(dims_of(cfg, T), x, w_router, expert_mask, topk_idx, topk_gate, logits, (hipStream_t)stream));
 }
 
 int team_moe_build_dispatch(const team_moe_config* cfg, const int32_t* topk_idx, int32_t T, int32_t* expert_offsets,
@@ -122,7 +131,7 @@ int team_moe_build_dispatch(const team_moe_config* cfg, const int32_t* topk_idx,
     team::CtrlZero cz{nullptr, 0, 0};
     if (workspace) {
         const Layout L = layout_of(cfg);
-        if (!aligned16(workspace) || ws_bytes < L.topk_idx) return TEAM_ERR_WORKSPACE;
+        if (!aligned16(workspace) || ws_bytes < L.logits) return TEAM_ERR_WORKSPACE;
         if (cfg->dtype == TEAM_BF16) cz = team::ffn_ctrl_zero((char*)workspace + L.ctrl);
     }
     clear_stale_error();
@@ -141,7 +150,7 @@ int team_moe_expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, co
     if (!aligned16(x) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) || !aligned16(expert_out))
         return TEAM_ERR_INVALID_ARG;
     const Layout L = layout_of(cfg);
-    if (!workspace || !aligned16(workspace) || ws_bytes < L.topk_idx /* = end of the control block + h segments */) return TEAM_ERR_WORKSPACE;
+    if (!workspace || !aligned16(workspace) || ws_bytes < L.logits /* = end of the control block + h segments */) return TEAM_ERR_WORKSPACE;
     clear_stale_error();
     return run_ffn(cfg, dims_of(cfg, T), x, expert_offsets, sorted_token, active_experts, n_active, w_gate, w_up, w_down, expert_out,
                    (char*)workspace + L.ctrl, (char*)workspace + L.h, (hipStream_t)stream);
@@ -181,7 +190,8 @@ int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T,
     const Dims d = dims_of(cfg, T);
     hipStream_t s = (hipStream_t)stream;
     clear_stale_error();
-    if ((st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, nullptr, s))) != TEAM_OK) return st;
+    if ((st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, (float*)(ws + L.logits), s))) != TEAM_OK)
+        return st;
     // the dispatch kernel also clears the FFN's control block
     const team::CtrlZero cz = cfg->dtype == TEAM_BF16 ? team::ffn_ctrl_zero(ws + L.ctrl) : team::CtrlZero{nullptr, 0, 0};
     if ((st = hip_status(team::launch_dispatch(d, topk_idx, offsets, sorted_token, inv_pos, active, n_active, cz, s))) != TEAM_OK)

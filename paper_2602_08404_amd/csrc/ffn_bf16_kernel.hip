@@ -150,6 +150,9 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
             const int tr_k = (int)(tr_na + tr_nb);
             if (tid == 0 && blockIdx.x < 2048 && tr_k < 12) { g_ffn_items[blockIdx.x][0][tr_k] = tr_i0; g_ffn_items[blockIdx.x][2][tr_k] = (step < n_a) ? (step < n_a ? a_begin + step : b_begin + step - n_a) : 1000000 + (step < n_a ? a_begin + step : b_begin + step - n_a); }
 #endif
+#ifdef TEAM_FFN_PRIO
+            if (((step + (blockIdx.x >= (unsigned)G / 2 ? 1 : 0)) & 1)) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(0);
+#endif
             const bool is_a = step < n_a;
             const int li = is_a ? a_begin + step : b_begin + (step - n_a);
             const int tiles = is_a ? TILES_A : TILES_B;
@@ -259,7 +262,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                     if (tid == 0) {
                         int spins = 0;
                         while (__hip_atomic_load(&ctrl->done[a][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < TILES_A) {
-                            __builtin_amdgcn_s_sleep(32);     // ~1 us between polls: many workgroups poll the same few counters
+                            __builtin_amdgcn_s_sleep(8);      // ~0.2 us between polls; the counters sit in different memory channels
                             if (++spins > spin_limit) {          // cannot happen with a control block zeroed before the launch
                                 ctrl->error = 1;
                                 break;

@@ -12,8 +12,9 @@ struct Dims {
     int renormalize;
 };
 
+// logits: [T,E] floats, required (scratch of the selection kernel and, for the caller, the router scores).
 hipError_t launch_route(const Dims& d, const void* x, const void* w_router, const uint8_t* mask, int32_t* topk_idx,
-                        float* topk_gate, float* logits_out, hipStream_t s);
+                        float* topk_gate, float* logits, hipStream_t s);
 // Words of the FFN control block that must be zero before an FFN launch: `header` leading words, then one word
 // every `stride` words for each of the E expert slots.
 struct CtrlZero {

@@ -1,17 +1,25 @@
 // Router restricted to the activated-expert set: logits, masked top-k, gates.
 // Paper: Algorithm 1, "Router(C, E_A)" (second-round routing confined to the necessary experts) and, with no
-// mask, the first-round router over E_0.  One workgroup per token: every wavefront scores a share of the
-// experts (dot products reduced across lanes; the loads of a group of experts are issued together so the
-// kernel pays the memory latency once per group, not once per expert), then wavefront 0 selects the k best
-// allowed experts with cross-lane arg-max and turns the selected logits into gates with a cross-lane softmax.
+// mask, the first-round router over E_0.  Two small latency-bound kernels:
+//   logits : one workgroup per (token, group of 32 experts); a wavefront scores 8 experts with all their loads
+//            in flight together (one memory round trip), fp32 FMA, cross-lane sums without LDS traffic.
+//            Splitting the experts of a token over several compute units keeps the router matrix traffic per
+//            compute unit small (the whole matrix through one compute unit costs more than the rest together).
+//   select : one workgroup per token, one thread per expert.  The slot of an expert is its rank = the number of
+//            allowed experts that beat it (larger logit, or equal logit and lower id): every thread counts its
+//            own rank against the logits in LDS, so there is no serial arg-max loop; experts with rank < k write
+//            themselves into their slot.  One wavefront then turns the selected logits into gates.
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
 namespace team {
 
-constexpr int ROUTE_THREADS = 512;
-constexpr int ROUTE_WAVES = ROUTE_THREADS / WAVE;
+constexpr int LOGIT_THREADS = 256;
+constexpr int LOGIT_WAVES = LOGIT_THREADS / WAVE;
+constexpr int EG = 8;                                   // experts per wavefront
+constexpr int LOGIT_GROUP = LOGIT_WAVES * EG;           // experts per workgroup
 constexpr int MAX_E = 256;
+constexpr int SELECT_THREADS = MAX_E;
 
 template <typename ST> struct Chunk;
 template <> struct Chunk<uint16_t> { static constexpr int N = 8; };
@@ -30,146 +38,143 @@ template <> __device__ __forceinline__ void unpack_chunk<float>(const uint4& v, 
     out[0] = __uint_as_float(v.x); out[1] = __uint_as_float(v.y); out[2] = __uint_as_float(v.z); out[3] = __uint_as_float(v.w);
 }
 
-// Selection key: larger logit wins, equal logits go to the lower expert id.  The float is mapped to an
-// unsigned integer with the same order; the id is stored complemented in the low word; 0 = no candidate.
-__device__ __forceinline__ unsigned long long select_key(float v, int e) {
-    const uint32_t b = __float_as_uint(v + 0.f);      // -0 and +0 compare equal: both become +0
-    const uint32_t ord = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-    return ((unsigned long long)ord << 32) | (uint32_t)(0xffffffffu - (uint32_t)e);
-}
-__device__ __forceinline__ int key_expert(unsigned long long key) { return (int)(0xffffffffu - (uint32_t)key); }
-
 template <typename ST>
-__global__ __launch_bounds__(ROUTE_THREADS) void route_kernel(const ST* __restrict__ x, const ST* __restrict__ w_router,
-                                                              const uint8_t* __restrict__ mask, int32_t* __restrict__ topk_idx,
-                                                              float* __restrict__ topk_gate, float* __restrict__ logits_out,
-                                                              int H, int E, int k, int renormalize) {
+__global__ __launch_bounds__(LOGIT_THREADS) void route_logits_kernel(const ST* __restrict__ x, const ST* __restrict__ w_router,
+                                                                     float* __restrict__ logits, int H, int E) {
     constexpr int CN = Chunk<ST>::N;
-    __shared__ float s_logit[MAX_E];
-    const int t = blockIdx.x;
+    constexpr int XC = 4;          // chunks of the token row per lane per block of 256 chunks
+    const int t = blockIdx.y;
     const int lane = threadIdx.x & (WAVE - 1);
     const int wave = threadIdx.x / WAVE;
-    const int n_chunks = H / CN;                 // chunks of CN consecutive elements; lane takes chunk lane, lane+64, ...
+    const int n_chunks = H / CN;   // chunks of CN consecutive elements; lane takes chunk lane, lane+64, ...
     const ST* xt = x + (size_t)t * H;
+    const int e0 = blockIdx.x * LOGIT_GROUP + wave;     // this wavefront: experts e0, e0+4, ..., e0+28
 
-    // ---- logits: fixed summation order (per lane ascending, then butterfly) -> deterministic.
-    // Wavefront w scores experts w, w+8, ...; EG of them per pass with all their loads in flight together.
-    constexpr int EG = 8;          // experts per pass
-    constexpr int XC = 4;          // chunks of the token row per lane per block of 256 chunks
-    for (int e0 = wave; e0 < E; e0 += ROUTE_WAVES * EG) {
-        float acc[EG];
+    // fixed summation order (per lane ascending, then the cross-lane tree) -> deterministic
+    float acc[EG];
 #pragma unroll
-        for (int g = 0; g < EG; ++g) acc[g] = 0.f;
-        for (int cb = 0; cb < n_chunks; cb += WAVE * XC) {
-            // 16-byte packed chunks stay packed in registers until they are multiplied
-            uint4 xp[XC], wp[EG][XC];
+    for (int g = 0; g < EG; ++g) acc[g] = 0.f;
+    for (int cb = 0; cb < n_chunks; cb += WAVE * XC) {
+        // 16-byte packed chunks stay packed in registers until they are multiplied
+        uint4 xp[XC], wp[EG][XC];
 #pragma unroll
-            for (int j = 0; j < XC; ++j) {
-                const int c = cb + j * WAVE + lane;
-                xp[j] = c < n_chunks ? *reinterpret_cast<const uint4*>(xt + (size_t)c * CN) : make_uint4(0u, 0u, 0u, 0u);
-            }
-#pragma unroll
-            for (int g = 0; g < EG; ++g) {
-                const int e = e0 + g * ROUTE_WAVES;
-                const ST* wr = w_router + (size_t)(e < E ? e : 0) * H;
-#pragma unroll
-                for (int j = 0; j < XC; ++j) {
-                    const int c = cb + j * WAVE + lane;
-                    wp[g][j] = (c < n_chunks && e < E) ? *reinterpret_cast<const uint4*>(wr + (size_t)c * CN) : make_uint4(0u, 0u, 0u, 0u);
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < XC; ++j) {
-                float xv[CN];
-                unpack_chunk<ST>(xp[j], xv);
-#pragma unroll
-                for (int g = 0; g < EG; ++g) {
-                    float wv[CN];
-                    unpack_chunk<ST>(wp[g][j], wv);
-#pragma unroll
-                    for (int i = 0; i < CN; ++i) acc[g] = fmaf(xv[i], wv[i], acc[g]);
-                }
-            }
+        for (int j = 0; j < XC; ++j) {
+            const int c = cb + j * WAVE + lane;
+            xp[j] = c < n_chunks ? *reinterpret_cast<const uint4*>(xt + (size_t)c * CN) : make_uint4(0u, 0u, 0u, 0u);
         }
 #pragma unroll
         for (int g = 0; g < EG; ++g) {
-            const float v = wave_sum(acc[g]);
-            const int e = e0 + g * ROUTE_WAVES;
-            if (lane == 0 && e < E) {
-                s_logit[e] = v;
-                if (logits_out) logits_out[(size_t)t * E + e] = v;
+            const int e = e0 + g * LOGIT_WAVES;
+            const ST* wr = w_router + (size_t)(e < E ? e : 0) * H;
+#pragma unroll
+            for (int j = 0; j < XC; ++j) {
+                const int c = cb + j * WAVE + lane;
+                wp[g][j] = (c < n_chunks && e < E) ? *reinterpret_cast<const uint4*>(wr + (size_t)c * CN) : make_uint4(0u, 0u, 0u, 0u);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < XC; ++j) {
+            float xv[CN];
+            unpack_chunk<ST>(xp[j], xv);
+#pragma unroll
+            for (int g = 0; g < EG; ++g) {
+                float wv[CN];
+                unpack_chunk<ST>(wp[g][j], wv);
+#pragma unroll
+                for (int i = 0; i < CN; ++i) acc[g] = fmaf(xv[i], wv[i], acc[g]);
             }
         }
     }
-    __syncthreads();
-    if (wave != 0) return;
+#pragma unroll
+    for (int g = 0; g < EG; ++g) {
+        const float v = wave_sum(acc[g]);
+        const int e = e0 + g * LOGIT_WAVES;
+        if (lane == 0 && e < E) logits[(size_t)t * E + e] = v;
+    }
+}
 
-    // ---- selection by wavefront 0: lane owns experts lane, lane+64, lane+128, lane+192
-    constexpr int PER_LANE = MAX_E / WAVE;
-    float v[PER_LANE];
-    bool ok[PER_LANE];
-#pragma unroll
-    for (int j = 0; j < PER_LANE; ++j) {
-        int e = lane + j * WAVE;
-        ok[j] = e < E && (mask == nullptr || mask[e] != 0);
-        v[j] = e < E ? s_logit[e] : 0.f;
+// Selection key: larger logit wins, equal logits go to the lower expert id.  The float is mapped to an unsigned
+// integer with the same order; the id is stored complemented in the low word; 0 = not a candidate.
+__device__ __forceinline__ unsigned long long select_key(float v, int e) {
+    const uint32_t b = __float_as_uint(v);
+    const uint32_t ord = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    return ((unsigned long long)ord << 32) | (uint32_t)(0xffffffffu - (uint32_t)e);
+}
+
+__global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(const float* __restrict__ logits, const uint8_t* __restrict__ mask,
+                                                                      int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate,
+                                                                      int E, int k, int renormalize) {
+    __shared__ __attribute__((aligned(16))) unsigned long long s_key[MAX_E];   // 0 for experts that are not candidates
+    __shared__ float s_all[MAX_E];                                              // every logit (for the full softmax)
+    __shared__ float s_sel_logit[16];
+    __shared__ int32_t s_sel_idx[16];
+    __shared__ int32_t s_count[SELECT_THREADS / WAVE];
+    const int t = blockIdx.x;
+    const int e = threadIdx.x;
+    const int lane = e & (WAVE - 1);
+    float v = 0.f;
+    bool ok = false;
+    if (e < E) {
+        v = logits[(size_t)t * E + e] + 0.f;                         // -0 -> +0 so that equal logits compare equal
+        ok = (mask == nullptr || mask[e] != 0) && v == v;            // a NaN logit is never selected
     }
-    float full_max = 0.f, full_den = 1.f;
-    if (!renormalize) {                         // softmax denominator over all E experts
-        float m = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < PER_LANE; ++j) if (lane + j * WAVE < E) m = fmaxf(m, v[j]);
-        m = wave_max(m);
-        float dsum = 0.f;
-#pragma unroll
-        for (int j = 0; j < PER_LANE; ++j) if (lane + j * WAVE < E) dsum += expf(v[j] - m);
-        full_max = m;
-        full_den = wave_sum(dsum);
+    const unsigned long long my_key = ok ? select_key(v, e) : 0ull;
+    if (e < 16) { s_sel_idx[e] = -1; s_sel_logit[e] = 0.f; }
+    s_all[e] = e < E ? v : -INFINITY;
+    s_key[e] = my_key;
+    const unsigned long long ok_lanes = __ballot(ok);
+    if (lane == 0) s_count[e / WAVE] = __popcll(ok_lanes);
+    __syncthreads();
+    if (ok) {                                                         // rank = number of candidates that beat this one
+        int rank = 0;
+        const int n2 = (E + 1) / 2;
+#pragma unroll 8
+        for (int j2 = 0; j2 < n2; ++j2) {
+            const ulonglong2 o = *reinterpret_cast<const ulonglong2*>(s_key + 2 * j2);   // same address in all lanes: broadcast
+            rank += (o.x > my_key) + (o.y > my_key);
+        }
+        if (rank < k) { s_sel_idx[rank] = e; s_sel_logit[rank] = v; }
     }
-    float my_sel_logit = 0.f;     // lane s keeps the logit of slot s
-    int my_sel_idx = -1;
-    int k_eff = 0;
-    for (int s = 0; s < k; ++s) {
-        unsigned long long best = 0;                     // NaN logits are never selected (their key is not formed)
+    __syncthreads();
+    if (e >= WAVE) return;
+    // ---- gates by wavefront 0: lane s owns slot s
+    int n_allowed = 0;
 #pragma unroll
-        for (int j = 0; j < PER_LANE; ++j)
-            if (ok[j] && v[j] == v[j]) {
-                const unsigned long long key = select_key(v[j], lane + j * WAVE);
-                best = key > best ? key : best;
-            }
-        best = wave_max_u64(best);
-        if (best == 0) break;                            // allowed set exhausted: k_eff = |S| < k
-        const int bi = key_expert(best);
-        ++k_eff;
-        if (lane == s) { my_sel_logit = s_logit[bi]; my_sel_idx = bi; }
-#pragma unroll
-        for (int j = 0; j < PER_LANE; ++j) if (lane + j * WAVE == bi) ok[j] = false;
-    }
-    // ---- gates
+    for (int w = 0; w < SELECT_THREADS / WAVE; ++w) n_allowed += s_count[w];
+    const int k_eff = min(k, n_allowed);
+    const float my_logit = lane < 16 ? s_sel_logit[lane] : 0.f;
     float gate = 0.f;
     if (renormalize) {
-        const float m = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_sel_logit), 0));
-        float w = lane < k_eff ? expf(my_sel_logit - m) : 0.f;
-        float den = wave_sum(w);
+        const float m = s_sel_logit[0];
+        const float w = lane < k_eff ? expf(my_logit - m) : 0.f;
+        const float den = wave_sum(w);
         gate = lane < k_eff ? w / den : 0.f;
-    } else {
-        gate = lane < k_eff ? expf(my_sel_logit - full_max) / full_den : 0.f;
+    } else {                                                         // selected entries of the softmax over all E experts
+        float m = -INFINITY;
+        for (int j = lane; j < E; j += WAVE) m = fmaxf(m, s_all[j]);
+        m = wave_max(m);
+        float dsum = 0.f;
+        for (int j = lane; j < E; j += WAVE) dsum += expf(s_all[j] - m);
+        const float den = wave_sum(dsum);
+        gate = lane < k_eff ? expf(my_logit - m) / den : 0.f;
     }
     if (lane < k) {
-        topk_idx[(size_t)t * k + lane] = lane < k_eff ? my_sel_idx : -1;
+        topk_idx[(size_t)t * k + lane] = lane < k_eff ? s_sel_idx[lane] : -1;
         topk_gate[(size_t)t * k + lane] = gate;
     }
 }
 
 hipError_t launch_route(const Dims& d, const void* x, const void* w_router, const uint8_t* mask, int32_t* topk_idx,
-                        float* topk_gate, float* logits_out, hipStream_t s) {
-    dim3 grid(d.T), block(ROUTE_THREADS);
+                        float* topk_gate, float* logits, hipStream_t s) {
+    dim3 grid((d.E + LOGIT_GROUP - 1) / LOGIT_GROUP, d.T), block(LOGIT_THREADS);
     if (d.bf16)
-        hipLaunchKernelGGL(route_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)x, (const uint16_t*)w_router, mask,
-                           topk_idx, topk_gate, logits_out, d.H, d.E, d.k, d.renormalize);
+        hipLaunchKernelGGL(route_logits_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)x, (const uint16_t*)w_router, logits, d.H, d.E);
     else
-        hipLaunchKernelGGL(route_kernel<float>, grid, block, 0, s, (const float*)x, (const float*)w_router, mask, topk_idx,
-                           topk_gate, logits_out, d.H, d.E, d.k, d.renormalize);
+        hipLaunchKernelGGL(route_logits_kernel<float>, grid, block, 0, s, (const float*)x, (const float*)w_router, logits, d.H, d.E);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(route_select_kernel, dim3(d.T), dim3(SELECT_THREADS), 0, s, logits, mask, topk_idx, topk_gate, d.E, d.k,
+                       d.renormalize);
     return hipGetLastError();
 }
 

@@ -70,8 +70,9 @@ def gpu_route(case: Case, mask: Optional[np.ndarray], want_logits=True):
     idx = torch.full((s.T, s.k), -7, dtype=torch.int32, device=DEV)
     gate = torch.full((s.T, s.k), -7.0, dtype=torch.float32, device=DEV)
     logits = torch.empty((s.T, s.E), dtype=torch.float32, device=DEV) if want_logits else None
+    ws = None if want_logits else torch.empty(tm.team_moe_workspace_size(case.cfg), dtype=torch.uint8, device=DEV)
     d_mask = None if mask is None else torch.from_numpy(mask).to(DEV)
-    tm.team_moe_route(case.cfg, case.d_x, s.T, case.d_w["router"], d_mask, idx, gate, logits)
+    tm.team_moe_route(case.cfg, case.d_x, s.T, case.d_w["router"], d_mask, idx, gate, logits, ws)
     torch.cuda.synchronize()
     return idx.cpu().numpy(), gate.cpu().numpy(), (logits.cpu().numpy() if want_logits else None)
 

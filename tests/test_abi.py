@@ -66,16 +66,19 @@ def test_bad_call_arguments_are_rejected_before_any_launch():
     odd = C.c_void_p(0x1004)
     st = 0
     # NULL required pointers
-    assert lib.team_moe_route(C.byref(cfg), None, 8, fake, None, fake, fake, None, st) == -1
+    assert lib.team_moe_route(C.byref(cfg), None, 8, fake, None, fake, fake, None, None, 0, st) == -1
     assert lib.team_moe_build_dispatch(C.byref(cfg), None, 8, fake, fake, fake, fake, fake, None, 0, st) == -1
     assert lib.team_moe_combine(C.byref(cfg), fake, fake, None, 8, fake, st) == -1
     assert lib.team_moe_expert_ffn(C.byref(cfg), fake, 8, fake, fake, fake, fake, fake, fake, None, fake, fake, 1 << 30, st) == -1
     assert lib.team_moe_layer_forward(C.byref(cfg), fake, 8, fake, fake, fake, fake, None, None, fake, 1 << 30, st) == -1
     # token count out of range
-    assert lib.team_moe_route(C.byref(cfg), fake, 0, fake, None, fake, fake, None, st) == -1
-    assert lib.team_moe_route(C.byref(cfg), fake, 33, fake, None, fake, fake, None, st) == -1
+    assert lib.team_moe_route(C.byref(cfg), fake, 0, fake, None, fake, fake, None, None, 0, st) == -1
+    assert lib.team_moe_route(C.byref(cfg), fake, 33, fake, None, fake, fake, None, None, 0, st) == -1
+    # no logits_out and no workspace to keep the scores in
+    assert lib.team_moe_route(C.byref(cfg), fake, 8, fake, None, fake, fake, None, None, 0, st) == -3
+    assert lib.team_moe_route(C.byref(cfg), fake, 8, fake, None, fake, fake, None, fake, 64, st) == -3
     # misaligned tensor
-    assert lib.team_moe_route(C.byref(cfg), odd, 8, fake, None, fake, fake, None, st) == -1
+    assert lib.team_moe_route(C.byref(cfg), odd, 8, fake, None, fake, fake, None, None, 0, st) == -1
     # workspace missing / too small / misaligned
     assert lib.team_moe_layer_forward(C.byref(cfg), fake, 8, fake, fake, fake, fake, None, fake, None, 0, st) == -3
     assert lib.team_moe_layer_forward(C.byref(cfg), fake, 8, fake, fake, fake, fake, None, fake, fake, 1024, st) == -3
@@ -86,7 +89,7 @@ def test_bad_call_arguments_are_rejected_before_any_launch():
     assert lib.team_moe_workspace_size(C.byref(cfg), None) == -1
     bad = tm.make_config(2048, 768, 128, 8, "bf16", 1, 32)
     bad.dtype = 7
-    assert lib.team_moe_route(C.byref(bad), fake, 8, fake, None, fake, fake, None, st) == -1
+    assert lib.team_moe_route(C.byref(bad), fake, 8, fake, None, fake, fake, None, None, 0, st) == -1
 
 
 def test_product_package_does_not_use_the_oracle():

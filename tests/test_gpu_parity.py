@@ -123,6 +123,14 @@ def test_cfg2_superset_invariance(cfg2_case):
     assert torch.equal(t0, t1)
 
 
+def test_cfg2_route_scores_in_workspace_or_returned(cfg2_case):
+    """The router keeps its scores in the workspace when the caller does not ask for them: same routing table."""
+    mask = c12_mask(cfg2_case, 32)
+    a = hz.gpu_route(cfg2_case, mask, want_logits=True)
+    b = hz.gpu_route(cfg2_case, mask, want_logits=False)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
 def test_cfg2_no_renormalisation(cfg2_case):
     s = gen.scaled(gen.CFG2, renormalize=0)
     case = hz.Case.make(s, cfg2_case.x, cfg2_case.w, cfg2_case.wf, cfg2_case.d_w)
