@@ -150,9 +150,6 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
             const int tr_k = (int)(tr_na + tr_nb);
             if (tid == 0 && blockIdx.x < 2048 && tr_k < 12) { g_ffn_items[blockIdx.x][0][tr_k] = tr_i0; g_ffn_items[blockIdx.x][2][tr_k] = (step < n_a) ? (step < n_a ? a_begin + step : b_begin + step - n_a) : 1000000 + (step < n_a ? a_begin + step : b_begin + step - n_a); }
 #endif
-#ifdef TEAM_FFN_PRIO
-            if (((step + (blockIdx.x >= (unsigned)G / 2 ? 1 : 0)) & 1)) __builtin_amdgcn_s_setprio(2); else __builtin_amdgcn_s_setprio(0);
-#endif
             const bool is_a = step < n_a;
             const int li = is_a ? a_begin + step : b_begin + (step - n_a);
             const int tiles = is_a ? TILES_A : TILES_B;
