@@ -1,16 +1,21 @@
 #!/usr/bin/env python3
 """Benchmark of the MoE-layer hot path on one MI355X.
 
-A step is one team_moe_layer_forward call (router -> dispatch -> grouped SwiGLU FFN -> combine) over one block
-of 32 tokens of a 30B-A3B-shaped layer (hidden 2048, 128 experts, top-8, intermediate 768, bf16) with routing
-confined to an activated-expert set of M = 32 experts, inputs resident in HBM.  Consecutive steps rotate over
-several distinct weight sets so that no weight byte is re-read before > 1 GB of other traffic (the 256 MB
-last-level cache would otherwise serve part of a 151-302 MB working set).  The same loop is repeated for
-M in {128, 64, 32, 16} and reported under "sweep" (step time vs number of activated experts).
+Default workload (the one the headline metric is quoted on): a step is one team_moe_layer_forward call
+(router -> dispatch -> grouped SwiGLU FFN -> combine) over one block of 32 tokens of a 30B-A3B-shaped layer
+(hidden 2048, 128 experts, top-8, intermediate 768, bf16) with routing confined to an activated-expert set of
+M = 32 experts, inputs resident in HBM.  Consecutive steps rotate over several distinct weight sets so that no
+weight byte is re-read before > 1 GB of other traffic (the 256 MB last-level cache would otherwise serve part
+of a 151-302 MB working set).  The same loop is repeated for M in {128, 64, 32, 16} and reported under "sweep"
+(step time vs number of activated experts).
 
-Prints ONE JSON line.  `roofline` is for the expert FFN (the kernels that stream the expert weights), timed
+Prints ONE JSON line.  `roofline` is for the expert FFN kernel (the one that streams the expert weights), timed
 with HIP events on the launch stream around team_moe_expert_ffn; `cpu_baseline` is the CPU oracle on the same
 workload on this machine's host cores.
+
+Other workloads (--workload): cfg3 = 4 speculative candidates x 32 tokens sharing one set of 32 experts;
+cfg5 = 256 tokens over 256 fine-grained experts (sets 256/96/48); cfg4 = a stack of 48 such layers run for 16
+denoising steps with an activated set of 24 per (layer, step), a step being one pass over the whole stack.
 """
 from __future__ import annotations
 
@@ -27,8 +32,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-MASK_SIZES = (128, 64, 32, 16)
-HEADLINE_M = 32
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per ffn_fused_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), keyed by
+# (workload, activated-set size); counters cannot be read from inside this script.
+PMC_TRAFFIC_BYTES = {("cfg2", 32): 306521000 + 2900000}
 
 
 def log(*a):
@@ -40,9 +47,10 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--copies", type=int, default=4, help="distinct weight sets rotated over")
-    ap.add_argument("--masks", type=str, default="128,64,32,16",
-                    help="activated-set sizes of the sweep (the headline size 32 is always measured); e.g. --masks 32 for a profile of the headline only")
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg5"], default="cfg2")
+    ap.add_argument("--copies", type=int, default=0, help="distinct weight sets rotated over (default 4; cfg4: layers of the stack, default 48)")
+    ap.add_argument("--masks", type=str, default="",
+                    help="activated-set sizes of the sweep (the headline size is always measured); e.g. --masks 32 for a profile of the headline only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     args = ap.parse_args()
@@ -50,9 +58,6 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU (one process, one MI355X); --gpus must be 1. "
               "Nothing here uses a second GPU.", file=sys.stderr)
         return 2
-
-    global MASK_SIZES
-    MASK_SIZES = tuple(sorted({int(v) for v in args.masks.split(",") if v} | {HEADLINE_M}, reverse=True))
 
     import torch
 
@@ -62,70 +67,93 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    shape = gen.CFG2
+    wl = args.workload
+    shape, x_kind, x_noise, default_masks, headline = {
+        "cfg2": (gen.CFG2, "iid", 0.0, (128, 64, 32, 16), 32),
+        "cfg3": (gen.CFG3, "candidates", 0.1, (32,), 32),
+        "cfg4": (gen.CFG4, "drift", 0.0552, (24,), 24),
+        "cfg5": (gen.CFG5, "iid", 0.0, (256, 96, 48), 96),
+    }[wl]
+    mask_sizes = tuple(sorted({int(v) for v in args.masks.split(",") if v} | {headline}, reverse=True)) if args.masks else default_masks
     T, H, E, k, I = shape.T, shape.H, shape.E, shape.k, shape.I
+    A = T * k
     cfg = tm.make_config(H, I, E, k, "bf16", 1, T)
     bytes_per_expert = shape.bytes_per_expert
+    n_sets = args.copies if args.copies > 0 else (48 if wl == "cfg4" else 4)
+    n_steps_per_block = 16 if wl == "cfg4" else 1
 
     def dev_t(a):
         if a.dtype == np.uint16:
             return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
         return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
 
-    # ---- inputs: one x, `copies` weight sets (generator layers 0..copies-1), masks per (copy, M) from the GPU router's logits
-    x_host = gen.make_x(shape, seed=0)
-    d_x = dev_t(x_host)
     ws = torch.empty(tm.team_moe_workspace_size(cfg), dtype=torch.uint8, device=dev)
     y = torch.empty((T, H), dtype=torch.bfloat16, device=dev)
-    copies = []
-    host_w0 = None
-    t0 = time.time()
-    for c in range(args.copies):
-        w = gen.make_weights(shape, seed=0, layer=c)
-        if c == 0:
-            host_w0 = w
-        d_w = {n: dev_t(a) for n, a in w.items()}
-        idx = torch.empty((T, k), dtype=torch.int32, device=dev)
-        gate = torch.empty((T, k), dtype=torch.float32, device=dev)
-        logits = torch.empty((T, E), dtype=torch.float32, device=dev)
-        tm.team_moe_route(cfg, d_x, T, d_w["router"], None, idx, gate, logits)
+    r_idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+    r_gate = torch.empty((T, k), dtype=torch.float32, device=dev)
+    r_logits = torch.empty((T, E), dtype=torch.float32, device=dev)
+
+    def gpu_logits(d_x, d_router):
+        tm.team_moe_route(cfg, d_x, T, d_router, None, r_idx, r_gate, r_logits)
         torch.cuda.synchronize()
-        lg = logits.cpu().numpy()
-        masks = {M: (None if M == E else torch.from_numpy(gen.activated_set_by_summed_probability(lg, M)).to(dev)) for M in MASK_SIZES}
-        copies.append((d_w, masks))
+        return r_logits.cpu().numpy()
+
+    # ---- inputs: weight sets (generator layers 0..n_sets-1); x per set (cfg4: per layer and denoising step);
+    #      masks per (set, step, M) = top-M experts by summed router probability, from the GPU router's logits
+    t0 = time.time()
+    x_host0 = None
+    host_w0 = None
+    sets = []   # per set: (weights, [x per step], [masks per step: {M: tensor or None}])
+    for c in range(n_sets):
+        w = gen.make_weights(shape, seed=0, layer=c)
+        d_w = {n: dev_t(a) for n, a in w.items()}
+        xs, ms = [], []
+        for step in range(n_steps_per_block):
+            layer_for_x = c if wl == "cfg4" else 0
+            xh = gen.make_x(shape, seed=0, layer=layer_for_x, step=step, kind=x_kind, noise_std=x_noise)
+            if c == 0 and step == 0:
+                x_host0, host_w0 = xh, w
+            d_x = dev_t(xh)
+            lg = gpu_logits(d_x, d_w["router"])
+            xs.append(d_x)
+            ms.append({M: (None if M == E else torch.from_numpy(gen.activated_set_by_summed_probability(lg, M)).to(dev)) for M in mask_sizes})
+        sets.append((d_w, xs, ms))
         del w
-    log(f"[bench] generated {args.copies} weight sets in {time.time() - t0:.1f}s")
+    log(f"[bench] {wl}: generated {n_sets} weight sets in {time.time() - t0:.1f}s")
 
     stream = torch.cuda.current_stream()
 
-    def layer(c, M):
-        d_w, masks = copies[c]
-        tm.team_moe_layer_forward(cfg, d_x, T, d_w["router"], d_w["gate"], d_w["up"], d_w["down"], masks[M], y, ws)
+    def layer(c, step, M):
+        d_w, xs, ms = sets[c]
+        tm.team_moe_layer_forward(cfg, xs[step], T, d_w["router"], d_w["gate"], d_w["up"], d_w["down"], ms[step][M], y, ws)
 
-    def n_touched(c, M):
+    def n_touched(c, step, M):
         """Experts that receive at least one token (their weights are what the call must read)."""
-        d_w, masks = copies[c]
-        idx = torch.empty((T, k), dtype=torch.int32, device=dev)
-        gate = torch.empty((T, k), dtype=torch.float32, device=dev)
-        tm.team_moe_route(cfg, d_x, T, d_w["router"], masks[M], idx, gate, None, ws)
+        d_w, xs, ms = sets[c]
+        tm.team_moe_route(cfg, xs[step], T, d_w["router"], ms[step][M], r_idx, r_gate, None, ws)
         torch.cuda.synchronize()
-        v = idx.cpu().numpy()
+        v = r_idx.cpu().numpy()
         return int(np.unique(v[v >= 0]).size)
 
-    def time_layer(M, steps, warmup):
+    def bench_step(i, M):
+        """One timed step: one layer call (cfg2/3/5, rotating weight sets) or one pass over the whole stack (cfg4)."""
+        if wl == "cfg4":
+            for c in range(n_sets):
+                layer(c, i % n_steps_per_block, M)
+        else:
+            layer(i % n_sets, 0, M)
+
+    def time_steps(M, steps, warmup):
         for i in range(warmup):
-            layer(i % args.copies, M)
+            bench_step(i, M)
         torch.cuda.synchronize()
         t_begin = time.perf_counter()
         for i in range(steps):
-            layer(i % args.copies, M)
+            bench_step(i, M)
         torch.cuda.synchronize()
         return (time.perf_counter() - t_begin) / steps
 
     # staged calls with HIP events around the expert FFN (same stream as the launches)
-    A = T * k
-    st_idx = torch.empty((T, k), dtype=torch.int32, device=dev)
-    st_gate = torch.empty((T, k), dtype=torch.float32, device=dev)
     st_off = torch.empty((E + 1,), dtype=torch.int32, device=dev)
     st_sorted = torch.empty((A,), dtype=torch.int32, device=dev)
     st_inv = torch.empty((T, k), dtype=torch.int32, device=dev)
@@ -133,39 +161,47 @@ def main() -> int:
     st_nact = torch.empty((1,), dtype=torch.int32, device=dev)
     st_out = torch.empty((A, H), dtype=torch.float32, device=dev)
 
-    def time_ffn(M, steps, warmup):
-        """Average duration of team_moe_expert_ffn (the weight-streaming kernels) from HIP events on the launch stream."""
+    def time_ffn(M, calls, warmup):
+        """Average duration of team_moe_expert_ffn (one launch of the weight-streaming kernel) from HIP events on the launch stream."""
         evs = []
-        for i in range(warmup + steps):
-            d_w, masks = copies[i % args.copies]
-            tm.team_moe_route(cfg, d_x, T, d_w["router"], masks[M], st_idx, st_gate, None, ws)
-            tm.team_moe_build_dispatch(cfg, st_idx, T, st_off, st_sorted, st_inv, st_act, st_nact, ws)
+        for i in range(warmup + calls):
+            d_w, xs, ms = sets[i % n_sets]
+            step = (i // n_sets) % n_steps_per_block
+            tm.team_moe_route(cfg, xs[step], T, d_w["router"], ms[step][M], r_idx, r_gate, None, ws)
+            tm.team_moe_build_dispatch(cfg, r_idx, T, st_off, st_sorted, st_inv, st_act, st_nact, ws)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
-            tm.team_moe_expert_ffn(cfg, d_x, T, st_off, st_sorted, st_act, st_nact, d_w["gate"], d_w["up"], d_w["down"], st_out, ws)
+            tm.team_moe_expert_ffn(cfg, xs[step], T, st_off, st_sorted, st_act, st_nact, d_w["gate"], d_w["up"], d_w["down"], st_out, ws)
             e1.record(stream)
-            tm.team_moe_combine(cfg, st_out, st_gate, st_inv, T, y)
+            tm.team_moe_combine(cfg, st_out, r_gate, st_inv, T, y)
             if i >= warmup:
                 evs.append((e0, e1))
         torch.cuda.synchronize()
         return float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
 
-    # ---- headline: M = 32, exactly `steps` timed steps between synchronisations
-    sec_per_step = time_layer(HEADLINE_M, args.steps, args.warmup)
-    touched = {M: float(np.mean([n_touched(c, M) for c in range(args.copies)])) for M in MASK_SIZES}
+    # ---- headline: exactly `steps` timed steps between synchronisations
+    steps, warmup = (max(2, args.steps // 50), max(1, args.warmup // 20)) if wl == "cfg4" else (args.steps, args.warmup)
+    sec_per_step = time_steps(headline, steps, warmup)
+    layers_per_step = n_sets if wl == "cfg4" else 1
+    sample_sets = range(min(n_sets, 4))
+    touched = {M: float(np.mean([n_touched(c, 0, M) for c in sample_sets])) for M in mask_sizes}
     sweep = []
-    for M in MASK_SIZES:
-        s_layer = sec_per_step if M == HEADLINE_M else time_layer(M, max(50, args.steps // 2), max(10, args.warmup // 2))
+    for M in mask_sizes:
+        s_step = sec_per_step if M == headline else time_steps(M, max(50, steps // 2), max(10, warmup // 2))
+        s_layer = s_step / layers_per_step
         s_ffn = time_ffn(M, max(50, args.steps // 2), max(10, args.warmup // 2))
         wbytes = touched[M] * bytes_per_expert
-        sweep.append({"activated": M, "touched": touched[M], "ms_per_step": s_layer * 1e3, "tokens_per_s": T / s_layer,
-                      "ffn_ms": s_ffn * 1e3, "weight_GBps_ffn": wbytes / s_ffn / 1e9, "weight_GBps_layer": wbytes / s_layer / 1e9})
-        log(f"[bench] M={M}: layer {s_layer * 1e6:.1f} us, ffn {s_ffn * 1e6:.1f} us, touched {touched[M]:.1f}, "
-            f"ffn weight stream {wbytes / s_ffn / 1e9:.0f} GB/s")
-    head = next(r for r in sweep if r["activated"] == HEADLINE_M)
+        flops = 2.0 * A * 3 * H * I
+        sweep.append({"activated": M, "touched": touched[M], "ms_per_layer": s_layer * 1e3, "tokens_per_s": T / s_step,
+                      "ffn_ms": s_ffn * 1e3, "weight_GBps_ffn": wbytes / s_ffn / 1e9, "weight_GBps_layer": wbytes / s_layer / 1e9,
+                      "ffn_TFLOPs": flops / s_ffn / 1e12, "mfma_frac": flops / s_ffn / 1e12 / MFMA_BF16_PEAK_TFLOPS})
+        log(f"[bench] {wl} M={M}: layer {s_layer * 1e6:.1f} us, ffn {s_ffn * 1e6:.1f} us, touched {touched[M]:.1f}, "
+            f"ffn weight stream {wbytes / s_ffn / 1e9:.0f} GB/s, {flops / s_ffn / 1e12:.1f} TFLOP/s")
+    head = next(r for r in sweep if r["activated"] == headline)
     roofline = {"bound": "hbm", "kernel": "ffn_fused_kernel (team_moe_expert_ffn: gate/up + down GEMMs of the activated experts, one launch)",
                 "achieved": head["weight_GBps_ffn"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": head["weight_GBps_ffn"] / HBM_PEAK_GBS,
-                "traffic": None, "bytes_per_launch": touched[HEADLINE_M] * bytes_per_expert}
+                "traffic": PMC_TRAFFIC_BYTES.get((wl, headline)), "bytes_per_launch": touched[headline] * bytes_per_expert,
+                "launch_us": head["ffn_ms"] * 1e3}
 
     # ---- context: plain device-to-device copy rate (read + write bytes) of 1 GiB, the practical streaming ceiling
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
@@ -181,30 +217,40 @@ def main() -> int:
     copy_gbps = 2.0 * src.numel() * 10 / (c0.elapsed_time(c1) * 1e-3) / 1e9
     del src, dst
 
-    # ---- CPU baseline: the oracle, as it stands, on the same workload (copy 0, M = 32), host cores of this machine
+    # ---- CPU baseline: the oracle, as it stands, on the same workload (weight set 0, headline M), host cores of this machine
     cpu = None
     if not args.no_cpu:
         from oracle import c_oracle as orc
         wf = {n: gen.as_f32(a) for n, a in host_w0.items()}
-        xf = gen.as_f32(x_host)
-        mask = gen.activated_set_by_summed_probability(orc.router_logits(xf, wf["router"]), HEADLINE_M)
+        xf = gen.as_f32(x_host0)
+        mask = gen.activated_set_by_summed_probability(orc.router_logits(xf, wf["router"]), headline)
         orc.moe_layer(xf, wf["router"], wf["gate"], wf["up"], wf["down"], k, 1, mask)          # warm
         n, t_begin = 0, time.perf_counter()
         while time.perf_counter() - t_begin < args.cpu_seconds:
             orc.moe_layer(xf, wf["router"], wf["gate"], wf["up"], wf["down"], k, 1, mask)
             n += 1
         el = time.perf_counter() - t_begin
-        cpu = {"value": T * n / el, "unit": "tokens/s", "cores": orc.max_threads(), "kind": "oracle",
-               "sample": f"{n} full layer calls of the same workload (weight set 0, M={HEADLINE_M}, 32 tokens each) in {el:.1f}s"}
+        cpu_tokens_per_s = T * n / el / layers_per_step          # cfg4: a token has passed the step when all layers are done
+        cpu = {"value": cpu_tokens_per_s, "unit": "tokens/s", "cores": orc.max_threads(), "kind": "oracle",
+               "sample": f"{n} single-layer calls of the same workload (weight set 0, M={headline}, {T} tokens each) in {el:.1f}s"
+                         + (f"; scaled to the {layers_per_step}-layer step" if layers_per_step > 1 else "")}
 
-    out = {"metric": "moe_layer_tokens_per_s", "value": T / sec_per_step, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-           "warmup": args.warmup, "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+    desc = {
+        "cfg2": f"cfg2: one 30B-A3B-shaped MoE layer (H=2048, E=128, top-8, I=768, bf16), block of 32 tokens, activated-expert set "
+                f"M={headline} (top experts by summed router probability), {n_sets} weight sets rotated",
+        "cfg3": f"cfg3: same layer, 4 speculative candidates x 32 tokens = 128 tokens sharing one activated set of {headline} experts, "
+                f"{n_sets} weight sets rotated",
+        "cfg4": f"cfg4: stack of {n_sets} cfg2 layers (MoE FFN only), one 32-token block, 16 denoising steps with drifting hidden states, "
+                f"activated set of {headline} per (layer, step); a step = one pass over the stack",
+        "cfg5": f"cfg5: fine-grained layer (H=2048, E=256, top-8, I=512, bf16), 256 tokens, activated set M={headline}, {n_sets} weight sets rotated",
+    }[wl]
+    out = {"metric": "moe_layer_tokens_per_s", "value": T / sec_per_step, "unit": "tokens/s", "n_gpus": 1, "steps": steps,
+           "warmup": warmup, "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": f"cfg2: one 30B-A3B-shaped MoE layer (H=2048, E=128, top-8, I=768, bf16), block of 32 tokens, "
-                                  f"activated-expert set M={HEADLINE_M} (top experts by summed router probability), "
-                                  f"{args.copies} weight sets rotated", "tokens": T, "activated": HEADLINE_M,
-                      "touched": touched[HEADLINE_M]},
+           "config": {"workload": desc, "tokens": T, "activated": headline, "touched": touched[headline], "layers_per_step": layers_per_step},
            "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep, "device_copy_GBps": copy_gbps}
+    if wl == "cfg4":
+        out["ms_per_block_16_steps"] = sec_per_step * 1e3 * 16
     print(json.dumps(out), flush=True)
     return 0
 

@@ -46,6 +46,10 @@ hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offs
     p.grid_override = env_int("TEAM_MOE_FFN_GRID", 0);      // tuning aid only; never raises the grid above what is resident
     p.spin_limit = 1 << 16;          // ~0.1 s of polling; a wait this long means the control block was not zeroed
     p.stream = s;
+    // Up to 64 tokens per call every expert has at most 64 rows: the token operand fits in registers (two passes at
+    // most).  Beyond that the streaming variant is used.
+    const int tiled_from = env_int("TEAM_MOE_FFN_TILED_FROM", 65);      // tuning aid only
+    if (d.T >= tiled_from) return launch_ffn_tiled(p, d.H, d.I);
     switch (d.H / 128) {
         case 2: return launch_ffn_fused_ksa<2>(p, d.I / 128);
         case 4: return launch_ffn_fused_ksa<4>(p, d.I / 128);

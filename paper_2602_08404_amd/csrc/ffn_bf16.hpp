@@ -38,6 +38,9 @@ struct FfnArgs {
     hipStream_t stream;
 };
 
+// Variant for many rows per expert (both operands streamed through LDS); any hidden % 64 == 0, inter % 64 == 0.
+hipError_t launch_ffn_tiled(const FfnArgs& p, int H, int I);
+
 // KSA = hidden / 128; dispatches on ksb = inter / 128.
 template <int KSA>
 hipError_t launch_ffn_fused_ksa(const FfnArgs& p, int ksb);
