@@ -45,11 +45,10 @@ hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offs
     p.n_cu = compute_units();
     p.grid_override = env_int("TEAM_MOE_FFN_GRID", 0);      // tuning aid only; never raises the grid above what is resident
     p.spin_limit = 1 << 16;          // ~0.1 s of polling; a wait this long means the control block was not zeroed
+    // With at most 64 tokens per call an expert has at most 64 rows and the register-resident token operand is reused
+    // across its items; beyond that the kernel decides on the device from the average number of rows per expert.
+    p.tiled_min_avg_rows = d.T > 64 ? env_int("TEAM_MOE_FFN_TILED_ROWS", 26) : 0;      // override is a tuning aid only
     p.stream = s;
-    // Up to 64 tokens per call every expert has at most 64 rows: the token operand fits in registers (two passes at
-    // most).  Beyond that the streaming variant is used.
-    const int tiled_from = env_int("TEAM_MOE_FFN_TILED_FROM", 65);      // tuning aid only
-    if (d.T >= tiled_from) return launch_ffn_tiled(p, d.H, d.I);
     switch (d.H / 128) {
         case 2: return launch_ffn_fused_ksa<2>(p, d.I / 128);
         case 4: return launch_ffn_fused_ksa<4>(p, d.I / 128);

@@ -35,11 +35,9 @@ struct FfnArgs {
     int n_cu;                   // compute units of the current device
     int grid_override;          // > 0: use a smaller grid than the resident maximum (tuning aid)
     int spin_limit;
+    int tiled_min_avg_rows;     // > 0: switch to the streaming variant when the call averages at least this many rows per expert
     hipStream_t stream;
 };
-
-// Variant for many rows per expert (both operands streamed through LDS); any hidden % 64 == 0, inter % 64 == 0.
-hipError_t launch_ffn_tiled(const FfnArgs& p, int H, int I);
 
 // KSA = hidden / 128; dispatches on ksb = inter / 128.
 template <int KSA>

@@ -29,6 +29,7 @@
 // (C = 4 * K-steps).  Chunk (r, c) sits at position r*C + (c ^ (r >> (4 - V))), V = min(4, ctz(C)), which
 // makes the 16 rows of one MFMA operand read hit 16 different 16-byte bank groups.
 #include "ffn_bf16.hpp"
+#include "ffn_bf16_tiled.hpp"
 
 namespace team {
 
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                                                                    const uint16_t* __restrict__ wg, const uint16_t* __restrict__ wu,
                                                                    const uint16_t* __restrict__ wd, uint16_t* __restrict__ h,
                                                                    float* __restrict__ out, FfnCtrl* __restrict__ ctrl, int T, int k, int E,
-                                                                   int spin_limit) {
+                                                                   int spin_limit, int tiled_min_avg_rows) {
     using SA = Slice<KSA>;
     using SB = Slice<KSB>;
     constexpr int H = KSA * 128, I = KSB * 128;
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     constexpr int KSM = cmax(KSA, KSB);
     constexpr int W_A = FFN_WAVES * SA::BYTES, W_B = FFN_WAVES * RB * SB::BYTES;
     constexpr int RED_A = FFN_WAVES * NT * WAVE * 16, RED_B = FFN_WAVES * RB * NT * WAVE * 16;
-    constexpr int LDS_BYTES = cmax(W_A + RED_A, W_B + RED_B);
+    constexpr int LDS_BYTES = cmax(cmax(W_A + RED_A, W_B + RED_B), tiled::RING_BYTES);   // the streaming variant reuses s_mem
     constexpr int TILES_A = I / 8, TILES_B = H / (16 * RB);
     __shared__ __attribute__((aligned(1024))) char s_mem[LDS_BYTES];
     __shared__ int32_t s_slot_e[FFN_MAX_E];
@@ -131,6 +132,18 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     const int n_act = min(max(*n_active, 0), E);
     for (int i = tid; i < E; i += FFN_THREADS) s_slot_e[i] = active[i];
     for (int i = tid; i <= E; i += FFN_THREADS) s_off[i] = min(max(offsets[i], 0), A);
+    if (tiled_min_avg_rows > 0) {
+        // Many rows per expert on average: the register-resident token operand below would have to be re-gathered for
+        // every item; stream both operands through LDS instead.  The decision depends on the tables only, so every
+        // workgroup of the launch takes the same branch.
+        __syncthreads();
+        const int total_rows = s_off[E];
+        if (n_act > 0 && (long long)total_rows >= (long long)tiled_min_avg_rows * n_act) {
+            tiled::ffn_tiled_body<tiled::RING_STAGES>(s_mem, s_slot_e, s_off, n_act, x, sorted_token, wg, wu, wd, h, out, ctrl, T, E, H, I,
+                                                      spin_limit);
+            return;
+        }
+    }
     const long long total_a = (long long)n_act * TILES_A, total_b = (long long)n_act * TILES_B;
     const int a_begin = (int)(total_a * blockIdx.x / G), a_end = (int)(total_a * (blockIdx.x + 1) / G);
     const int b_begin = (int)(total_b * blockIdx.x / G), b_end = (int)(total_b * (blockIdx.x + 1) / G);
@@ -365,7 +378,8 @@ hipError_t launch_ffn_fused(const FfnArgs& p) {
     }
     const int grid = p.grid_override > 0 && p.grid_override < resident ? p.grid_override : resident;
     hipLaunchKernelGGL((ffn_fused_kernel<KSA, KSB, RB>), dim3(grid), dim3(FFN_THREADS), 0, p.stream, p.x, p.offsets, p.sorted_token,
-                       p.active, p.n_active, p.wg, p.wu, p.wd, p.h, p.out, p.ctrl, p.T, p.k, p.E, p.spin_limit);
+                       p.active, p.n_active, p.wg, p.wu, p.wd, p.h, p.out, p.ctrl, p.T, p.k, p.E, p.spin_limit,
+                       p.tiled_min_avg_rows);
     return hipGetLastError();
 }
 

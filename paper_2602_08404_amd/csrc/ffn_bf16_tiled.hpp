@@ -1,5 +1,6 @@
 // Grouped SwiGLU expert FFN, bf16, gfx950 MFMA: the variant for calls with many tokens per expert
-// (speculative branches and batched blocks: tens to hundreds of rows per activated expert).
+// (speculative branches and batched blocks: tens to hundreds of rows per activated expert).  Included by
+// ffn_bf16_kernel.hip; the persistent kernel switches to this body when the call averages many rows per expert.
 //
 // Same work decomposition, same per-expert h hand-over and same deterministic results as ffn_bf16_kernel.hip,
 // but both operands stream through LDS in a software pipeline instead of keeping the token operand in
@@ -23,11 +24,12 @@
 // The loop counts its own outstanding loads (s_waitcnt vmcnt(N) with a constant N per wavefront) and reads LDS
 // with explicit instructions: the compiler's automatic waits treat every direct-to-LDS load as aliasing every
 // LDS read and would drain the pipeline at each stage.
+#pragma once
 #include "ffn_bf16.hpp"
 
 namespace team {
 
-namespace {
+namespace tiled {
 
 constexpr int KC = 64;                 // reduction columns per stage
 constexpr int MT = 64;                 // token rows per pass
@@ -85,33 +87,23 @@ struct Seg {                   // one (item, pass) of a workgroup's share
     bool valid;
 };
 
-}  // namespace
+constexpr int RING_STAGES = 6;
+constexpr int RING_BYTES = RING_STAGES * STAGE_BYTES;
 
+// Body of the streaming variant; runs inside the persistent FFN kernel (all workgroups take it or none does).
+// s_ring: RING_BYTES of LDS, 1 KB aligned; s_slot_e / s_off: the kernel's tables (active list, clipped offsets).
 template <int D>
-__global__ __launch_bounds__(FFN_THREADS, 2) void ffn_tiled_kernel(const uint16_t* __restrict__ x, const int32_t* __restrict__ offsets,
-                                                                   const int32_t* __restrict__ sorted_token,
-                                                                   const int32_t* __restrict__ active, const int32_t* __restrict__ n_active,
-                                                                   const uint16_t* __restrict__ wg, const uint16_t* __restrict__ wu,
-                                                                   const uint16_t* __restrict__ wd, uint16_t* __restrict__ h,
-                                                                   float* __restrict__ out, FfnCtrl* __restrict__ ctrl, int T, int k, int E,
-                                                                   int H, int I, int spin_limit) {
-    __shared__ __attribute__((aligned(1024))) char s_ring[D * STAGE_BYTES];
-    __shared__ int32_t s_slot_e[FFN_MAX_E];
-    __shared__ int32_t s_off[FFN_MAX_E + 1];
-
+__device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_slot_e, const int32_t* s_off, int n_act,
+                                               const uint16_t* __restrict__ x, const int32_t* __restrict__ sorted_token,
+                                               const uint16_t* __restrict__ wg, const uint16_t* __restrict__ wu,
+                                               const uint16_t* __restrict__ wd, uint16_t* __restrict__ h, float* __restrict__ out,
+                                               FfnCtrl* __restrict__ ctrl, int T, int E, int H, int I, int spin_limit) {
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 15, q = lane >> 4;
-    const int A = T * k;
     const int G = gridDim.x;
     const int tiles_a = I / 16, tiles_b = H / W_ROWS;
-
-    // ---- tables into LDS (one global round trip)
-    const int n_act = min(max(*n_active, 0), E);
-    for (int i = tid; i < E; i += FFN_THREADS) s_slot_e[i] = active[i];
-    for (int i = tid; i <= E; i += FFN_THREADS) s_off[i] = min(max(offsets[i], 0), A);
-    __syncthreads();
 
     // ---- lane constants
     // loads: lane fetches row (l / 8) of an 8-row slab, stored chunk (l % 8)
@@ -320,20 +312,6 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_tiled_kernel(const uint16_
     }
 }
 
-hipError_t launch_ffn_tiled(const FfnArgs& p, int H, int I) {
-    constexpr int D = 6;
-    static int resident = 0;         // same value for every caller, so a benign race
-    if (resident == 0) {
-        int per_cu = 0;
-        hipError_t err = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, ffn_tiled_kernel<D>, FFN_THREADS, 0);
-        if (err != hipSuccess) return err;
-        if (per_cu < 1) return hipErrorLaunchOutOfResources;
-        resident = per_cu * p.n_cu;
-    }
-    const int grid = p.grid_override > 0 && p.grid_override < resident ? p.grid_override : resident;
-    hipLaunchKernelGGL(ffn_tiled_kernel<D>, dim3(grid), dim3(FFN_THREADS), 0, p.stream, p.x, p.offsets, p.sorted_token, p.active,
-                       p.n_active, p.wg, p.wu, p.wd, p.h, p.out, p.ctrl, p.T, p.k, p.E, H, I, p.spin_limit);
-    return hipGetLastError();
-}
+}  // namespace tiled
 
 }  // namespace team
