@@ -117,7 +117,8 @@ int team_moe_route(const team_moe_config* cfg, const void* x, int32_t T, const v
         return TEAM_ERR_INVALID_ARG;
     }
     clear_stale_error();
-    return hip_status(team::launch_route(dims_of(cfg, T), x, w_router, expert_mask, topk_idx, topk_gate, logits, (hipStream_t)stream));
+    return hip_status(team::launch_route(dims_of(cfg, T), x, w_router, expert_mask, topk_idx, topk_gate, logits,
+                                         team::CtrlZero{nullptr, 0, 0}, (hipStream_t)stream));
 }
 
 int team_moe_build_dispatch(const team_moe_config* cfg, const int32_t* topk_idx, int32_t T, int32_t* expert_offsets,
@@ -190,7 +191,20 @@ int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T,
     const Dims d = dims_of(cfg, T);
     hipStream_t s = (hipStream_t)stream;
     clear_stale_error();
-    if ((st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, (float*)(ws + L.logits), s))) != TEAM_OK)
+    if (team::ffn_bf16_groups_itself(d)) {
+        // Small calls (the block-decoding regime): route -> expert FFN -> combine.  The FFN kernel groups the routing table
+        // itself (every workgroup, in LDS) and writes inv_pos; the selection kernel clears the FFN's control block.
+        if ((st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, (float*)(ws + L.logits),
+                                                team::ffn_ctrl_zero(ws + L.ctrl), s))) != TEAM_OK)
+            return st;
+        if ((st = hip_status(team::launch_ffn_bf16_from_routing(d, (const uint16_t*)x, topk_idx, inv_pos, (const uint16_t*)w_gate,
+                                                                (const uint16_t*)w_up, (const uint16_t*)w_down, ws + L.ctrl,
+                                                                (uint16_t*)(ws + L.h), expert_out, s))) != TEAM_OK)
+            return st;
+        return hip_status(team::launch_combine(d, expert_out, topk_gate, inv_pos, y, s));
+    }
+    if ((st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, (float*)(ws + L.logits),
+                                            team::CtrlZero{nullptr, 0, 0}, s))) != TEAM_OK)
         return st;
     // the dispatch kernel also clears the FFN's control block
     const team::CtrlZero cz = cfg->dtype == TEAM_BF16 ? team::ffn_ctrl_zero(ws + L.ctrl) : team::CtrlZero{nullptr, 0, 0};

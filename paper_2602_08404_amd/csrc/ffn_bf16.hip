@@ -34,13 +34,11 @@ bool ffn_bf16_supported(int H, int I) {
     return h_ok && i_ok;
 }
 
-hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offsets, const int32_t* sorted_token, const int32_t* active,
-                           const int32_t* n_active, const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, void* ctrl,
-                           uint16_t* h_ws, float* expert_out, hipStream_t s) {
-    if (!ffn_bf16_supported(d.H, d.I) || d.E > FFN_MAX_E) return hipErrorInvalidValue;
-    FfnArgs p;
-    p.x = x; p.offsets = offsets; p.sorted_token = sorted_token; p.active = active; p.n_active = n_active;
-    p.wg = wg; p.wu = wu; p.wd = wd; p.h = h_ws; p.out = expert_out; p.ctrl = (FfnCtrl*)ctrl;
+bool ffn_bf16_groups_itself(const Dims& d) {
+    return d.bf16 && d.T <= FFN_LAYER_MAX_TOKENS && d.T * d.k <= FFN_LAYER_MAX_ROWS && d.E <= FFN_MAX_E && ffn_bf16_supported(d.H, d.I);
+}
+
+static hipError_t launch_common(const Dims& d, FfnArgs& p, hipStream_t s) {
     p.T = d.T; p.k = d.k; p.E = d.E;
     p.n_cu = compute_units();
     p.grid_override = env_int("TEAM_MOE_FFN_GRID", 0);      // tuning aid only; never raises the grid above what is resident
@@ -56,6 +54,28 @@ hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offs
         case 16: return launch_ffn_fused_ksa<16>(p, d.I / 128);
         default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offsets, const int32_t* sorted_token, const int32_t* active,
+                           const int32_t* n_active, const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, void* ctrl,
+                           uint16_t* h_ws, float* expert_out, hipStream_t s) {
+    if (!ffn_bf16_supported(d.H, d.I) || d.E > FFN_MAX_E) return hipErrorInvalidValue;
+    FfnArgs p;
+    p.x = x; p.offsets = offsets; p.sorted_token = sorted_token; p.active = active; p.n_active = n_active;
+    p.wg = wg; p.wu = wu; p.wd = wd; p.h = h_ws; p.out = expert_out; p.ctrl = (FfnCtrl*)ctrl;
+    p.topk_idx = nullptr; p.inv_pos_out = nullptr;
+    return launch_common(d, p, s);
+}
+
+hipError_t launch_ffn_bf16_from_routing(const Dims& d, const uint16_t* x, const int32_t* topk_idx, int32_t* inv_pos_out,
+                                        const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, void* ctrl, uint16_t* h_ws,
+                                        float* expert_out, hipStream_t s) {
+    if (!ffn_bf16_groups_itself(d)) return hipErrorInvalidValue;
+    FfnArgs p;
+    p.x = x; p.offsets = nullptr; p.sorted_token = nullptr; p.active = nullptr; p.n_active = nullptr;
+    p.wg = wg; p.wu = wu; p.wd = wd; p.h = h_ws; p.out = expert_out; p.ctrl = (FfnCtrl*)ctrl;
+    p.topk_idx = topk_idx; p.inv_pos_out = inv_pos_out;
+    return launch_common(d, p, s);
 }
 
 }  // namespace team

@@ -9,6 +9,9 @@ namespace team {
 constexpr int FFN_THREADS = 256;
 constexpr int FFN_WAVES = 4;
 constexpr int FFN_MAX_E = 256;
+constexpr int FFN_LAYER_MAX_TOKENS = 64;     // up to this many tokens (and FFN_LAYER_MAX_ROWS pairs) the kernel can group the routing table itself
+constexpr int FFN_LAYER_MAX_ROWS = 1024;
+static_assert(FFN_THREADS == FFN_MAX_E && FFN_LAYER_MAX_ROWS % FFN_THREADS == 0, "the in-kernel grouping maps one thread to one expert");
 constexpr int FFN_DONE_STRIDE = 64;      // one counter per 256 bytes: polled counters sit in different memory channels
 
 // Control block of one FFN launch (in the caller's workspace); must be all zero when the kernel starts.
@@ -31,6 +34,8 @@ struct FfnArgs {
     uint16_t* h;
     float* out;
     FfnCtrl* ctrl;
+    const int32_t* topk_idx;    // non-null: group this routing table in the kernel (offsets .. n_active are then unused)
+    int32_t* inv_pos_out;       // with topk_idx: [T,k] rows of the pairs, written for the combine kernel
     int T, k, E;
     int n_cu;                   // compute units of the current device
     int grid_override;          // > 0: use a smaller grid than the resident maximum (tuning aid)

@@ -25,6 +25,11 @@
 // bf16 with the weights as the 16-row operand and up to 32 token rows as the 16-column operand.  Partial
 // sums of the 4 wavefronts are added in a fixed order through LDS (deterministic, no float atomics).
 //
+// Two more things happen in this kernel.  (1) For small calls (at most 64 tokens) started by
+// team_moe_layer_forward, every workgroup groups the routing table itself in LDS during its prologue (the same
+// bitset / popcount / prefix-sum method as the dispatch kernel, which is then not launched).  (2) When a call
+// averages many rows per expert, all workgroups switch to the streaming body in ffn_bf16_tiled.hpp.
+//
 // LDS slice layout: a wavefront's slice of a 16-row sub-tile is 16 rows x C chunks of 16 bytes
 // (C = 4 * K-steps).  Chunk (r, c) sits at position r*C + (c ^ (r >> (4 - V))), V = min(4, ctz(C)), which
 // makes the 16 rows of one MFMA operand read hit 16 different 16-byte bank groups.
@@ -83,13 +88,6 @@ struct Slice {
     __device__ static __forceinline__ int phys(int r, int c) { return r * C + (c ^ (r >> (4 - V))); }
 };
 
-#ifdef TEAM_FFN_TRACE
-__device__ long long g_ffn_trace[2048][12];
-__device__ long long g_ffn_items[2048][3][12];   // per workgroup: start, end, item id of its first 12 items
-#define TRACE_NOW() wall_clock64()
-#else
-#define TRACE_NOW() 0ll
-#endif
 
 }  // namespace
 
@@ -102,7 +100,8 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                                                                    const uint16_t* __restrict__ wg, const uint16_t* __restrict__ wu,
                                                                    const uint16_t* __restrict__ wd, uint16_t* __restrict__ h,
                                                                    float* __restrict__ out, FfnCtrl* __restrict__ ctrl, int T, int k, int E,
-                                                                   int spin_limit, int tiled_min_avg_rows) {
+                                                                   int spin_limit, int tiled_min_avg_rows,
+                                                                   const int32_t* __restrict__ topk_idx, int32_t* __restrict__ inv_pos_out) {
     using SA = Slice<KSA>;
     using SB = Slice<KSB>;
     constexpr int H = KSA * 128, I = KSB * 128;
@@ -115,6 +114,8 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     __shared__ __attribute__((aligned(1024))) char s_mem[LDS_BYTES];
     __shared__ int32_t s_slot_e[FFN_MAX_E];
     __shared__ int32_t s_off[FFN_MAX_E + 1];
+    __shared__ int32_t s_sorted[FFN_LAYER_MAX_ROWS];     // token of every row, when the kernel groups the routing table itself
+    __shared__ int32_t s_nact;
     typedef f32x4_t (*red_a_t)[NT][WAVE];
     typedef f32x4_t (*red_b_t)[RB][NT][WAVE];
     red_a_t red_a = reinterpret_cast<red_a_t>(s_mem + LDS_BYTES - RED_A);
@@ -126,12 +127,79 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     const int A = T * k;
     const int G = gridDim.x;
 
-    [[maybe_unused]] long long tr_t0 = TRACE_NOW(), tr_a = 0, tr_b = 0, tr_wait = 0, tr_last_a = 0, tr_first_b = 0, tr_na = 0, tr_nb = 0,
-                               tr_runs = 0;
-    // ---- tables into LDS (one global round trip)
-    const int n_act = min(max(*n_active, 0), E);
-    for (int i = tid; i < E; i += FFN_THREADS) s_slot_e[i] = active[i];
-    for (int i = tid; i <= E; i += FFN_THREADS) s_off[i] = min(max(offsets[i], 0), A);
+    int n_act;
+    const bool own_tables = topk_idx != nullptr;
+    if (!own_tables) {
+        // ---- tables into LDS (one global round trip)
+        n_act = min(max(*n_active, 0), E);
+        for (int i = tid; i < E; i += FFN_THREADS) s_slot_e[i] = active[i];
+        for (int i = tid; i <= E; i += FFN_THREADS) s_off[i] = min(max(offsets[i], 0), A);
+    } else {
+        // ---- small calls (T <= 64, at most FFN_LAYER_MAX_ROWS pairs): every workgroup groups the routing table itself,
+        // in LDS, instead of waiting for a separate grouping kernel.  Same method and same result as that kernel: a token
+        // bitset per expert, popcount histogram, prefix sum, and the row of a pair = offset + number of lower tokens.
+        uint32_t* bits = reinterpret_cast<uint32_t*>(s_mem);                              // [E][2]
+        unsigned long long(*scan)[FFN_MAX_E] = reinterpret_cast<unsigned long long(*)[FFN_MAX_E]>(s_mem + 2 * FFN_MAX_E * 4);
+        for (int i = tid; i < 2 * E; i += FFN_THREADS) bits[i] = 0u;
+        __syncthreads();
+        int my_e[FFN_LAYER_MAX_ROWS / FFN_THREADS];
+#pragma unroll
+        for (int j = 0; j < FFN_LAYER_MAX_ROWS / FFN_THREADS; ++j) {
+            const int r = tid + j * FFN_THREADS;
+            int e = r < A ? topk_idx[r] : -1;
+            if (e >= E) e = -1;
+            my_e[j] = e;
+            if (e >= 0) {
+                const int t = r / k;
+                atomicOr(&bits[2 * e + (t >> 5)], 1u << (t & 31));
+            }
+        }
+        __syncthreads();
+        {
+            unsigned long long c = 0;
+            if (tid < E) {
+                const unsigned cnt = __popc(bits[2 * tid]) + __popc(bits[2 * tid + 1]);
+                c = (unsigned long long)cnt | ((unsigned long long)(cnt > 0) << 32);     // low: rows, high: 1 if the expert has rows
+            }
+            scan[0][tid] = c;
+        }
+        __syncthreads();
+        int cur = 0;
+        for (int step = 1; step < FFN_MAX_E; step <<= 1) {
+            unsigned long long v = scan[cur][tid];
+            if (tid >= step) v += scan[cur][tid - step];
+            scan[cur ^ 1][tid] = v;
+            cur ^= 1;
+            __syncthreads();
+        }
+        if (tid < E) {
+            const unsigned long long incl = scan[cur][tid], excl = tid ? scan[cur][tid - 1] : 0ull;
+            s_off[tid] = (int)(excl & 0xffffffffull);
+            if ((incl >> 32) != (excl >> 32)) s_slot_e[(int)(excl >> 32)] = tid;
+            if (tid == E - 1) {
+                s_off[E] = (int)(incl & 0xffffffffull);
+                s_nact = (int)(incl >> 32);
+            }
+        }
+        __syncthreads();
+        n_act = s_nact;
+#pragma unroll
+        for (int j = 0; j < FFN_LAYER_MAX_ROWS / FFN_THREADS; ++j) {
+            const int r = tid + j * FFN_THREADS;
+            if (r >= A) continue;
+            const int e = my_e[j];
+            int pos = -1;
+            if (e >= 0) {
+                const int t = r / k;
+                const uint32_t b0 = bits[2 * e], b1 = bits[2 * e + 1];
+                const int rank = t < 32 ? __popc(b0 & ((1u << t) - 1u)) : __popc(b0) + __popc(b1 & ((1u << (t - 32)) - 1u));
+                pos = s_off[e] + rank;
+                s_sorted[pos] = t;
+            }
+            if (blockIdx.x == 0) inv_pos_out[r] = pos;         // the combine kernel that follows needs the rows of every pair
+        }
+        __syncthreads();                                        // s_mem is handed to the weight stream from here on
+    }
     if (tiled_min_avg_rows > 0) {
         // Many rows per expert on average: the register-resident token operand below would have to be re-gathered for
         // every item; stream both operands through LDS instead.  The decision depends on the tables only, so every
@@ -150,7 +218,6 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     const int n_a = a_end - a_begin, n_mine = n_a + (b_end - b_begin);
     __syncthreads();
 
-    [[maybe_unused]] const long long tr_t1 = TRACE_NOW();
     bf16x8_t opr[NT][KSM];                   // token operand (x rows for gate/up items, h rows for down items)
     int cur_key = -1;                        // (phase, slot) the operand registers hold; -1: nothing
     int ready_slot = -1;                     // slot whose h this workgroup has already acquired
@@ -158,11 +225,6 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     int pend = 0;                            // finished gate/up items of the current slot not yet published
     {
         for (int step = 0; step < n_mine; ++step) {   // this workgroup's gate/up items, then its down items
-            [[maybe_unused]] const long long tr_i0 = TRACE_NOW();
-#ifdef TEAM_FFN_TRACE
-            const int tr_k = (int)(tr_na + tr_nb);
-            if (tid == 0 && blockIdx.x < 2048 && tr_k < 12) { g_ffn_items[blockIdx.x][0][tr_k] = tr_i0; g_ffn_items[blockIdx.x][2][tr_k] = (step < n_a) ? (step < n_a ? a_begin + step : b_begin + step - n_a) : 1000000 + (step < n_a ? a_begin + step : b_begin + step - n_a); }
-#endif
             const bool is_a = step < n_a;
             const int li = is_a ? a_begin + step : b_begin + (step - n_a);
             const int tiles = is_a ? TILES_A : TILES_B;
@@ -197,7 +259,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
 #pragma unroll
                         for (int nt = 0; nt < NT; ++nt) {
                             const int row = row_base + nt * 16 + n;
-                            int tok = row < m ? sorted_token[r0 + row] : -1;
+                            int tok = row < m ? (own_tables ? s_sorted[r0 + row] : sorted_token[r0 + row]) : -1;
                             if (tok >= T) tok = -1;
                             const uint16_t* xp = x + (size_t)(tok < 0 ? 0 : tok) * H + wave * KSLICE_A + q * 8;
                             if (tok >= 0) {
@@ -245,14 +307,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                     if (tid == 0) __hip_atomic_fetch_add(&ctrl->done[a][0], pend, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     pend = 0;
                 }
-                tr_last_a = TRACE_NOW();
-                tr_a += tr_last_a - tr_i0;
-#ifdef TEAM_FFN_TRACE
-                if (tid == 0 && blockIdx.x < 2048 && tr_k < 12) g_ffn_items[blockIdx.x][1][tr_k] = tr_last_a;
-#endif
-                ++tr_na;
             } else {
-                if (tr_first_b == 0) tr_first_b = tr_i0;
                 // =============================================================== down item
                 char* region = s_mem + wave * (RB * SB::BYTES);
                 if (m > 0) {
@@ -268,7 +323,6 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                         }
                 }
                 if (a != ready_slot) {       // wait until every gate/up item of this expert has published h
-                    [[maybe_unused]] const long long tr_w0 = TRACE_NOW();
                     if (tid == 0) {
                         int spins = 0;
                         while (__hip_atomic_load(&ctrl->done[a][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < TILES_A) {
@@ -281,7 +335,6 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                     }
                     __syncthreads();
                     ready_slot = a;
-                    tr_wait += TRACE_NOW() - tr_w0;
                 }
                 const int chunks = (m + 16 * NT - 1) / (16 * NT);
                 for (int ch = 0; ch < chunks; ++ch) {
@@ -290,7 +343,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
 #pragma unroll
                         for (int nt = 0; nt < NT; ++nt) {
                             const int row = row_base + nt * 16 + n;
-                            const bool valid = row < m && sorted_token[r0 + row] >= 0;
+                            const bool valid = row < m && (own_tables || sorted_token[r0 + row] >= 0);
                             const uint16_t* hp = h + (size_t)(valid ? r0 + row : 0) * I + wave * KSLICE_B + q * 8;
                             if (valid) {
 #pragma unroll
@@ -337,31 +390,11 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                     }
                     __syncthreads();
                 }
-                tr_b += TRACE_NOW() - tr_i0;
-#ifdef TEAM_FFN_TRACE
-                if (tid == 0 && blockIdx.x < 2048 && tr_k < 12) g_ffn_items[blockIdx.x][1][tr_k] = TRACE_NOW();
-#endif
-                ++tr_nb;
             }
         }
     }
-#ifdef TEAM_FFN_TRACE
-    if (tid == 0 && blockIdx.x < 2048) {
-        long long* t = g_ffn_trace[blockIdx.x];
-        t[0] = tr_t0; t[1] = tr_t1; t[2] = tr_a; t[3] = tr_na; t[4] = tr_b; t[5] = tr_nb; t[6] = tr_wait; t[7] = tr_last_a;
-        t[8] = tr_first_b; t[9] = TRACE_NOW(); t[10] = tr_runs; t[11] = (long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) | ((long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32);  /* HW_ID, XCC_ID */
-    }
-#endif
 }
 
-#ifdef TEAM_FFN_TRACE
-extern "C" int team_moe_debug_read_trace(void* host, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_ffn_trace), bytes);
-}
-extern "C" int team_moe_debug_read_items(void* host, size_t bytes) {
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_ffn_items), bytes);
-}
-#endif
 
 // The kernel's waits need every workgroup of the grid to be resident at once, so the grid is what the runtime
 // says fits: (workgroups per compute unit for this instantiation) x (compute units), never more.
@@ -379,7 +412,7 @@ hipError_t launch_ffn_fused(const FfnArgs& p) {
     const int grid = p.grid_override > 0 && p.grid_override < resident ? p.grid_override : resident;
     hipLaunchKernelGGL((ffn_fused_kernel<KSA, KSB, RB>), dim3(grid), dim3(FFN_THREADS), 0, p.stream, p.x, p.offsets, p.sorted_token,
                        p.active, p.n_active, p.wg, p.wu, p.wd, p.h, p.out, p.ctrl, p.T, p.k, p.E, p.spin_limit,
-                       p.tiled_min_avg_rows);
+                       p.tiled_min_avg_rows, p.topk_idx, p.inv_pos_out);
     return hipGetLastError();
 }
 

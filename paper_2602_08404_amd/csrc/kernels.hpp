@@ -12,15 +12,16 @@ struct Dims {
     int renormalize;
 };
 
-// logits: [T,E] floats, required (scratch of the selection kernel and, for the caller, the router scores).
-hipError_t launch_route(const Dims& d, const void* x, const void* w_router, const uint8_t* mask, int32_t* topk_idx,
-                        float* topk_gate, float* logits, hipStream_t s);
 // Words of the FFN control block that must be zero before an FFN launch: `header` leading words, then one word
 // every `stride` words for each of the E expert slots.
 struct CtrlZero {
     int32_t* words;     // nullptr: nothing to clear
     int header, stride;
 };
+// logits: [T,E] floats, required (scratch of the selection kernel and, for the caller, the router scores).
+// ctrl: control block the selection kernel also clears for an expert FFN that follows without a dispatch kernel.
+hipError_t launch_route(const Dims& d, const void* x, const void* w_router, const uint8_t* mask, int32_t* topk_idx,
+                        float* topk_gate, float* logits, CtrlZero ctrl, hipStream_t s);
 // ctrl: control block the dispatch kernel also clears for the expert FFN that follows (words == nullptr: none).
 hipError_t launch_dispatch(const Dims& d, const int32_t* topk_idx, int32_t* offsets, int32_t* sorted_token,
                            int32_t* inv_pos, int32_t* active, int32_t* n_active, CtrlZero ctrl, hipStream_t s);
@@ -39,5 +40,11 @@ CtrlZero ffn_ctrl_zero(void* ctrl);
 hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offsets, const int32_t* sorted_token,
                            const int32_t* active, const int32_t* n_active, const uint16_t* wg, const uint16_t* wu,
                            const uint16_t* wd, void* ctrl, uint16_t* h_ws, float* expert_out, hipStream_t s);
+// Whole-layer form for small calls: the FFN kernel groups the routing table (topk_idx) itself and writes inv_pos for
+// the combine kernel; no dispatch kernel is needed.  ffn_bf16_groups_itself says whether a call qualifies.
+bool ffn_bf16_groups_itself(const Dims& d);
+hipError_t launch_ffn_bf16_from_routing(const Dims& d, const uint16_t* x, const int32_t* topk_idx, int32_t* inv_pos_out,
+                                        const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, void* ctrl, uint16_t* h_ws,
+                                        float* expert_out, hipStream_t s);
 
 }  // namespace team

@@ -103,7 +103,7 @@ __device__ __forceinline__ unsigned long long select_key(float v, int e) {
 
 __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(const float* __restrict__ logits, const uint8_t* __restrict__ mask,
                                                                       int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate,
-                                                                      int E, int k, int renormalize) {
+                                                                      int E, int k, int renormalize, CtrlZero ctrl) {
     __shared__ __attribute__((aligned(16))) unsigned long long s_key[MAX_E];   // 0 for experts that are not candidates
     __shared__ float s_all[MAX_E];                                              // every logit (for the full softmax)
     __shared__ float s_sel_logit[16];
@@ -112,6 +112,10 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(const floa
     const int t = blockIdx.x;
     const int e = threadIdx.x;
     const int lane = e & (WAVE - 1);
+    if (ctrl.words && t == 0) {                     // control block of an expert FFN that follows without a dispatch kernel
+        if (e < ctrl.header) ctrl.words[e] = 0;
+        if (e < E) ctrl.words[ctrl.header + e * ctrl.stride] = 0;
+    }
     float v = 0.f;
     bool ok = false;
     if (e < E) {
@@ -165,7 +169,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(const floa
 }
 
 hipError_t launch_route(const Dims& d, const void* x, const void* w_router, const uint8_t* mask, int32_t* topk_idx,
-                        float* topk_gate, float* logits, hipStream_t s) {
+                        float* topk_gate, float* logits, CtrlZero ctrl, hipStream_t s) {
     dim3 grid((d.E + LOGIT_GROUP - 1) / LOGIT_GROUP, d.T), block(LOGIT_THREADS);
     if (d.bf16)
         hipLaunchKernelGGL(route_logits_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)x, (const uint16_t*)w_router, logits, d.H, d.E);
@@ -174,7 +178,7 @@ hipError_t launch_route(const Dims& d, const void* x, const void* w_router, cons
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(route_select_kernel, dim3(d.T), dim3(SELECT_THREADS), 0, s, logits, mask, topk_idx, topk_gate, d.E, d.k,
-                       d.renormalize);
+                       d.renormalize, ctrl);
     return hipGetLastError();
 }
 
