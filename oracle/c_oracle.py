@@ -62,6 +62,20 @@ def route(x, w_router, k: int, renormalize: int = 1, mask=None):
     return idx, gate, logits
 
 
+def route_two_round(logits, k: int, first_round, renormalize: int = 1):
+    """Algorithm 1: returns (activated mask uint8 [E], topk_idx int32 [T,k], topk_gate fp64 [T,k])."""
+    logits = _f32(logits)
+    T, E = logits.shape
+    fr = np.ascontiguousarray(first_round, dtype=np.uint8)
+    assert fr.shape == (T,)
+    mask = np.zeros(E, np.uint8)
+    idx = np.empty((T, k), np.int32)
+    gate = np.empty((T, k), np.float64)
+    lib().oracle_route_two_round(_p(logits, C.c_float), T, E, k, int(renormalize), _p(fr, C.c_uint8), _p(mask, C.c_uint8),
+                                 _p(idx, C.c_int32), _p(gate, C.c_double))
+    return mask, idx, gate
+
+
 def dispatch(topk_idx, E: int):
     topk_idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
     T, k = topk_idx.shape

@@ -24,6 +24,9 @@
  * place floating point decides an integer - which experts are selected - is decided on the logit rounded
  * to fp32, the precision the kernels select in.
  *
+ * oracle_route_two_round is Algorithm 1 itself (first-round tokens over all experts, E_A = union of their picks,
+ * cold tokens inside E_A).
+ *
  * Pins (tests/test_oracle_pins.py): hand-worked example (tests/golden), dense-SwiGLU special case,
  * mask-free top-k MoE written separately, brute-force subset enumeration, superset invariance from
  * Algorithm 1, sub-model equivalence, permutation equivariance, closed forms, and an independent NumPy
@@ -89,6 +92,25 @@ void oracle_route_from_logits(const float *logits, int T, int E, int k, int reno
                               int32_t *topk_idx, double *topk_gate) {
     for (int t = 0; t < T; ++t)
         route_token(logits + (size_t)t * E, E, k, renormalize, mask, topk_idx + (size_t)t * k, topk_gate + (size_t)t * k);
+}
+
+/* Two-round routing (Algorithm 1, "Limited Activation for cold tokens").
+ * Round 1: tokens with first_round[t] != 0 (newly accepted tokens D_a and hot tokens H) are routed over all experts E_0.
+ * E_A = union over those tokens of their selected experts (mask_out[e] = 1 for e in E_A, else 0).
+ * Round 2: the remaining (cold) tokens are routed inside E_A.  W = Concat(W_1, W_2): one row per token, in token order. */
+void oracle_route_two_round(const float *logits, int T, int E, int k, int renormalize, const uint8_t *first_round,
+                            uint8_t *mask_out, int32_t *topk_idx, double *topk_gate) {
+    for (int e = 0; e < E; ++e) mask_out[e] = 0;
+    for (int t = 0; t < T; ++t) {
+        if (!first_round[t]) continue;
+        route_token(logits + (size_t)t * E, E, k, renormalize, NULL, topk_idx + (size_t)t * k, topk_gate + (size_t)t * k);
+        for (int s = 0; s < k; ++s)
+            if (topk_idx[(size_t)t * k + s] >= 0) mask_out[topk_idx[(size_t)t * k + s]] = 1;
+    }
+    for (int t = 0; t < T; ++t) {
+        if (first_round[t]) continue;
+        route_token(logits + (size_t)t * E, E, k, renormalize, mask_out, topk_idx + (size_t)t * k, topk_gate + (size_t)t * k);
+    }
 }
 
 /* Output of one expert for one token: out[H] = W_d ( silu(W_g x) * (W_u x) ); hbuf is I doubles of scratch. */

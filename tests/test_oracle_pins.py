@@ -174,6 +174,58 @@ def test_superset_invariance(renorm):
     assert union[idx2].all()
 
 
+# ----------------------------------------------------------------------------- Algorithm 1 (two-round routing)
+@pytest.mark.parametrize("renorm", [1, 0])
+@pytest.mark.parametrize("seed", range(3))
+def test_two_round_routing_is_algorithm_1(seed, renorm):
+    E, k, T = 16, 3, 14
+    r = np.random.default_rng(300 + seed)
+    logits = r.standard_normal((T, E)).astype(np.float32)
+    first = (r.random(T) < 0.4).astype(np.uint8)
+    first[0] = 1
+    mask, idx, gate = orc.route_two_round(logits, k, first, renorm)
+    fr = np.nonzero(first)[0]
+    cold = np.nonzero(first == 0)[0]
+    # round 1 = free routing of the first-round tokens (brute force: full sort of their logits)
+    for t in fr:
+        assert idx[t].tolist() == sorted(range(E), key=lambda e: (-logits[t, e], e))[:k]
+    # E_A = union of their picks, nothing else
+    union = np.zeros(E, np.uint8)
+    union[np.unique(idx[fr])] = 1
+    np.testing.assert_array_equal(mask, union)
+    # round 2 = routing confined to E_A: cold tokens only pick inside it, and pick its best members
+    assert mask[idx[cold][idx[cold] >= 0]].all()
+    allowed = [e for e in range(E) if mask[e]]
+    for t in cold:
+        assert idx[t].tolist()[:min(k, len(allowed))] == sorted(allowed, key=lambda e: (-logits[t, e], e))[:k]
+    # Concat(W_1, W_2) equals one masked call over ALL tokens (first-round picks lie in E_A: superset invariance)
+    idx_all, gate_all = orc.route_from_logits(logits, k, renorm, mask)
+    np.testing.assert_array_equal(idx, idx_all)
+    np.testing.assert_array_equal(gate, gate_all)
+    # and each round equals the single-round router on its own tokens
+    i1, g1 = orc.route_from_logits(logits[fr], k, renorm, None)
+    np.testing.assert_array_equal(idx[fr], i1)
+    np.testing.assert_array_equal(gate[fr], g1)
+
+
+def test_two_round_routing_degenerate():
+    logits = np.random.default_rng(9).standard_normal((5, 8)).astype(np.float32)
+    # no first-round token: E_A is empty and cold tokens get no expert
+    mask, idx, gate = orc.route_two_round(logits, 2, np.zeros(5, np.uint8))
+    assert mask.sum() == 0 and (idx == -1).all() and (gate == 0).all()
+    # all tokens first-round: plain top-k, E_A = everything selected
+    mask, idx, gate = orc.route_two_round(logits, 2, np.ones(5, np.uint8))
+    i0, g0 = orc.route_from_logits(logits, 2, 1, None)
+    np.testing.assert_array_equal(idx, i0)
+    assert mask.sum() == len(np.unique(i0))
+    # E_A smaller than k: cold tokens get k_eff = |E_A| slots
+    first = np.array([1, 0, 0, 0, 0], np.uint8)
+    mask, idx, gate = orc.route_two_round(logits, 1, first)
+    assert mask.sum() == 1
+    mask3, idx3, gate3 = orc.route_two_round(np.repeat(logits, 1, 0), 3, first)
+    assert mask3.sum() == 3 and (idx3[1:] >= 0).all() and mask3[idx3].all()
+
+
 # ----------------------------------------------------------------------------- P7 sub-model equivalence
 def test_masked_layer_equals_compacted_model():
     x, wr, wg, wu, wd = tiny(T=7, E=8, seed=8)
