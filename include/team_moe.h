@@ -135,6 +135,36 @@ int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T,
                            const void* w_gate, const void* w_up, const void* w_down,
                            const uint8_t* expert_mask, void* y, void* workspace, size_t ws_bytes, void* stream);
 
+/*
+ * Two-round routing of Algorithm 1 ("Limited Activation for cold tokens") in one call.
+ *   token_class [T] bytes: non-zero = first-round token (a newly accepted token of D_a or a hot token of H, which may
+ *                          activate experts); zero = cold token of C.
+ *   round 1: every first-round token is routed over all experts E_0 exactly as team_moe_route with expert_mask == NULL;
+ *   E_A     = the union of the experts those tokens selected;
+ *   round 2: every cold token is routed exactly as team_moe_route with expert_mask = E_A.
+ *   topk_idx / topk_gate [T,k]: W = Concat(W_1, W_2), one row per token in token order, same conventions as
+ *                               team_moe_route (cold tokens have min(k, |E_A|) valid slots).
+ *   activated_mask_out [E] bytes (1 = in E_A) and n_activated_out [1] (= |E_A|): optional, may be NULL.
+ *   logits_out [T,E]: optional as in team_moe_route.
+ * With no first-round token E_A is empty and every cold token gets topk_idx = -1, gate 0.
+ * `workspace` is required (team_moe_workspace_size bytes, 256-byte aligned): it holds E_A while it is being built.
+ */
+int team_moe_route_two_round(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router,
+                             const uint8_t* token_class /* [T] */, uint8_t* activated_mask_out /* [E] or NULL */,
+                             int32_t* n_activated_out /* [1] or NULL */, int32_t* topk_idx /* [T,k] */,
+                             float* topk_gate /* [T,k] */, float* logits_out /* [T,E] or NULL */, void* workspace,
+                             size_t ws_bytes, void* stream);
+
+/*
+ * team_moe_layer_forward with the routing step replaced by team_moe_route_two_round: the MoE layer of one denoising
+ * step under Algorithm 1, E_A decided on the device from the tokens' classes.  Only experts of E_A can be read.
+ */
+int team_moe_layer_forward_two_round(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router,
+                                     const void* w_gate, const void* w_up, const void* w_down,
+                                     const uint8_t* token_class /* [T] */, uint8_t* activated_mask_out /* [E] or NULL */,
+                                     int32_t* n_activated_out /* [1] or NULL */, void* y, void* workspace,
+                                     size_t ws_bytes, void* stream);
+
 /* Static, NUL-terminated description of a team_status value. */
 const char* team_moe_status_string(int status);
 

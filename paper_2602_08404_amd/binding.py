@@ -18,7 +18,8 @@ TEAM_F32, TEAM_BF16 = 0, 1
 STATUS_OK = 0
 
 EXPORTS = ["team_moe_workspace_size", "team_moe_route", "team_moe_build_dispatch", "team_moe_expert_ffn",
-           "team_moe_combine", "team_moe_layer_forward", "team_moe_status_string"]
+           "team_moe_combine", "team_moe_layer_forward", "team_moe_route_two_round", "team_moe_layer_forward_two_round",
+           "team_moe_status_string"]
 
 
 class TeamMoeError(RuntimeError):
@@ -55,6 +56,8 @@ def lib() -> C.CDLL:
         L.team_moe_expert_ffn.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_combine.argtypes = [cfgp, vp, vp, vp, i32, vp, vp]
         L.team_moe_layer_forward.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.team_moe_route_two_round.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.team_moe_layer_forward_two_round.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_status_string.argtypes = [C.c_int]
         L.team_moe_status_string.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -121,3 +124,20 @@ def team_moe_layer_forward(cfg: Config, x, T: int, w_router, w_gate, w_up, w_dow
     _check(lib().team_moe_layer_forward(C.byref(cfg), _ptr(x), T, _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
                                         _ptr(expert_mask), _ptr(y), _ptr(workspace), ws_bytes,
                                         stream if stream is not None else _stream()), "team_moe_layer_forward")
+
+
+def team_moe_route_two_round(cfg: Config, x, T: int, w_router, token_class, activated_mask_out, n_activated_out, topk_idx, topk_gate,
+                             logits_out=None, workspace=None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().team_moe_route_two_round(C.byref(cfg), _ptr(x), T, _ptr(w_router), _ptr(token_class), _ptr(activated_mask_out),
+                                          _ptr(n_activated_out), _ptr(topk_idx), _ptr(topk_gate), _ptr(logits_out), _ptr(workspace),
+                                          ws_bytes, stream if stream is not None else _stream()), "team_moe_route_two_round")
+
+
+def team_moe_layer_forward_two_round(cfg: Config, x, T: int, w_router, w_gate, w_up, w_down, token_class, activated_mask_out,
+                                     n_activated_out, y, workspace, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().team_moe_layer_forward_two_round(C.byref(cfg), _ptr(x), T, _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+                                                  _ptr(token_class), _ptr(activated_mask_out), _ptr(n_activated_out), _ptr(y),
+                                                  _ptr(workspace), ws_bytes, stream if stream is not None else _stream()),
+           "team_moe_layer_forward_two_round")

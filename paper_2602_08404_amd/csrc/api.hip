@@ -47,7 +47,7 @@ Dims dims_of(const team_moe_config* c, int32_t T) {
 // Workspace layout, sized for max_tokens.  The expert FFN's scratch (control block, h) comes first so that
 // team_moe_expert_ffn and team_moe_layer_forward agree on where it is.
 struct Layout {
-    size_t ctrl, h, logits, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, total;
+    size_t ctrl, h, logits, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, two_round, total;
 };
 Layout layout_of(const team_moe_config* c) {
     const size_t A = (size_t)c->max_tokens * c->top_k;
@@ -65,6 +65,7 @@ Layout layout_of(const team_moe_config* c) {
     L.active = off;       off += align256((size_t)c->num_experts * 4);
     L.n_active = off;     off += 256;
     L.expert_out = off;   off += align256(A * c->hidden * 4);
+    L.two_round = off;    off += 256;                       // bit set E_A and arrival counter of two-round routing
     L.total = off;
     return L;
 }
@@ -168,9 +169,32 @@ int team_moe_combine(const team_moe_config* cfg, const float* expert_out, const 
     return hip_status(team::launch_combine(dims_of(cfg, T), expert_out, topk_gate, inv_pos, y, (hipStream_t)stream));
 }
 
-int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const void* w_gate,
-                           const void* w_up, const void* w_down, const uint8_t* expert_mask, void* y, void* workspace,
-                           size_t ws_bytes, void* stream) {
+int team_moe_route_two_round(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const uint8_t* token_class,
+                             uint8_t* activated_mask_out, int32_t* n_activated_out, int32_t* topk_idx, float* topk_gate,
+                             float* logits_out, void* workspace, size_t ws_bytes, void* stream) {
+    int st = check_cfg(cfg);
+    if (st != TEAM_OK) return st;
+    if ((st = check_T(cfg, T)) != TEAM_OK) return st;
+    if (!x || !w_router || !token_class || !topk_idx || !topk_gate) return TEAM_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(w_router) || (logits_out && !aligned16(logits_out))) return TEAM_ERR_INVALID_ARG;
+    if (cfg->hidden % (cfg->dtype == TEAM_BF16 ? 8 : 4) != 0) return TEAM_ERR_UNSUPPORTED;
+    const Layout L = layout_of(cfg);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || ws_bytes < L.total) return TEAM_ERR_WORKSPACE;
+    char* ws = (char*)workspace;
+    float* logits = logits_out ? logits_out : (float*)(ws + L.logits);
+    clear_stale_error();
+    return hip_status(team::launch_route_two_round(dims_of(cfg, T), x, w_router, token_class, activated_mask_out, n_activated_out,
+                                                   topk_idx, topk_gate, logits, ws + L.two_round, team::CtrlZero{nullptr, 0, 0},
+                                                   (hipStream_t)stream));
+}
+
+namespace {
+
+// The whole layer; the routing step is either the single-round router confined to expert_mask (token_class == nullptr) or
+// the two-round router driven by token_class.
+int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const void* w_gate, const void* w_up,
+                  const void* w_down, const uint8_t* expert_mask, const uint8_t* token_class, uint8_t* activated_mask_out,
+                  int32_t* n_activated_out, void* y, void* workspace, size_t ws_bytes, void* stream) {
     int st = check_cfg(cfg);
     if (st != TEAM_OK) return st;
     if ((st = check_T(cfg, T)) != TEAM_OK) return st;
@@ -188,32 +212,52 @@ int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T,
     int32_t* active = (int32_t*)(ws + L.active);
     int32_t* n_active = (int32_t*)(ws + L.n_active);
     float* expert_out = (float*)(ws + L.expert_out);
+    float* logits = (float*)(ws + L.logits);
     const Dims d = dims_of(cfg, T);
     hipStream_t s = (hipStream_t)stream;
     clear_stale_error();
-    if (team::ffn_bf16_groups_itself(d)) {
-        // Small calls (the block-decoding regime): route -> expert FFN -> combine.  The FFN kernel groups the routing table
-        // itself (every workgroup, in LDS) and writes inv_pos; the selection kernel clears the FFN's control block.
-        if ((st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, (float*)(ws + L.logits),
-                                                team::ffn_ctrl_zero(ws + L.ctrl), s))) != TEAM_OK)
-            return st;
+    // Small calls (the block-decoding regime): route -> expert FFN -> combine.  The FFN kernel groups the routing table itself
+    // (every workgroup, in LDS) and writes inv_pos; the selection kernel clears the FFN's control block.  Otherwise a dispatch
+    // kernel groups the table and clears the control block.
+    const bool short_path = team::ffn_bf16_groups_itself(d);
+    const team::CtrlZero none{nullptr, 0, 0};
+    const team::CtrlZero cz = cfg->dtype == TEAM_BF16 ? team::ffn_ctrl_zero(ws + L.ctrl) : none;
+    if (token_class)
+        st = hip_status(team::launch_route_two_round(d, x, w_router, token_class, activated_mask_out, n_activated_out, topk_idx,
+                                                     topk_gate, logits, ws + L.two_round, short_path ? cz : none, s));
+    else
+        st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, logits, short_path ? cz : none, s));
+    if (st != TEAM_OK) return st;
+    if (short_path) {
         if ((st = hip_status(team::launch_ffn_bf16_from_routing(d, (const uint16_t*)x, topk_idx, inv_pos, (const uint16_t*)w_gate,
                                                                 (const uint16_t*)w_up, (const uint16_t*)w_down, ws + L.ctrl,
                                                                 (uint16_t*)(ws + L.h), expert_out, s))) != TEAM_OK)
             return st;
         return hip_status(team::launch_combine(d, expert_out, topk_gate, inv_pos, y, s));
     }
-    if ((st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, (float*)(ws + L.logits),
-                                            team::CtrlZero{nullptr, 0, 0}, s))) != TEAM_OK)
-        return st;
-    // the dispatch kernel also clears the FFN's control block
-    const team::CtrlZero cz = cfg->dtype == TEAM_BF16 ? team::ffn_ctrl_zero(ws + L.ctrl) : team::CtrlZero{nullptr, 0, 0};
     if ((st = hip_status(team::launch_dispatch(d, topk_idx, offsets, sorted_token, inv_pos, active, n_active, cz, s))) != TEAM_OK)
         return st;
     if ((st = run_ffn(cfg, d, x, offsets, sorted_token, active, n_active, w_gate, w_up, w_down, expert_out, ws + L.ctrl,
                       ws + L.h, s)) != TEAM_OK)
         return st;
     return hip_status(team::launch_combine(d, expert_out, topk_gate, inv_pos, y, s));
+}
+
+}  // namespace
+
+int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const void* w_gate,
+                           const void* w_up, const void* w_down, const uint8_t* expert_mask, void* y, void* workspace,
+                           size_t ws_bytes, void* stream) {
+    return layer_forward(cfg, x, T, w_router, w_gate, w_up, w_down, expert_mask, nullptr, nullptr, nullptr, y, workspace, ws_bytes,
+                         stream);
+}
+
+int team_moe_layer_forward_two_round(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const void* w_gate,
+                                     const void* w_up, const void* w_down, const uint8_t* token_class, uint8_t* activated_mask_out,
+                                     int32_t* n_activated_out, void* y, void* workspace, size_t ws_bytes, void* stream) {
+    if (!token_class) return TEAM_ERR_INVALID_ARG;
+    return layer_forward(cfg, x, T, w_router, w_gate, w_up, w_down, nullptr, token_class, activated_mask_out, n_activated_out, y,
+                         workspace, ws_bytes, stream);
 }
 
 const char* team_moe_status_string(int status) {

@@ -22,6 +22,12 @@ struct CtrlZero {
 // ctrl: control block the selection kernel also clears for an expert FFN that follows without a dispatch kernel.
 hipError_t launch_route(const Dims& d, const void* x, const void* w_router, const uint8_t* mask, int32_t* topk_idx,
                         float* topk_gate, float* logits, CtrlZero ctrl, hipStream_t s);
+// Two-round routing (Algorithm 1): tokens with token_class != 0 are routed over all experts, E_A = union of their picks,
+// the other tokens are routed inside E_A.  state: 256 bytes of device memory (cleared by the call); mask_out [E] bytes and
+// n_activated_out [1] may be null.  T <= 1024.
+hipError_t launch_route_two_round(const Dims& d, const void* x, const void* w_router, const uint8_t* token_class, uint8_t* mask_out,
+                                  int32_t* n_activated_out, int32_t* topk_idx, float* topk_gate, float* logits, void* state,
+                                  CtrlZero ctrl, hipStream_t s);
 // ctrl: control block the dispatch kernel also clears for the expert FFN that follows (words == nullptr: none).
 hipError_t launch_dispatch(const Dims& d, const int32_t* topk_idx, int32_t* offsets, int32_t* sorted_token,
                            int32_t* inv_pos, int32_t* active, int32_t* n_active, CtrlZero ctrl, hipStream_t s);

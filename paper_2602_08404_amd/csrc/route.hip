@@ -9,6 +9,11 @@
 //            allowed experts that beat it (larger logit, or equal logit and lower id): every thread counts its
 //            own rank against the logits in LDS, so there is no serial arg-max loop; experts with rank < k write
 //            themselves into their slot.  One wavefront then turns the selected logits into gates.
+//   two-round select : Algorithm 1 in one launch.  Workgroups are ordered first-round tokens (newly accepted and
+//            hot) before cold tokens.  A first-round workgroup selects over all experts, ORs its picks into a
+//            device-wide bit set E_A and counts itself done; a cold workgroup waits until every first-round
+//            workgroup is counted, then selects inside E_A.  Workgroups start in index order and first-round ones
+//            never wait, so a waiting workgroup can only wait for workgroups that already run.
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -20,6 +25,19 @@ constexpr int EG = 8;                                   // experts per wavefront
 constexpr int LOGIT_GROUP = LOGIT_WAVES * EG;           // experts per workgroup
 constexpr int MAX_E = 256;
 constexpr int SELECT_THREADS = MAX_E;
+constexpr int MAX_TOKENS_2R = 1024;                     // tokens of one two-round call (class bit set in LDS)
+constexpr int TWO_ROUND_MASK_WORDS = MAX_E / 32;
+constexpr int TWO_ROUND_STATE_WORDS = 64;               // 256 bytes of device state, cleared by the logits kernel
+
+struct TwoRound {
+    const uint8_t* token_class;    // [T] non-zero: first-round token
+    uint32_t* mask_bits;           // E_A as a bit set, built with device-scope atomics
+    uint32_t* arrived;             // first-round workgroups that have added their picks
+    uint32_t* error;               // set when a wait ran into its limit
+    uint8_t* mask_out;             // [E] or null
+    int32_t* n_activated_out;      // [1] or null
+    int spin_limit;
+};
 
 template <typename ST> struct Chunk;
 template <> struct Chunk<uint16_t> { static constexpr int N = 8; };
@@ -40,8 +58,11 @@ template <> __device__ __forceinline__ void unpack_chunk<float>(const uint4& v, 
 
 template <typename ST>
 __global__ __launch_bounds__(LOGIT_THREADS) void route_logits_kernel(const ST* __restrict__ x, const ST* __restrict__ w_router,
-                                                                     float* __restrict__ logits, int H, int E) {
+                                                                     float* __restrict__ logits, int H, int E,
+                                                                     uint32_t* __restrict__ zero_words, int n_zero) {
     constexpr int CN = Chunk<ST>::N;
+    // state the selection kernel that follows starts from (two-round routing: bit set and arrival counter)
+    if (zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < n_zero) zero_words[threadIdx.x] = 0u;
     constexpr int XC = 4;          // chunks of the token row per lane per block of 256 chunks
     const int t = blockIdx.y;
     const int lane = threadIdx.x & (WAVE - 1);
@@ -101,84 +122,232 @@ __device__ __forceinline__ unsigned long long select_key(float v, int e) {
     return ((unsigned long long)ord << 32) | (uint32_t)(0xffffffffu - (uint32_t)e);
 }
 
+struct SelectLds {
+    __attribute__((aligned(16))) unsigned long long key[MAX_E];   // 0 for experts that are not candidates
+    float all[MAX_E];                                              // every logit (for the full softmax)
+    float sel_logit[16];
+    int32_t sel_idx[16];
+    int32_t count[SELECT_THREADS / WAVE];
+};
+
+// Thread e ranks expert e among the candidates; on return (after a workgroup barrier) LDS holds the k selected experts in
+// slot order and the number of candidates.  Returns whether expert e is one of the selected.
+__device__ __forceinline__ bool select_rank(SelectLds& sm, float v, bool ok, int e, int E, int k) {
+    const int lane = e & (WAVE - 1);
+    const unsigned long long my_key = ok ? select_key(v, e) : 0ull;
+    if (e < 16) { sm.sel_idx[e] = -1; sm.sel_logit[e] = 0.f; }
+    sm.all[e] = e < E ? v : -INFINITY;
+    sm.key[e] = my_key;
+    const unsigned long long ok_lanes = __ballot(ok);
+    if (lane == 0) sm.count[e / WAVE] = __popcll(ok_lanes);
+    __syncthreads();
+    bool selected = false;
+    if (ok) {                                                         // rank = number of candidates that beat this one
+        int rank = 0;
+        const int n2 = (E + 1) / 2;
+#pragma unroll 8
+        for (int j2 = 0; j2 < n2; ++j2) {
+            const ulonglong2 o = *reinterpret_cast<const ulonglong2*>(sm.key + 2 * j2);   // same address in all lanes: broadcast
+            rank += (o.x > my_key) + (o.y > my_key);
+        }
+        if (rank < k) { sm.sel_idx[rank] = e; sm.sel_logit[rank] = v; selected = true; }
+    }
+    __syncthreads();
+    return selected;
+}
+
+// Gates of token t from the selection in LDS; called by wavefront 0 only, lane s owns slot s.
+__device__ __forceinline__ void write_gates(const SelectLds& sm, int t, int lane, int E, int k, int renormalize,
+                                            int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate) {
+    int n_allowed = 0;
+#pragma unroll
+    for (int w = 0; w < SELECT_THREADS / WAVE; ++w) n_allowed += sm.count[w];
+    const int k_eff = min(k, n_allowed);
+    const float my_logit = lane < 16 ? sm.sel_logit[lane] : 0.f;
+    float gate = 0.f;
+    if (renormalize) {
+        const float m = sm.sel_logit[0];
+        const float w = lane < k_eff ? expf(my_logit - m) : 0.f;
+        const float den = wave_sum(w);
+        gate = lane < k_eff ? w / den : 0.f;
+    } else {                                                         // selected entries of the softmax over all E experts
+        float m = -INFINITY;
+        for (int j = lane; j < E; j += WAVE) m = fmaxf(m, sm.all[j]);
+        m = wave_max(m);
+        float dsum = 0.f;
+        for (int j = lane; j < E; j += WAVE) dsum += expf(sm.all[j] - m);
+        const float den = wave_sum(dsum);
+        gate = lane < k_eff ? expf(my_logit - m) / den : 0.f;
+    }
+    if (lane < k) {
+        topk_idx[(size_t)t * k + lane] = lane < k_eff ? sm.sel_idx[lane] : -1;
+        topk_gate[(size_t)t * k + lane] = gate;
+    }
+}
+
+__device__ __forceinline__ void clear_ffn_ctrl(const CtrlZero& ctrl, int tid, int E) {
+    if (tid < ctrl.header) ctrl.words[tid] = 0;
+    if (tid < E) ctrl.words[ctrl.header + tid * ctrl.stride] = 0;
+}
+
 __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(const float* __restrict__ logits, const uint8_t* __restrict__ mask,
                                                                       int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate,
                                                                       int E, int k, int renormalize, CtrlZero ctrl) {
-    __shared__ __attribute__((aligned(16))) unsigned long long s_key[MAX_E];   // 0 for experts that are not candidates
-    __shared__ float s_all[MAX_E];                                              // every logit (for the full softmax)
-    __shared__ float s_sel_logit[16];
-    __shared__ int32_t s_sel_idx[16];
-    __shared__ int32_t s_count[SELECT_THREADS / WAVE];
+    __shared__ SelectLds sm;
     const int t = blockIdx.x;
     const int e = threadIdx.x;
-    const int lane = e & (WAVE - 1);
-    if (ctrl.words && t == 0) {                     // control block of an expert FFN that follows without a dispatch kernel
-        if (e < ctrl.header) ctrl.words[e] = 0;
-        if (e < E) ctrl.words[ctrl.header + e * ctrl.stride] = 0;
-    }
+    if (ctrl.words && t == 0) clear_ffn_ctrl(ctrl, e, E);   // control block of an expert FFN that follows without a dispatch kernel
     float v = 0.f;
     bool ok = false;
     if (e < E) {
         v = logits[(size_t)t * E + e] + 0.f;                         // -0 -> +0 so that equal logits compare equal
         ok = (mask == nullptr || mask[e] != 0) && v == v;            // a NaN logit is never selected
     }
-    const unsigned long long my_key = ok ? select_key(v, e) : 0ull;
-    if (e < 16) { s_sel_idx[e] = -1; s_sel_logit[e] = 0.f; }
-    s_all[e] = e < E ? v : -INFINITY;
-    s_key[e] = my_key;
-    const unsigned long long ok_lanes = __ballot(ok);
-    if (lane == 0) s_count[e / WAVE] = __popcll(ok_lanes);
-    __syncthreads();
-    if (ok) {                                                         // rank = number of candidates that beat this one
-        int rank = 0;
-        const int n2 = (E + 1) / 2;
-#pragma unroll 8
-        for (int j2 = 0; j2 < n2; ++j2) {
-            const ulonglong2 o = *reinterpret_cast<const ulonglong2*>(s_key + 2 * j2);   // same address in all lanes: broadcast
-            rank += (o.x > my_key) + (o.y > my_key);
-        }
-        if (rank < k) { s_sel_idx[rank] = e; s_sel_logit[rank] = v; }
-    }
-    __syncthreads();
-    if (e >= WAVE) return;
-    // ---- gates by wavefront 0: lane s owns slot s
-    int n_allowed = 0;
+    select_rank(sm, v, ok, e, E, k);
+    if (e < WAVE) write_gates(sm, t, e, E, k, renormalize, topk_idx, topk_gate);
+}
+
+// ---- two-round routing (Algorithm 1) -------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t load_agent(const uint32_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+__global__ __launch_bounds__(SELECT_THREADS) void route_select_two_round_kernel(const float* __restrict__ logits, TwoRound tr,
+                                                                                int32_t* __restrict__ topk_idx,
+                                                                                float* __restrict__ topk_gate, int T, int E, int k,
+                                                                                int renormalize, CtrlZero ctrl) {
+    __shared__ SelectLds sm;
+    __shared__ unsigned long long s_cls[MAX_TOKENS_2R / WAVE];   // bit t: token t is a first-round token
+    __shared__ uint32_t s_bits[TWO_ROUND_MASK_WORDS];
+    __shared__ int s_last;
+    const int b = blockIdx.x;
+    const int e = threadIdx.x;
+    const int lane = e & (WAVE - 1);
+    const int wave = e / WAVE;
+    if (ctrl.words && b == 0) clear_ffn_ctrl(ctrl, e, E);
+
+    // ---- which token is this workgroup's: the b-th in the order (first-round tokens ascending, then cold tokens ascending)
 #pragma unroll
-    for (int w = 0; w < SELECT_THREADS / WAVE; ++w) n_allowed += s_count[w];
-    const int k_eff = min(k, n_allowed);
-    const float my_logit = lane < 16 ? s_sel_logit[lane] : 0.f;
-    float gate = 0.f;
-    if (renormalize) {
-        const float m = s_sel_logit[0];
-        const float w = lane < k_eff ? expf(my_logit - m) : 0.f;
-        const float den = wave_sum(w);
-        gate = lane < k_eff ? w / den : 0.f;
-    } else {                                                         // selected entries of the softmax over all E experts
-        float m = -INFINITY;
-        for (int j = lane; j < E; j += WAVE) m = fmaxf(m, s_all[j]);
-        m = wave_max(m);
-        float dsum = 0.f;
-        for (int j = lane; j < E; j += WAVE) dsum += expf(s_all[j] - m);
-        const float den = wave_sum(dsum);
-        gate = lane < k_eff ? expf(my_logit - m) / den : 0.f;
+    for (int j = 0; j < MAX_TOKENS_2R / SELECT_THREADS; ++j) {
+        const int tok = j * SELECT_THREADS + e;
+        const bool first = tok < T && tr.token_class[tok] != 0;
+        const unsigned long long bal = __ballot(first);
+        if (lane == 0) s_cls[j * (SELECT_THREADS / WAVE) + wave] = bal;
     }
-    if (lane < k) {
-        topk_idx[(size_t)t * k + lane] = lane < k_eff ? s_sel_idx[lane] : -1;
-        topk_gate[(size_t)t * k + lane] = gate;
+    __syncthreads();
+    int n_first = 0, t = 0;
+    {
+        constexpr int NW = MAX_TOKENS_2R / WAVE;
+        const int n_words = (T + WAVE - 1) / WAVE;
+        int c1[NW];
+#pragma unroll
+        for (int w = 0; w < NW; ++w) { c1[w] = w < n_words ? __popcll(s_cls[w]) : 0; n_first += c1[w]; }
+        const bool want_first = b < n_first;
+        int target = want_first ? b : b - n_first;
+        unsigned long long bits = 0ull;
+        int word = 0;
+        bool found = false;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const int left = T - w * WAVE;                                             // tokens of this word that exist
+            const unsigned long long valid = left >= WAVE ? ~0ull : (left > 0 ? ((1ull << left) - 1ull) : 0ull);
+            const unsigned long long cand = want_first ? s_cls[w] : (~s_cls[w] & valid);
+            const int c = __popcll(cand);
+            if (!found) {
+                if (target < c) { found = true; word = w; bits = cand; }
+                else target -= c;
+            }
+        }
+        for (int i = 0; i < target; ++i) bits &= bits - 1ull;                          // drop the lower set bits
+        t = word * WAVE + (bits ? __builtin_ctzll(bits) : 0);
     }
+    const bool is_first = b < n_first;
+
+    float v = 0.f;
+    bool ok = false;
+    if (e < E) {
+        v = logits[(size_t)t * E + e] + 0.f;
+        ok = v == v;
+    }
+    if (!is_first) {
+        // ---- cold token: wait until every first-round workgroup has added its picks to E_A, then route inside E_A
+        if (e == 0) {
+            int it = 0;
+            while (load_agent(tr.arrived) < (uint32_t)n_first) {
+                if (++it > tr.spin_limit) { __hip_atomic_store(tr.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
+                __builtin_amdgcn_s_sleep(8);
+            }
+        }
+        __syncthreads();
+        if (e < TWO_ROUND_MASK_WORDS) s_bits[e] = load_agent(tr.mask_bits + e);
+        __syncthreads();
+        ok = ok && ((s_bits[e >> 5] >> (e & 31)) & 1u);
+    }
+    const bool selected = select_rank(sm, v, ok, e, E, k);
+    if (is_first) {
+        // ---- first-round token: E_A |= picks; the picks are in place (acknowledged) before the arrival is counted
+        const unsigned long long sel_lanes = __ballot(selected);
+        if (lane == 0) {
+            const uint32_t lo = (uint32_t)sel_lanes, hi = (uint32_t)(sel_lanes >> 32);
+            if (lo) __hip_atomic_fetch_or(tr.mask_bits + 2 * wave, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (hi) __hip_atomic_fetch_or(tr.mask_bits + 2 * wave + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (e == 0) {
+            const uint32_t before = __hip_atomic_fetch_add(tr.arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = before + 1u == (uint32_t)n_first;
+        }
+        __syncthreads();
+        if (s_last) {                                   // E_A is complete: publish it as a byte mask, and its size
+            if (e < TWO_ROUND_MASK_WORDS) s_bits[e] = load_agent(tr.mask_bits + e);
+            __syncthreads();
+            if (tr.mask_out && e < E) tr.mask_out[e] = (uint8_t)((s_bits[e >> 5] >> (e & 31)) & 1u);
+            if (tr.n_activated_out && e == 0) {
+                int n = 0;
+#pragma unroll
+                for (int w = 0; w < TWO_ROUND_MASK_WORDS; ++w) n += __popc(s_bits[w]);
+                *tr.n_activated_out = n;
+            }
+        }
+    } else if (n_first == 0 && b == 0) {                // no first-round token: E_A is empty
+        if (tr.mask_out && e < E) tr.mask_out[e] = 0;
+        if (tr.n_activated_out && e == 0) *tr.n_activated_out = 0;
+    }
+    if (e < WAVE) write_gates(sm, t, e, E, k, renormalize, topk_idx, topk_gate);
+}
+
+static hipError_t launch_logits(const Dims& d, const void* x, const void* w_router, float* logits, uint32_t* zero_words, int n_zero,
+                                hipStream_t s) {
+    dim3 grid((d.E + LOGIT_GROUP - 1) / LOGIT_GROUP, d.T), block(LOGIT_THREADS);
+    if (d.bf16)
+        hipLaunchKernelGGL(route_logits_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)x, (const uint16_t*)w_router, logits, d.H,
+                           d.E, zero_words, n_zero);
+    else
+        hipLaunchKernelGGL(route_logits_kernel<float>, grid, block, 0, s, (const float*)x, (const float*)w_router, logits, d.H, d.E,
+                           zero_words, n_zero);
+    return hipGetLastError();
 }
 
 hipError_t launch_route(const Dims& d, const void* x, const void* w_router, const uint8_t* mask, int32_t* topk_idx,
                         float* topk_gate, float* logits, CtrlZero ctrl, hipStream_t s) {
-    dim3 grid((d.E + LOGIT_GROUP - 1) / LOGIT_GROUP, d.T), block(LOGIT_THREADS);
-    if (d.bf16)
-        hipLaunchKernelGGL(route_logits_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)x, (const uint16_t*)w_router, logits, d.H, d.E);
-    else
-        hipLaunchKernelGGL(route_logits_kernel<float>, grid, block, 0, s, (const float*)x, (const float*)w_router, logits, d.H, d.E);
-    hipError_t err = hipGetLastError();
+    hipError_t err = launch_logits(d, x, w_router, logits, nullptr, 0, s);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(route_select_kernel, dim3(d.T), dim3(SELECT_THREADS), 0, s, logits, mask, topk_idx, topk_gate, d.E, d.k,
                        d.renormalize, ctrl);
+    return hipGetLastError();
+}
+
+hipError_t launch_route_two_round(const Dims& d, const void* x, const void* w_router, const uint8_t* token_class, uint8_t* mask_out,
+                                  int32_t* n_activated_out, int32_t* topk_idx, float* topk_gate, float* logits, void* state,
+                                  CtrlZero ctrl, hipStream_t s) {
+    if (d.T > MAX_TOKENS_2R || d.E > 32 * TWO_ROUND_MASK_WORDS) return hipErrorInvalidValue;
+    uint32_t* words = (uint32_t*)state;                 // [0..7] bit set E_A, [16] arrivals, [32] error flag
+    hipError_t err = launch_logits(d, x, w_router, logits, words, TWO_ROUND_STATE_WORDS, s);
+    if (err != hipSuccess) return err;
+    TwoRound tr;
+    tr.token_class = token_class; tr.mask_bits = words; tr.arrived = words + 16; tr.error = words + 32;
+    tr.mask_out = mask_out; tr.n_activated_out = n_activated_out; tr.spin_limit = 1 << 16;
+    hipLaunchKernelGGL(route_select_two_round_kernel, dim3(d.T), dim3(SELECT_THREADS), 0, s, logits, tr, topk_idx, topk_gate, d.T, d.E,
+                       d.k, d.renormalize, ctrl);
     return hipGetLastError();
 }
 

@@ -26,7 +26,7 @@ from typing import Dict, Optional
 import numpy as np
 
 # tensor tags of the Philox key
-TAG_X_BASE, TAG_X_NOISE, TAG_W_ROUTER, TAG_W_GATE, TAG_W_UP, TAG_W_DOWN, TAG_MASK, TAG_PERM = range(1, 9)
+TAG_X_BASE, TAG_X_NOISE, TAG_W_ROUTER, TAG_W_GATE, TAG_W_UP, TAG_W_DOWN, TAG_MASK, TAG_PERM, TAG_CLASS = range(1, 10)
 
 WEIGHT_STD = 0.02          # "weights ~ N(0, 0.02)" read as standard deviation 0.02
 RMS_EPS = 1e-6
@@ -208,3 +208,12 @@ def activated_set_by_summed_probability(logits: np.ndarray, M: int) -> np.ndarra
 
 def token_permutation(T: int, seed: int = 0) -> np.ndarray:
     return _stream(seed, TAG_PERM, 0, T).permutation(T)
+
+
+def token_classes(T: int, n_first: int, seed: int = 0, layer: int = 0) -> np.ndarray:
+    """Byte vector [T] with exactly n_first ones at seeded random positions: the tokens of a denoising step that
+    take part in the first routing round (newly accepted and hot tokens); the zeros are the cold tokens."""
+    perm = _stream(seed, TAG_CLASS, layer, n_first).permutation(T)
+    c = np.zeros(T, np.uint8)
+    c[perm[:n_first]] = 1
+    return c

@@ -129,6 +129,35 @@ def gpu_layer(case: Case, mask: Optional[np.ndarray], ws=None) -> np.ndarray:
     return y_to_host(y), y
 
 
+def gpu_route_two_round(case: Case, token_class: np.ndarray, want_logits=True, ws=None):
+    s = case.shape
+    idx = torch.full((s.T, s.k), -7, dtype=torch.int32, device=DEV)
+    gate = torch.full((s.T, s.k), -7.0, dtype=torch.float32, device=DEV)
+    mask = torch.full((s.E,), 9, dtype=torch.uint8, device=DEV)
+    n_act = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+    logits = torch.empty((s.T, s.E), dtype=torch.float32, device=DEV) if want_logits else None
+    if ws is None:
+        ws = torch.empty(tm.team_moe_workspace_size(case.cfg), dtype=torch.uint8, device=DEV)
+    tm.team_moe_route_two_round(case.cfg, case.d_x, s.T, case.d_w["router"], torch.from_numpy(token_class).to(DEV), mask, n_act,
+                                idx, gate, logits, ws)
+    torch.cuda.synchronize()
+    return (idx.cpu().numpy(), gate.cpu().numpy(), mask.cpu().numpy(), int(n_act.cpu().numpy()[0]),
+            logits.cpu().numpy() if want_logits else None)
+
+
+def gpu_layer_two_round(case: Case, token_class: np.ndarray, ws=None):
+    s = case.shape
+    if ws is None:
+        ws = torch.empty(tm.team_moe_workspace_size(case.cfg), dtype=torch.uint8, device=DEV)
+    y = torch.empty((s.T, s.H), dtype=out_dtype(s), device=DEV)
+    mask = torch.full((s.E,), 9, dtype=torch.uint8, device=DEV)
+    n_act = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+    tm.team_moe_layer_forward_two_round(case.cfg, case.d_x, s.T, case.d_w["router"], case.d_w["gate"], case.d_w["up"],
+                                        case.d_w["down"], torch.from_numpy(token_class).to(DEV), mask, n_act, y, ws)
+    torch.cuda.synchronize()
+    return y_to_host(y), y, mask.cpu().numpy(), int(n_act.cpu().numpy()[0])
+
+
 # ----------------------------------------------------------------------------- oracle side
 def oracle_layer(case: Case, mask, threads=0):
     s = case.shape
@@ -241,3 +270,51 @@ def full_parity(case: Case, mask, threads=0):
     layer_err, n_band = check_layer(case, mask, y_gpu, g_idx, g_gate, o_y, o_idx, set_safe)
     return {"ffn_err": float(ffn_err), "layer_err": layer_err, "band_tokens": n_band, "unsafe": int((~set_safe).sum()),
             "n_active": n_active}
+
+
+def two_round_parity(case: Case, token_class: np.ndarray, threads=0):
+    """team_moe_route_two_round and team_moe_layer_forward_two_round against the oracle's Algorithm 1.
+
+    E_A is the union of the first-round picks, so a first-round token inside the gap band may legitimately move one
+    expert in or out of it.  What is compared: every first-round token against the oracle's free routing; the GPU's E_A
+    against the union of the GPU's own first-round picks (always) and against the oracle's E_A (when no first-round
+    token is in the band); every cold token against the oracle's routing confined to the GPU's E_A; the layer output
+    against the oracle's layer under the GPU's E_A, and bitwise against team_moe_layer_forward given that E_A."""
+    import dataclasses
+    from types import SimpleNamespace
+    s = case.shape
+    first = np.nonzero(token_class)[0]
+    cold = np.nonzero(token_class == 0)[0]
+    o_logits = oracle_logits(case)
+    o_mask, o_idx, o_gate = orc.route_two_round(o_logits, s.k, token_class, s.renormalize)
+    g_idx, g_gate, g_mask, g_n, g_logits = gpu_route_two_round(case, token_class)
+    assert set(np.unique(g_mask).tolist()) <= {0, 1} and g_n == int(g_mask.sum())
+    # first round
+    sub = lambda rows: SimpleNamespace(shape=dataclasses.replace(s, T=len(rows)))
+    first_safe = True
+    if len(first):
+        set_safe, _ = check_route(sub(first), None, g_idx[first], g_gate[first], g_logits[first], o_idx[first], o_gate[first],
+                                  o_logits[first])
+        first_safe = bool(set_safe.all())
+    union = np.zeros(s.E, np.uint8)
+    picks = g_idx[first]
+    union[np.unique(picks[picks >= 0])] = 1
+    assert np.array_equal(g_mask, union)
+    if first_safe:
+        assert np.array_equal(g_mask, o_mask)
+    # second round, inside the GPU's E_A
+    if len(cold):
+        c_idx, c_gate = orc.route_from_logits(o_logits[cold], s.k, s.renormalize, g_mask)
+        check_route(sub(cold), g_mask, g_idx[cold], g_gate[cold], g_logits[cold], c_idx, c_gate, o_logits[cold])
+    # scores kept in the workspace: same tables
+    g2 = gpu_route_two_round(case, token_class, want_logits=False)
+    assert np.array_equal(g2[0], g_idx) and np.array_equal(g2[1], g_gate) and np.array_equal(g2[2], g_mask)
+    # whole layer
+    y_gpu, y_dev, l_mask, l_n = gpu_layer_two_round(case, token_class)
+    assert np.array_equal(l_mask, g_mask) and l_n == g_n
+    _, y_ref_dev = gpu_layer(case, g_mask)
+    assert torch.equal(y_dev, y_ref_dev)
+    o_y, o_idx_m, _ = oracle_layer(case, g_mask, threads)
+    set_safe_m, _ = safe_tokens(o_logits, g_mask, s.k)
+    layer_err, n_band = check_layer(case, g_mask, y_gpu, g_idx, g_gate, o_y, o_idx_m, set_safe_m)
+    return {"n_first": int(len(first)), "n_activated": g_n, "first_safe": first_safe, "layer_err": layer_err, "band_tokens": n_band}

@@ -84,6 +84,15 @@ def test_bad_call_arguments_are_rejected_before_any_launch():
     assert lib.team_moe_layer_forward(C.byref(cfg), fake, 8, fake, fake, fake, fake, None, fake, fake, 1024, st) == -3
     assert lib.team_moe_layer_forward(C.byref(cfg), fake, 8, fake, fake, fake, fake, None, fake, odd, 1 << 30, st) == -3
     assert lib.team_moe_expert_ffn(C.byref(cfg), fake, 8, fake, fake, fake, fake, fake, fake, fake, fake, fake, 16, st) == -3
+    # two-round routing: token classes and a full workspace are required
+    assert lib.team_moe_route_two_round(C.byref(cfg), fake, 8, fake, None, None, None, fake, fake, None, fake, 1 << 30, st) == -1
+    assert lib.team_moe_route_two_round(C.byref(cfg), fake, 8, fake, fake, None, None, fake, fake, None, None, 0, st) == -3
+    assert lib.team_moe_route_two_round(C.byref(cfg), fake, 8, fake, fake, None, None, fake, fake, fake, fake, 1024, st) == -3
+    assert lib.team_moe_route_two_round(C.byref(cfg), fake, 40, fake, fake, None, None, fake, fake, None, fake, 1 << 30, st) == -1
+    assert lib.team_moe_layer_forward_two_round(C.byref(cfg), fake, 8, fake, fake, fake, fake, None, None, None, fake, fake,
+                                                1 << 30, st) == -1
+    assert lib.team_moe_layer_forward_two_round(C.byref(cfg), fake, 8, fake, fake, fake, fake, fake, None, None, fake, None,
+                                                0, st) == -3
     # NULL cfg / NULL size pointer
     assert lib.team_moe_workspace_size(None, C.byref(C.c_size_t())) == -1
     assert lib.team_moe_workspace_size(C.byref(cfg), None) == -1

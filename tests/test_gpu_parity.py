@@ -215,3 +215,58 @@ def test_dispatch_treats_out_of_range_ids_as_padding():
     ref = orc.dispatch(clean, s.E)
     for a, b in zip((off, st, inv, act, na), ref):
         assert np.array_equal(np.asarray(a), np.asarray(b))
+
+
+# ----------------------------------------------------------------------------- two-round routing (Algorithm 1) on the device
+@pytest.mark.parametrize("n_first", [4, 1, 16, 32, 0])
+def test_cfg2_two_round_routing(cfg2_case, n_first):
+    """Block of 32 tokens; 4 first-round tokens (a few newly accepted plus hot ones) activate about 32 experts."""
+    cls = gen.token_classes(32, n_first, seed=n_first)
+    rep = hz.two_round_parity(cfg2_case, cls)
+    say("two-round cfg2", rep)
+    assert rep["n_activated"] <= min(128, 8 * n_first)
+    if n_first in (4, 16):
+        assert rep["first_safe"]                      # the exact-E_A comparison was not skipped
+
+
+@pytest.mark.parametrize("renorm", [1, 0])
+def test_cfg1_two_round_routing_fp32(cfg1_case, renorm):
+    s = gen.scaled(gen.CFG1, renormalize=renorm)
+    case = hz.Case.make(s, cfg1_case.x, cfg1_case.w, cfg1_case.wf, cfg1_case.d_w)
+    for n_first in (0, 1, 3, 8):
+        say("two-round cfg1", renorm, hz.two_round_parity(case, gen.token_classes(s.T, n_first, seed=1)))
+
+
+def test_cfg2_two_round_is_deterministic_with_a_reused_workspace(cfg2_case):
+    ws = torch.empty(tm.team_moe_workspace_size(cfg2_case.cfg), dtype=torch.uint8, device=hz.DEV)
+    ws.fill_(0xAB)                                    # the call clears what it needs
+    cls_a, cls_b = gen.token_classes(32, 4, seed=0), gen.token_classes(32, 9, seed=1)
+    ya, _, ma, na = hz.gpu_layer_two_round(cfg2_case, cls_a, ws)
+    yb, _, mb, nb = hz.gpu_layer_two_round(cfg2_case, cls_b, ws)
+    ya2, _, ma2, na2 = hz.gpu_layer_two_round(cfg2_case, cls_a, ws)
+    assert np.array_equal(ya, ya2) and np.array_equal(ma, ma2) and na == na2
+    assert nb >= na or not np.array_equal(ma, mb)
+
+
+def test_cfg3_two_round_with_candidate_branches(cfg2_case):
+    """128 live tokens (4 candidate branches of a block); the hot tokens of every branch route freely."""
+    s = gen.CFG3
+    case = cfg2_case.with_x(s, gen.make_x(s, seed=0, kind="candidates", noise_std=0.1))
+    say("two-round cfg3", hz.two_round_parity(case, gen.token_classes(s.T, 12, seed=3)))
+
+
+def test_cfg5_two_round_256_experts(cfg5_case):
+    """All eight words of the E_A bit set and several words of the token-class bit set."""
+    s = gen.CFG5
+    for n_first in (6, 200):
+        say("two-round cfg5", hz.two_round_parity(cfg5_case, gen.token_classes(s.T, n_first, seed=5)))
+
+
+def test_two_round_limits_and_ragged_counts():
+    s = gen.MoEShape("limits", T=1024, H=256, E=256, k=2, I=128, dtype="bf16")
+    case = hz.Case.make(s, gen.make_x(s, seed=3), gen.make_weights(s, seed=3))
+    say("two-round limits", hz.two_round_parity(case, gen.token_classes(1024, 37, seed=3)))
+    for T, n_first in ((77, 5), (65, 64), (129, 1)):
+        sT = gen.scaled(s, T=T)
+        caseT = hz.Case.make(sT, gen.make_x(sT, seed=4), case.w, case.wf, case.d_w)
+        say("two-round ragged", T, hz.two_round_parity(caseT, gen.token_classes(T, n_first, seed=T)))
