@@ -203,6 +203,36 @@ def main() -> int:
                 "traffic": PMC_TRAFFIC_BYTES.get((wl, headline)), "bytes_per_launch": touched[headline] * bytes_per_expert,
                 "launch_us": head["ffn_ms"] * 1e3}
 
+    # ---- the same layer with the activated set decided on the device (Algorithm 1: two-round routing from token classes)
+    two_round = None
+    if wl != "cfg4":
+        n_first = max(1, T // 8)
+        cls = [torch.from_numpy(gen.token_classes(T, n_first, seed=c)).to(dev) for c in range(n_sets)]
+        d_nact = torch.zeros((1,), dtype=torch.int32, device=dev)
+        d_mask = torch.zeros((E,), dtype=torch.uint8, device=dev)
+
+        def layer2(i):
+            d_w, xs, ms = sets[i % n_sets]
+            tm.team_moe_layer_forward_two_round(cfg, xs[0], T, d_w["router"], d_w["gate"], d_w["up"], d_w["down"], cls[i % n_sets],
+                                                d_mask, d_nact, y, ws)
+
+        n_act = []
+        for c in range(n_sets):
+            layer2(c)
+            torch.cuda.synchronize()
+            n_act.append(int(d_nact.item()))
+        n2 = max(50, steps // 2)
+        for i in range(10):
+            layer2(i)
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for i in range(n2):
+            layer2(i)
+        torch.cuda.synchronize()
+        s2 = (time.perf_counter() - t_begin) / n2
+        two_round = {"first_round_tokens": n_first, "activated": float(np.mean(n_act)), "ms_per_layer": s2 * 1e3, "tokens_per_s": T / s2}
+        log(f"[bench] {wl} two-round routing: {n_first} first-round tokens -> |E_A| = {np.mean(n_act):.1f}, layer {s2 * 1e6:.1f} us")
+
     # ---- context: plain device-to-device copy rate (read + write bytes) of 1 GiB, the practical streaming ceiling
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
@@ -248,7 +278,7 @@ def main() -> int:
            "warmup": warmup, "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16", "data": "synthetic",
            "config": {"workload": desc, "tokens": T, "activated": headline, "touched": touched[headline], "layers_per_step": layers_per_step},
-           "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep, "device_copy_GBps": copy_gbps}
+           "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep, "two_round": two_round, "device_copy_GBps": copy_gbps}
     if wl == "cfg4":
         out["ms_per_block_16_steps"] = sec_per_step * 1e3 * 16
     print(json.dumps(out), flush=True)
