@@ -76,6 +76,23 @@ __device__ __forceinline__ int opaque(int v) {
     return v;
 }
 
+// One 32-bit load at (uniform base + per-lane byte offset), complete on return.
+__device__ __forceinline__ int global_read_i32(const int32_t* base_uniform, uint32_t byte_off) {
+    int v;
+    asm volatile("global_load_dword %0, %1, %2\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(byte_off), "s"(base_uniform) : "memory");
+    return v;
+}
+// LDS accesses and the workgroup barrier as explicit instructions (see the item loop for why).
+__device__ __forceinline__ void lds_write_f4(uint32_t a, const f32x4_t& v) { asm volatile("ds_write_b128 %0, %1" ::"v"(a), "v"(v) : "memory"); }
+__device__ __forceinline__ f32x4_t lds_read_f4(uint32_t a) {
+    f32x4_t v;
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
+    return v;
+}
+// Every LDS operation of this wavefront has completed, then all wavefronts of the workgroup meet.  Vector-memory
+// operations in flight are NOT waited for.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 constexpr int ctz_cap4(int c) { return (c % 16 == 0) ? 4 : (c % 8 == 0) ? 3 : (c % 4 == 0) ? 2 : (c % 2 == 0) ? 1 : 0; }
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
 
@@ -88,6 +105,31 @@ struct Slice {
     __device__ static __forceinline__ int phys(int r, int c) { return r * C + (c ^ (r >> (4 - V))); }
 };
 
+
+// Products of one item for one wavefront: for every K-step s and weight sub-tile rb, one 16-byte LDS read of the weight
+// operand and one matrix instruction per token tile.  The reads run READ_AHEAD steps ahead of the matrix instructions
+// that consume them (a scheduling barrier per step pins that order), so LDS latency is paid once per item, not per step.
+constexpr int READ_AHEAD = 2;
+template <class SL, int KS, int RBN, bool TWO, int KSM_>
+__device__ __forceinline__ void mfma_stream(const char* region, int n, int q, const bf16x8_t (&opr)[NT][KSM_], f32x4_t (&acc)[RBN][NT]) {
+    constexpr int N = KS * RBN;
+    bf16x8_t w[READ_AHEAD + 1];
+    auto read = [&](int j) {
+        const int s = j / RBN, rb = j % RBN;
+        return *reinterpret_cast<const bf16x8_t*>(region + rb * SL::BYTES + SL::phys(n, 4 * s + q) * 16);
+    };
+#pragma unroll
+    for (int j = 0; j < READ_AHEAD && j < N; ++j) w[j] = read(j);
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (j + READ_AHEAD < N) w[(j + READ_AHEAD) % (READ_AHEAD + 1)] = read(j + READ_AHEAD);
+        const int s = j / RBN, rb = j % RBN;
+        acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[j % (READ_AHEAD + 1)], opr[0][s], acc[rb][0], 0, 0, 0);
+        if (TWO) acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[j % (READ_AHEAD + 1)], opr[1][s], acc[rb][1], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
 
 }  // namespace
 
@@ -116,10 +158,6 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     __shared__ int32_t s_off[FFN_MAX_E + 1];
     __shared__ int32_t s_sorted[FFN_LAYER_MAX_ROWS];     // token of every row, when the kernel groups the routing table itself
     __shared__ int32_t s_nact;
-    typedef f32x4_t (*red_a_t)[NT][WAVE];
-    typedef f32x4_t (*red_b_t)[RB][NT][WAVE];
-    red_a_t red_a = reinterpret_cast<red_a_t>(s_mem + LDS_BYTES - RED_A);
-    red_b_t red_b = reinterpret_cast<red_b_t>(s_mem + LDS_BYTES - RED_B);
 
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1);
@@ -129,11 +167,15 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
 
     int n_act;
     const bool own_tables = topk_idx != nullptr;
+    // the token of every row sits in LDS when the table fits (always, when the kernel groups the routing table itself)
+    const bool lds_tokens = own_tables || A <= FFN_LAYER_MAX_ROWS;
     if (!own_tables) {
         // ---- tables into LDS (one global round trip)
         n_act = min(max(*n_active, 0), E);
         for (int i = tid; i < E; i += FFN_THREADS) s_slot_e[i] = active[i];
         for (int i = tid; i <= E; i += FFN_THREADS) s_off[i] = min(max(offsets[i], 0), A);
+        if (lds_tokens)
+            for (int i = tid; i < A; i += FFN_THREADS) s_sorted[i] = sorted_token[i];
     } else {
         // ---- small calls (T <= 64, at most FFN_LAYER_MAX_ROWS pairs): every workgroup groups the routing table itself,
         // in LDS, instead of waiting for a separate grouping kernel.  Same method and same result as that kernel: a token
@@ -221,177 +263,221 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     bf16x8_t opr[NT][KSM];                   // token operand (x rows for gate/up items, h rows for down items)
     int cur_key = -1;                        // (phase, slot) the operand registers hold; -1: nothing
     int ready_slot = -1;                     // slot whose h this workgroup has already acquired
-
     int pend = 0;                            // finished gate/up items of the current slot not yet published
-    {
-        for (int step = 0; step < n_mine; ++step) {   // this workgroup's gate/up items, then its down items
-            const bool is_a = step < n_a;
-            const int li = is_a ? a_begin + step : b_begin + (step - n_a);
-            const int tiles = is_a ? TILES_A : TILES_B;
-            const int a = li / tiles, it = li - a * tiles;
-            const int e = s_slot_e[a];
-            const bool e_ok = e >= 0 && e < E;
-            const int r0 = e_ok ? s_off[e] : 0;
-            const int m = e_ok ? max(s_off[e + 1] - r0, 0) : 0;
-            const int key = (is_a ? 0 : 0x10000) | a;
-            const int ln = opaque(lane);
-            const int n = ln & 15, q = ln >> 4;
-            if (is_a) {
-                // =============================================================== gate/up item
-                char* region = s_mem + wave * SA::BYTES;
-                if (m > 0) {
-                    const size_t ebase = (size_t)e * I;
+
+    // While direct-to-LDS loads of the NEXT item are in flight, every LDS read below is written as explicit
+    // instructions: the compiler would otherwise wait for all outstanding direct-to-LDS loads before any LDS read it
+    // can see, and so would the fence of __syncthreads().
+    const uint32_t tab_e = tiled::lds_addr(s_slot_e), tab_off = tiled::lds_addr(s_off), tab_sorted = tiled::lds_addr(s_sorted);
+    struct Item {
+        bool is_a;
+        int li, a, it, e, r0, m;
+    };
+    // Token of a row (-1: no such row).  A token that comes from global memory is only usable after every load
+    // issued before it, the weights included; that wait stays inside the branch that needs it.
+    auto token_of_row = [&](int r0, int m, int row) {
+        int tok = -1;
+        if (row < m) {
+            if (lds_tokens) tok = tiled::lds_read_i32(tab_sorted + 4 * (r0 + row));
+            else tok = global_read_i32(sorted_token, 4u * (uint32_t)(r0 + row));
+        }
+        return tok >= T ? -1 : tok;
+    };
+    auto item_at = [&](int step) {
+        Item t;
+        t.is_a = step < n_a;
+        t.li = t.is_a ? a_begin + step : b_begin + (step - n_a);
+        const int tiles = t.is_a ? TILES_A : TILES_B;
+        t.a = t.li / tiles;
+        t.it = t.li - t.a * tiles;
+        t.e = __builtin_amdgcn_readfirstlane(tiled::lds_read_i32(tab_e + 4 * t.a));
+        const bool ok = t.e >= 0 && t.e < E;
+        t.r0 = ok ? __builtin_amdgcn_readfirstlane(tiled::lds_read_i32(tab_off + 4 * t.e)) : 0;
+        t.m = ok ? max(__builtin_amdgcn_readfirstlane(tiled::lds_read_i32(tab_off + 4 * t.e + 4)) - t.r0, 0) : 0;
+        return t;
+    };
+    // All weight bytes of an item into this wavefront's private LDS region (every slab in flight at once).
+    auto issue_loads = [&](const Item& t) {
+        if (t.m <= 0) return;
+        const int ln = opaque(lane);
+        if (t.is_a) {
+            char* region = s_mem + wave * SA::BYTES;
+            const size_t ebase = (size_t)t.e * I;
 #pragma unroll
-                    for (int j = 0; j < SA::SLABS; ++j) {
-                        const int P = 64 * j + ln;
-                        const int r = P / SA::C, cp = P % SA::C;
-                        const int c = cp ^ (r >> (4 - SA::V));
-                        // MFMA row r = 4*qq + j2: j2 in {0,1} -> gate rows, {2,3} -> up rows of intermediate index 2*qq + (j2 & 1)
-                        const uint16_t* mat = (r & 2) ? wu : wg;
-                        const int irow = it * 8 + 2 * (r >> 2) + (r & 1);
-                        slab_load(mat + (ebase + irow) * H + wave * KSLICE_A + c * 8, region + j * 1024);
+            for (int j = 0; j < SA::SLABS; ++j) {
+                const int P = 64 * j + ln;
+                const int r = P / SA::C, cp = P % SA::C;
+                const int c = cp ^ (r >> (4 - SA::V));
+                // MFMA row r = 4*qq + j2: j2 in {0,1} -> gate rows, {2,3} -> up rows of intermediate index 2*qq + (j2 & 1)
+                const uint16_t* mat = (r & 2) ? wu : wg;
+                const int irow = t.it * 8 + 2 * (r >> 2) + (r & 1);
+                slab_load(mat + (ebase + irow) * H + wave * KSLICE_A + c * 8, region + j * 1024);
+            }
+        } else {
+            char* region = s_mem + wave * (RB * SB::BYTES);
+            const size_t ebase = (size_t)t.e * H + (size_t)t.it * 16 * RB;
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int j = 0; j < SB::SLABS; ++j) {
+                    const int P = 64 * j + ln;
+                    const int r = P / SB::C, cp = P % SB::C;
+                    const int c = cp ^ (r >> (4 - SB::V));
+                    slab_load(wd + (ebase + rb * 16 + r) * I + wave * KSLICE_B + c * 8, region + rb * SB::BYTES + j * 1024);
+                }
+        }
+    };
+    const uint32_t red_base = tiled::lds_addr(s_mem + LDS_BYTES - RED_A);     // red_a; red_b ends at the same address
+    const uint32_t redb_base = tiled::lds_addr(s_mem + LDS_BYTES - RED_B);
+
+    Item cur{};
+    if (n_mine > 0) cur = item_at(0);
+    bool ahead = false;                      // the current item's weights were requested during the previous item
+    for (int step = 0; step < n_mine; ++step) {   // this workgroup's gate/up items, then its down items
+        const bool has_next = step + 1 < n_mine;
+        const Item nxt = item_at(has_next ? step + 1 : step);
+        if (!ahead) issue_loads(cur);
+        ahead = false;
+        const bool is_a = cur.is_a;
+        const int li = cur.li, a = cur.a, it = cur.it, r0 = cur.r0, m = cur.m;
+        const int key = (is_a ? 0 : 0x10000) | a;
+        const int ln = opaque(lane);
+        const int n = ln & 15, q = ln >> 4;
+        const int chunks = (m + 16 * NT - 1) / (16 * NT);
+        if (is_a) {
+            // =============================================================== gate/up item
+            char* region = s_mem + wave * SA::BYTES;
+            // Items of one slot are published together after the last of them; that one waits for its h stores.
+            const bool publish_now = step + 1 >= n_a || (li + 1) / TILES_A != a;
+            for (int ch = 0; ch < chunks; ++ch) {
+                const int row_base = ch * 16 * NT;
+                const bool last_chunk = ch + 1 == chunks;
+                if (key != cur_key || chunks > 1) {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) {
+                        const int tok = token_of_row(r0, m, row_base + nt * 16 + n);
+                        const uint16_t* xp = x + (size_t)(tok < 0 ? 0 : tok) * H + wave * KSLICE_A + q * 8;
+                        if (tok >= 0) {
+#pragma unroll
+                            for (int s = 0; s < KSA; ++s) opr[nt][s] = *reinterpret_cast<const bf16x8_t*>(xp + s * 32);
+                        } else {
+#pragma unroll
+                            for (int s = 0; s < KSA; ++s) opr[nt][s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                        }
+                    }
+                    cur_key = chunks > 1 ? -1 : key;
+                }
+                wait_all_loads();
+                const bool two = m - row_base > 16;
+                f32x4_t acc[1][NT] = {{{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}};
+                // one branch per item, not per K-step
+                if (two) mfma_stream<SA, KSA, 1, true, KSM>(region, n, q, opr, acc);
+                else mfma_stream<SA, KSA, 1, false, KSM>(region, n, q, opr, acc);
+                // This wavefront has consumed its region: the next item's weights can start to arrive while the
+                // partial sums are reduced and h is stored.
+                if (last_chunk && has_next && !publish_now) {
+                    issue_loads(nxt);
+                    ahead = true;
+                }
+                lds_write_f4(red_base + ((wave * NT + 0) * WAVE + ln) * 16, acc[0][0]);
+                lds_write_f4(red_base + ((wave * NT + 1) * WAVE + ln) * 16, acc[0][1]);
+                lds_barrier();
+                if (wave < NT && (wave == 0 || two)) {        // wavefront nt finishes token tile nt
+                    f32x4_t v = lds_read_f4(red_base + ((0 * NT + wave) * WAVE + ln) * 16);
+#pragma unroll
+                    for (int w = 1; w < FFN_WAVES; ++w) v += lds_read_f4(red_base + ((w * NT + wave) * WAVE + ln) * 16);
+                    const int row = row_base + wave * 16 + n;
+                    if (row < m) {
+                        // lane holds (g_a, g_b, u_a, u_b) of intermediate indices it*8 + 2*q, +1 for token row `row`
+                        const float h0 = silu_f32(v[0]) * v[2];
+                        const float h1 = silu_f32(v[1]) * v[3];
+                        const uint32_t packed = f32_to_bf16_bits(h0) | (f32_to_bf16_bits(h1) << 16);
+                        store_coherent(reinterpret_cast<uint32_t*>(h + (size_t)(r0 + row) * I + it * 8 + 2 * q), packed);
                     }
                 }
-                const int chunks = (m + 16 * NT - 1) / (16 * NT);
-                for (int ch = 0; ch < chunks; ++ch) {
-                    const int row_base = ch * 16 * NT;
-                    if (key != cur_key || chunks > 1) {
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) {
-                            const int row = row_base + nt * 16 + n;
-                            int tok = row < m ? (own_tables ? s_sorted[r0 + row] : sorted_token[r0 + row]) : -1;
-                            if (tok >= T) tok = -1;
-                            const uint16_t* xp = x + (size_t)(tok < 0 ? 0 : tok) * H + wave * KSLICE_A + q * 8;
-                            if (tok >= 0) {
-#pragma unroll
-                                for (int s = 0; s < KSA; ++s) opr[nt][s] = *reinterpret_cast<const bf16x8_t*>(xp + s * 32);
-                            } else {
-#pragma unroll
-                                for (int s = 0; s < KSA; ++s) opr[nt][s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                            }
-                        }
-                        cur_key = chunks > 1 ? -1 : key;
-                    }
-                    wait_all_loads();
-                    const bool two = m - row_base > 16;
-                    f32x4_t acc[NT] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-                    for (int s = 0; s < KSA; ++s) {
-                        const bf16x8_t wv = *reinterpret_cast<const bf16x8_t*>(region + SA::phys(n, 4 * s + q) * 16);
-                        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, opr[0][s], acc[0], 0, 0, 0);
-                        if (two) acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, opr[1][s], acc[1], 0, 0, 0);
-                    }
-                    red_a[wave][0][ln] = acc[0];
-                    red_a[wave][1][ln] = acc[1];
-                    __syncthreads();
-                    if (wave < NT && (wave == 0 || two)) {        // wavefront nt finishes token tile nt
-                        f32x4_t v = red_a[0][wave][ln];
-#pragma unroll
-                        for (int w = 1; w < FFN_WAVES; ++w) v += red_a[w][wave][ln];
-                        const int row = row_base + wave * 16 + n;
-                        if (row < m) {
-                            // lane holds (g_a, g_b, u_a, u_b) of intermediate indices it*8 + 2*q, +1 for token row `row`
-                            const float h0 = silu_f32(v[0]) * v[2];
-                            const float h1 = silu_f32(v[1]) * v[3];
-                            const uint32_t packed = f32_to_bf16_bits(h0) | (f32_to_bf16_bits(h1) << 16);
-                            store_coherent(reinterpret_cast<uint32_t*>(h + (size_t)(r0 + row) * I + it * 8 + 2 * q), packed);
+                // vmcnt counts stores too.  Before a publication every h store of this workgroup must have been
+                // acknowledged: the stores of earlier items were covered by the wait for the following item's weights,
+                // the stores of this last item are waited for here (nothing else is in flight then).
+                if (publish_now && last_chunk) wait_all_loads();
+                lds_barrier();            // partial-sum buffer is free; with the wait above, h of this workgroup is complete
+            }
+            // publish finished gate/up items, once per run of items of one slot.  The h stores are device-coherent
+            // write-through stores and every wavefront has waited for its own before the barrier.
+            ++pend;
+            if (publish_now) {
+                if (tid == 0) __hip_atomic_fetch_add(&ctrl->done[a][0], pend, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                pend = 0;
+            }
+        } else {
+            // =============================================================== down item
+            char* region = s_mem + wave * (RB * SB::BYTES);
+            if (a != ready_slot) {       // wait until every gate/up item of this expert has published h
+                if (tid == 0) {
+                    int spins = 0;
+                    while (__hip_atomic_load(&ctrl->done[a][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < TILES_A) {
+                        __builtin_amdgcn_s_sleep(8);      // ~0.2 us between polls; the counters sit in different memory channels
+                        if (++spins > spin_limit) {          // cannot happen with a control block zeroed before the launch
+                            ctrl->error = 1;
+                            break;
                         }
                     }
-                    wait_all_loads();     // vmcnt counts stores too: this wavefront's h stores have been acknowledged
-                    __syncthreads();      // h stores of this workgroup are complete; partial-sum buffer is free
                 }
-                // publish finished gate/up items, once per run of items of one slot.  The h stores above are
-                // device-coherent write-through stores and every wavefront has waited for its own before the barrier.
-                ++pend;
-                if (step + 1 >= n_a || (li + 1) / TILES_A != a) {
-                    if (tid == 0) __hip_atomic_fetch_add(&ctrl->done[a][0], pend, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    pend = 0;
-                }
-            } else {
-                // =============================================================== down item
-                char* region = s_mem + wave * (RB * SB::BYTES);
-                if (m > 0) {
-                    const size_t ebase = (size_t)e * H + (size_t)it * 16 * RB;
+                lds_barrier();
+                ready_slot = a;
+            }
+            for (int ch = 0; ch < chunks; ++ch) {
+                const int row_base = ch * 16 * NT;
+                const bool last_chunk = ch + 1 == chunks;
+                if (key != cur_key || chunks > 1) {
 #pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                        for (int j = 0; j < SB::SLABS; ++j) {
-                            const int P = 64 * j + ln;
-                            const int r = P / SB::C, cp = P % SB::C;
-                            const int c = cp ^ (r >> (4 - SB::V));
-                            slab_load(wd + (ebase + rb * 16 + r) * I + wave * KSLICE_B + c * 8, region + rb * SB::BYTES + j * 1024);
-                        }
-                }
-                if (a != ready_slot) {       // wait until every gate/up item of this expert has published h
-                    if (tid == 0) {
-                        int spins = 0;
-                        while (__hip_atomic_load(&ctrl->done[a][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < TILES_A) {
-                            __builtin_amdgcn_s_sleep(8);      // ~0.2 us between polls; the counters sit in different memory channels
-                            if (++spins > spin_limit) {          // cannot happen with a control block zeroed before the launch
-                                ctrl->error = 1;
-                                break;
-                            }
-                        }
-                    }
-                    __syncthreads();
-                    ready_slot = a;
-                }
-                const int chunks = (m + 16 * NT - 1) / (16 * NT);
-                for (int ch = 0; ch < chunks; ++ch) {
-                    const int row_base = ch * 16 * NT;
-                    if (key != cur_key || chunks > 1) {
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) {
-                            const int row = row_base + nt * 16 + n;
-                            const bool valid = row < m && (own_tables || sorted_token[r0 + row] >= 0);
-                            const uint16_t* hp = h + (size_t)(valid ? r0 + row : 0) * I + wave * KSLICE_B + q * 8;
-                            if (valid) {
-#pragma unroll
-                                for (int s = 0; s < KSB; ++s) opr[nt][s] = load_coherent_16(hp + s * 32);
-                            } else {
-#pragma unroll
-                                for (int s = 0; s < KSB; ++s) opr[nt][s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
-                            }
-                        }
-                        cur_key = chunks > 1 ? -1 : key;
-                    }
-                    wait_all_loads();
-                    const bool two = m - row_base > 16;
-                    f32x4_t acc[RB][NT];
-#pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) acc[rb][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int s = 0; s < KSB; ++s) {
-#pragma unroll
-                        for (int rb = 0; rb < RB; ++rb) {
-                            const bf16x8_t wv = *reinterpret_cast<const bf16x8_t*>(region + rb * SB::BYTES + SB::phys(n, 4 * s + q) * 16);
-                            acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, opr[0][s], acc[rb][0], 0, 0, 0);
-                            if (two) acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wv, opr[1][s], acc[rb][1], 0, 0, 0);
-                        }
-                    }
-#pragma unroll
-                    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) red_b[wave][rb][nt][ln] = acc[rb][nt];
-                    __syncthreads();
-                    // (rb, nt) pairs are finished by wavefronts round-robin, partial sums added in wavefront order
-                    for (int pair = wave; pair < RB * NT; pair += FFN_WAVES) {
-                        const int rb = pair / NT, nt = pair % NT;
+                    for (int nt = 0; nt < NT; ++nt) {
                         const int row = row_base + nt * 16 + n;
-                        if (row < m) {
-                            f32x4_t v = red_b[0][rb][nt][ln];
+                        const bool valid = token_of_row(r0, m, row) >= 0;
+                        const uint16_t* hp = h + (size_t)(valid ? r0 + row : 0) * I + wave * KSLICE_B + q * 8;
+                        if (valid) {
 #pragma unroll
-                            for (int w = 1; w < FFN_WAVES; ++w) v += red_b[w][rb][nt][ln];
-                            // lane holds output rows it*16*RB + rb*16 + 4*q + (0..3) of token row `row`
-                            *reinterpret_cast<f32x4_t*>(out + (size_t)(r0 + row) * H + it * 16 * RB + rb * 16 + 4 * q) = v;
+                            for (int s = 0; s < KSB; ++s) opr[nt][s] = load_coherent_16(hp + s * 32);
+                        } else {
+#pragma unroll
+                            for (int s = 0; s < KSB; ++s) opr[nt][s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
                         }
                     }
-                    __syncthreads();
+                    cur_key = chunks > 1 ? -1 : key;
                 }
+                wait_all_loads();
+                const bool two = m - row_base > 16;
+                f32x4_t acc[RB][NT];
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) acc[rb][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                if (two) mfma_stream<SB, KSB, RB, true, KSM>(region, n, q, opr, acc);
+                else mfma_stream<SB, KSB, RB, false, KSM>(region, n, q, opr, acc);
+                if (last_chunk && has_next) {                 // next down item's weights arrive during the reduction
+                    issue_loads(nxt);
+                    ahead = true;
+                }
+#pragma unroll
+                for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) lds_write_f4(redb_base + (((wave * RB + rb) * NT + nt) * WAVE + ln) * 16, acc[rb][nt]);
+                lds_barrier();
+                // (rb, nt) pairs are finished by wavefronts round-robin, partial sums added in wavefront order
+                for (int pair = wave; pair < RB * NT; pair += FFN_WAVES) {
+                    const int rb = pair / NT, nt = pair % NT;
+                    const int row = row_base + nt * 16 + n;
+                    if (row < m) {
+                        f32x4_t v = lds_read_f4(redb_base + (((0 * RB + rb) * NT + nt) * WAVE + ln) * 16);
+#pragma unroll
+                        for (int w = 1; w < FFN_WAVES; ++w) v += lds_read_f4(redb_base + (((w * RB + rb) * NT + nt) * WAVE + ln) * 16);
+                        // lane holds output rows it*16*RB + rb*16 + 4*q + (0..3) of token row `row`
+                        *reinterpret_cast<f32x4_t*>(out + (size_t)(r0 + row) * H + it * 16 * RB + rb * 16 + 4 * q) = v;
+                    }
+                }
+                lds_barrier();
             }
         }
+        cur = nxt;
     }
 }
 
@@ -400,7 +486,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
 // says fits: (workgroups per compute unit for this instantiation) x (compute units), never more.
 template <int KSA, int KSB>
 hipError_t launch_ffn_fused(const FfnArgs& p) {
-    constexpr int RB = KSB <= 7 ? 2 : 1;
+    constexpr int RB = KSB <= 6 ? 2 : 1;      // two sub-tiles per down item while the partial sums fit the register budget
     static int resident = 0;         // per instantiation; same value for every caller, so a benign race
     if (resident == 0) {
         int per_cu = 0;
