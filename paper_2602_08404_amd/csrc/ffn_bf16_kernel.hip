@@ -89,46 +89,102 @@ __device__ __forceinline__ f32x4_t lds_read_f4(uint32_t a) {
     asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
     return v;
 }
+// A matrix instruction's result may only be read by a memory instruction a number of cycles after it was issued.  The compiler
+// inserts that distance for instructions it knows, not for the explicit LDS writes above, so the accumulators pass through this
+// first: it is ordered after the matrix instructions that produce them (operands) and idles for longer than any of them needs.
+template <int N>
+__device__ __forceinline__ void settle_accumulators(f32x4_t (&acc)[N]) {
+    if constexpr (N == 2) asm volatile("s_nop 15\n\ts_nop 7" : "+v"(acc[0]), "+v"(acc[1]));
+    else asm volatile("s_nop 15\n\ts_nop 7" : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3]));
+}
 // Every LDS operation of this wavefront has completed, then all wavefronts of the workgroup meet.  Vector-memory
 // operations in flight are NOT waited for.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-constexpr int ctz_cap4(int c) { return (c % 16 == 0) ? 4 : (c % 8 == 0) ? 3 : (c % 4 == 0) ? 2 : (c % 2 == 0) ? 1 : 0; }
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
 
+// LDS layout of a wavefront's slice of a 16-row weight sub-tile (KS K-steps of 32 columns = C chunks of 16 bytes per row).
+// The slice is cut into stages of two K-steps: a stage is 16 rows x 8 chunks = 2 KB = two direct-to-LDS slabs (rows 0-7 and
+// 8-15), lane l of a slab fetching row l/8, so every row contributes a 128-byte segment.  Inside a row of a stage chunk c sits
+// at slot c ^ ((row >> 1) & 7), which spreads the 16 rows of one MFMA operand read over the LDS banks.  A stage can be consumed
+// as soon as its two slabs have arrived and refilled as soon as it has been read.
 template <int KS>
-struct Slice {
-    static constexpr int C = 4 * KS;                  // 16-byte chunks per row of the wavefront's slice
-    static constexpr int V = ctz_cap4(C);
-    static constexpr int SLABS = KS;                  // 1 KB slabs per 16-row sub-tile
-    static constexpr int BYTES = 16 * C * 16;         // bytes of one 16-row sub-tile slice
-    __device__ static __forceinline__ int phys(int r, int c) { return r * C + (c ^ (r >> (4 - V))); }
+struct Staged {
+    static constexpr int C = 4 * KS;                  // chunks per row of the slice
+    static constexpr int S = (KS + 1) / 2;            // stages per sub-tile
+    static constexpr int BYTES = S * 2048;            // LDS bytes of one sub-tile slice
+    __device__ static __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+    // lane ln of slab `half` of stage st: the row it fetches and the chunk of that row (may be >= C in the last stage of an
+    // odd KS: such lanes fetch nothing)
+    __device__ static __forceinline__ int slab_row(int half, int ln) { return 8 * half + (ln >> 3); }
+    __device__ static __forceinline__ int slab_chunk(int st, int half, int ln) { return 8 * st + ((ln & 7) ^ swz(slab_row(half, ln))); }
+    // byte offset inside the sub-tile slice of the operand of K-step 2*st + u for MFMA lane (n, q)
+    __device__ static __forceinline__ int read_off(int n, int st, int u, int q) {
+        return st * 2048 + (n >> 3) * 1024 + (((n & 7) * 8) + ((4 * u + q) ^ swz(n))) * 16;
+    }
 };
 
-
-// Products of one item for one wavefront: for every K-step s and weight sub-tile rb, one 16-byte LDS read of the weight
-// operand and one matrix instruction per token tile.  The reads run READ_AHEAD steps ahead of the matrix instructions
-// that consume them (a scheduling barrier per step pins that order), so LDS latency is paid once per item, not per step.
-constexpr int READ_AHEAD = 2;
-template <class SL, int KS, int RBN, bool TWO, int KSM_>
-__device__ __forceinline__ void mfma_stream(const char* region, int n, int q, const bf16x8_t (&opr)[NT][KSM_], f32x4_t (&acc)[RBN][NT]) {
-    constexpr int N = KS * RBN;
-    bf16x8_t w[READ_AHEAD + 1];
-    auto read = [&](int j) {
-        const int s = j / RBN, rb = j % RBN;
-        return *reinterpret_cast<const bf16x8_t*>(region + rb * SL::BYTES + SL::phys(n, 4 * s + q) * 16);
-    };
-#pragma unroll
-    for (int j = 0; j < READ_AHEAD && j < N; ++j) w[j] = read(j);
-#pragma unroll
-    for (int j = 0; j < N; ++j) {
-        __builtin_amdgcn_sched_barrier(0);
-        if (j + READ_AHEAD < N) w[(j + READ_AHEAD) % (READ_AHEAD + 1)] = read(j + READ_AHEAD);
-        const int s = j / RBN, rb = j % RBN;
-        acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[j % (READ_AHEAD + 1)], opr[0][s], acc[rb][0], 0, 0, 0);
-        if (TWO) acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[j % (READ_AHEAD + 1)], opr[1][s], acc[rb][1], 0, 0, 0);
+// Waits until at most n (even, 0..46) vector-memory operations of this wavefront are outstanding; n is a constant after
+// unrolling, so the switch folds to one instruction.  Anything else waits for all of them.
+__device__ __forceinline__ void wait_outstanding(int n) {
+#define TEAM_WAIT_CASE(N) \
+    case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
+    switch (n) {
+        TEAM_WAIT_CASE(2) TEAM_WAIT_CASE(4) TEAM_WAIT_CASE(6) TEAM_WAIT_CASE(8) TEAM_WAIT_CASE(10) TEAM_WAIT_CASE(12)
+        TEAM_WAIT_CASE(14) TEAM_WAIT_CASE(16) TEAM_WAIT_CASE(18) TEAM_WAIT_CASE(20) TEAM_WAIT_CASE(22) TEAM_WAIT_CASE(24)
+        TEAM_WAIT_CASE(26) TEAM_WAIT_CASE(28) TEAM_WAIT_CASE(30) TEAM_WAIT_CASE(32) TEAM_WAIT_CASE(34) TEAM_WAIT_CASE(36)
+        TEAM_WAIT_CASE(38) TEAM_WAIT_CASE(40) TEAM_WAIT_CASE(42) TEAM_WAIT_CASE(44) TEAM_WAIT_CASE(46)
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
     }
-    __builtin_amdgcn_sched_barrier(0);
+#undef TEAM_WAIT_CASE
+}
+// Two / one 16-byte LDS reads, complete on return (explicit instructions: see the item loop).
+__device__ __forceinline__ void lds_read2(uint32_t a0, uint32_t a1, bf16x8_t& w0, bf16x8_t& w1) {
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)" : "=&v"(w0), "=&v"(w1) : "v"(a0), "v"(a1) : "memory");
+}
+__device__ __forceinline__ void lds_read1(uint32_t a0, bf16x8_t& w0) {
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(w0) : "v"(a0) : "memory");
+}
+
+// A use of every operand register, placed in the branch that has just loaded them: the compiler's wait for those loads then
+// sits in that branch, and not in front of the first matrix instruction of every item, where it would also wait for all the
+// weights in flight.
+template <int KS, int KSM_>
+__device__ __forceinline__ void settle(bf16x8_t (&opr)[NT][KSM_]) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) asm volatile("" : "+v"(opr[nt][s]));
+}
+
+// Products of one item (one pass over up to 32 token rows) for one wavefront, stage by stage.
+// The item's weights may still be arriving: before stage g the wavefront waits until at most the loads issued after that
+// stage are outstanding.  Loads complete in issue order, so that is a count: the later stages of this item, plus, when
+// PREFETCH, the stages of the next item already requested (two slabs per stage, g of them by then).  Other loads or stores
+// issued after the stage only make the wait stricter than needed.
+//   PREFETCH : right after stage g has been read, next_stage(g) requests stage g of the next item into the same LDS bytes
+//              (it must issue exactly two slab loads).
+template <class ST, int KS, int RBN, bool PREFETCH, bool TWO, int KSM_, class NextStage>
+__device__ __forceinline__ void stream_item(uint32_t region, int n, int q, const bf16x8_t (&opr)[NT][KSM_], f32x4_t (&acc)[RBN][NT],
+                                            NextStage&& next_stage) {
+    constexpr int NST = RBN * ST::S;
+#pragma unroll
+    for (int g = 0; g < NST; ++g) {
+        const int rb = g / ST::S, st = g % ST::S;
+        wait_outstanding(PREFETCH ? 2 * (NST - 1) : 2 * (NST - 1 - g));
+        const bool second = 2 * st + 1 < KS;
+        bf16x8_t w0, w1;
+        const uint32_t base = region + rb * ST::BYTES;
+        if (second) lds_read2(base + ST::read_off(n, st, 0, q), base + ST::read_off(n, st, 1, q), w0, w1);
+        else lds_read1(base + ST::read_off(n, st, 0, q), w0);
+        if (PREFETCH) next_stage(g);
+        acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, opr[0][2 * st], acc[rb][0], 0, 0, 0);
+        if (TWO) acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, opr[1][2 * st], acc[rb][1], 0, 0, 0);
+        if (second) {
+            acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, opr[0][2 * st + 1], acc[rb][0], 0, 0, 0);
+            if (TWO) acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, opr[1][2 * st + 1], acc[rb][1], 0, 0, 0);
+        }
+    }
 }
 
 }  // namespace
@@ -144,8 +200,8 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                                                                    float* __restrict__ out, FfnCtrl* __restrict__ ctrl, int T, int k, int E,
                                                                    int spin_limit, int tiled_min_avg_rows,
                                                                    const int32_t* __restrict__ topk_idx, int32_t* __restrict__ inv_pos_out) {
-    using SA = Slice<KSA>;
-    using SB = Slice<KSB>;
+    using SA = Staged<KSA>;
+    using SB = Staged<KSB>;
     constexpr int H = KSA * 128, I = KSB * 128;
     constexpr int KSLICE_A = KSA * 32, KSLICE_B = KSB * 32;       // columns per wavefront
     constexpr int KSM = cmax(KSA, KSB);
@@ -296,35 +352,40 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         t.m = ok ? max(__builtin_amdgcn_readfirstlane(tiled::lds_read_i32(tab_off + 4 * t.e + 4)) - t.r0, 0) : 0;
         return t;
     };
-    // All weight bytes of an item into this wavefront's private LDS region (every slab in flight at once).
+    // Stage g of an item's weights into this wavefront's private LDS region: exactly two slab loads.
+    auto issue_stage_a = [&](const Item& t, int g) {
+        const int ln = opaque(lane);
+        char* dst = s_mem + wave * SA::BYTES + g * 2048;
+        const size_t ebase = (size_t)t.e * I;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int r = SA::slab_row(half, ln), c = SA::slab_chunk(g, half, ln);
+            // MFMA row r = 4*qq + j2: j2 in {0,1} -> gate rows, {2,3} -> up rows of intermediate index 2*qq + (j2 & 1)
+            const uint16_t* mat = (r & 2) ? wu : wg;
+            const int irow = t.it * 8 + 2 * (r >> 2) + (r & 1);
+            if (SA::C % 8 == 0 || c < SA::C) slab_load(mat + (ebase + irow) * H + wave * KSLICE_A + c * 8, dst + half * 1024);
+        }
+    };
+    auto issue_stage_b = [&](const Item& t, int g) {
+        const int ln = opaque(lane);
+        const int rb = g / SB::S, st = g % SB::S;
+        char* dst = s_mem + wave * (RB * SB::BYTES) + g * 2048;
+        const size_t ebase = (size_t)t.e * H + (size_t)t.it * 16 * RB + rb * 16;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int r = SB::slab_row(half, ln), c = SB::slab_chunk(st, half, ln);
+            if (SB::C % 8 == 0 || c < SB::C) slab_load(wd + (ebase + r) * I + wave * KSLICE_B + c * 8, dst + half * 1024);
+        }
+    };
+    // All stages of an item at once (nothing of it has been requested yet).
     auto issue_loads = [&](const Item& t) {
         if (t.m <= 0) return;
-        const int ln = opaque(lane);
         if (t.is_a) {
-            char* region = s_mem + wave * SA::BYTES;
-            const size_t ebase = (size_t)t.e * I;
 #pragma unroll
-            for (int j = 0; j < SA::SLABS; ++j) {
-                const int P = 64 * j + ln;
-                const int r = P / SA::C, cp = P % SA::C;
-                const int c = cp ^ (r >> (4 - SA::V));
-                // MFMA row r = 4*qq + j2: j2 in {0,1} -> gate rows, {2,3} -> up rows of intermediate index 2*qq + (j2 & 1)
-                const uint16_t* mat = (r & 2) ? wu : wg;
-                const int irow = t.it * 8 + 2 * (r >> 2) + (r & 1);
-                slab_load(mat + (ebase + irow) * H + wave * KSLICE_A + c * 8, region + j * 1024);
-            }
+            for (int g = 0; g < SA::S; ++g) issue_stage_a(t, g);
         } else {
-            char* region = s_mem + wave * (RB * SB::BYTES);
-            const size_t ebase = (size_t)t.e * H + (size_t)t.it * 16 * RB;
 #pragma unroll
-            for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                for (int j = 0; j < SB::SLABS; ++j) {
-                    const int P = 64 * j + ln;
-                    const int r = P / SB::C, cp = P % SB::C;
-                    const int c = cp ^ (r >> (4 - SB::V));
-                    slab_load(wd + (ebase + rb * 16 + r) * I + wave * KSLICE_B + c * 8, region + rb * SB::BYTES + j * 1024);
-                }
+            for (int g = 0; g < RB * SB::S; ++g) issue_stage_b(t, g);
         }
     };
     const uint32_t red_base = tiled::lds_addr(s_mem + LDS_BYTES - RED_A);     // red_a; red_b ends at the same address
@@ -346,7 +407,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         const int chunks = (m + 16 * NT - 1) / (16 * NT);
         if (is_a) {
             // =============================================================== gate/up item
-            char* region = s_mem + wave * SA::BYTES;
+            const uint32_t region = tiled::lds_addr(s_mem + wave * SA::BYTES);
             // Items of one slot are published together after the last of them; that one waits for its h stores.
             const bool publish_now = step + 1 >= n_a || (li + 1) / TILES_A != a;
             for (int ch = 0; ch < chunks; ++ch) {
@@ -365,20 +426,24 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                             for (int s = 0; s < KSA; ++s) opr[nt][s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
                         }
                     }
+                    settle<KSA>(opr);
                     cur_key = chunks > 1 ? -1 : key;
                 }
-                wait_all_loads();
                 const bool two = m - row_base > 16;
                 f32x4_t acc[1][NT] = {{{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}}};
-                // one branch per item, not per K-step
-                if (two) mfma_stream<SA, KSA, 1, true, KSM>(region, n, q, opr, acc);
-                else mfma_stream<SA, KSA, 1, false, KSM>(region, n, q, opr, acc);
-                // This wavefront has consumed its region: the next item's weights can start to arrive while the
-                // partial sums are reduced and h is stored.
-                if (last_chunk && has_next && !publish_now) {
-                    issue_loads(nxt);
+                // Stage by stage: wait for the stage, read it, and (in the item's last pass, unless a publication follows)
+                // request the same stage of the next item, so this wavefront's loads never stop.  One branch per item.
+                const bool prefetch = last_chunk && has_next && !publish_now && nxt.m > 0;
+                auto next_stage = [&](int g) { issue_stage_a(nxt, g); };
+                if (prefetch) {
+                    if (two) stream_item<SA, KSA, 1, true, true, KSM>(region, n, q, opr, acc, next_stage);
+                    else stream_item<SA, KSA, 1, true, false, KSM>(region, n, q, opr, acc, next_stage);
                     ahead = true;
+                } else {
+                    if (two) stream_item<SA, KSA, 1, false, true, KSM>(region, n, q, opr, acc, next_stage);
+                    else stream_item<SA, KSA, 1, false, false, KSM>(region, n, q, opr, acc, next_stage);
                 }
+                settle_accumulators(acc[0]);
                 lds_write_f4(red_base + ((wave * NT + 0) * WAVE + ln) * 16, acc[0][0]);
                 lds_write_f4(red_base + ((wave * NT + 1) * WAVE + ln) * 16, acc[0][1]);
                 lds_barrier();
@@ -410,7 +475,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
             }
         } else {
             // =============================================================== down item
-            char* region = s_mem + wave * (RB * SB::BYTES);
+            const uint32_t region = tiled::lds_addr(s_mem + wave * (RB * SB::BYTES));
             if (a != ready_slot) {       // wait until every gate/up item of this expert has published h
                 if (tid == 0) {
                     int spins = 0;
@@ -442,21 +507,26 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                             for (int s = 0; s < KSB; ++s) opr[nt][s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
                         }
                     }
+                    settle<KSB>(opr);
                     cur_key = chunks > 1 ? -1 : key;
                 }
-                wait_all_loads();
                 const bool two = m - row_base > 16;
                 f32x4_t acc[RB][NT];
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt) acc[rb][nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                if (two) mfma_stream<SB, KSB, RB, true, KSM>(region, n, q, opr, acc);
-                else mfma_stream<SB, KSB, RB, false, KSM>(region, n, q, opr, acc);
-                if (last_chunk && has_next) {                 // next down item's weights arrive during the reduction
-                    issue_loads(nxt);
+                const bool prefetch = last_chunk && has_next && nxt.m > 0;     // the next item is a down item too
+                auto next_stage = [&](int g) { issue_stage_b(nxt, g); };
+                if (prefetch) {
+                    if (two) stream_item<SB, KSB, RB, true, true, KSM>(region, n, q, opr, acc, next_stage);
+                    else stream_item<SB, KSB, RB, true, false, KSM>(region, n, q, opr, acc, next_stage);
                     ahead = true;
+                } else {
+                    if (two) stream_item<SB, KSB, RB, false, true, KSM>(region, n, q, opr, acc, next_stage);
+                    else stream_item<SB, KSB, RB, false, false, KSM>(region, n, q, opr, acc, next_stage);
                 }
+                settle_accumulators(reinterpret_cast<f32x4_t(&)[RB * NT]>(acc));
 #pragma unroll
                 for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
