@@ -45,9 +45,11 @@ constexpr int NT = 2;                    // token tiles of 16 rows handled per p
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-// 64 lanes x 16 bytes, each lane from its own global address, land contiguously at lds_base + lane*16.
+// 64 lanes x 16 bytes, each lane from its own global address, land contiguously at lds_base + lane*16.  The loads carry the
+// non-temporal hint: weights are read exactly once per call, and without the hint the stream pushes the small reused data
+// (token rows, h, the output rows being written) out of L2 over and over, which costs far more than those bytes suggest.
 __device__ __forceinline__ void slab_load(const void* gsrc, char* lds_base_uniform) {
-    __builtin_amdgcn_global_load_lds((gptr_t)gsrc, (lptr_t)lds_base_uniform, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr_t)gsrc, (lptr_t)lds_base_uniform, 16, 0, /*nt*/ 2);
 }
 // Waits until every outstanding vector-memory operation of this wavefront (loads, direct-to-LDS loads and
 // stores: one counter on this architecture) has completed.

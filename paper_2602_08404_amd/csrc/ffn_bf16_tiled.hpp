@@ -48,6 +48,7 @@ __device__ __forceinline__ void slab_load(const void* gsrc, char* lds_base_unifo
     __builtin_amdgcn_global_load_lds((gptr_t)gsrc, (lptr_t)lds_base_uniform, 16, 0, AUX);
 }
 constexpr int AUX_NONE = 0;
+constexpr int AUX_STREAM = 2;          // nt: read once, do not displace the small reused data (tokens, h, out) from L2
 constexpr int AUX_DEVICE_SCOPE = 16;   // sc1: the load does not use possibly stale lines of this XCD's L2
 
 template <int N>
@@ -216,7 +217,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
         auto produce_stage = [&]() {      // issue the three loads of the producer's current stage, then advance it
             char* slot = s_ring + (p_issued % D) * STAGE_BYTES;
             const int koff = p_ks * KC;
-            slab_load<AUX_NONE>(src_w + koff, slot + wave * 8 * ROW_BYTES);
+            slab_load<AUX_STREAM>(src_w + koff, slot + wave * 8 * ROW_BYTES);
             if (phase == 0) {
                 slab_load<AUX_NONE>(src_x0 + koff, slot + W_BYTES + (16 * wave) * ROW_BYTES);
                 slab_load<AUX_NONE>(src_x1 + koff, slot + W_BYTES + (16 * wave + 8) * ROW_BYTES);
