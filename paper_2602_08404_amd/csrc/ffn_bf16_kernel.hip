@@ -41,6 +41,7 @@ namespace team {
 namespace {
 
 constexpr int NT = 2;                    // token tiles of 16 rows handled per pass (32 tokens)
+constexpr int H_BUF_ITEMS = 7;           // gate/up items whose h is held back in LDS (what is left of the workgroup's 80 KB)
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -84,6 +85,17 @@ __device__ __forceinline__ int global_read_i32(const int32_t* base_uniform, uint
     asm volatile("global_load_dword %0, %1, %2\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(byte_off), "s"(base_uniform) : "memory");
     return v;
 }
+__device__ __forceinline__ int lds_read_u16(uint32_t a) {
+    int v;
+    asm volatile("ds_read_u16 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
+    return v;
+}
+__device__ __forceinline__ uint32_t lds_read_u32(uint32_t a) {
+    uint32_t v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
+    return v;
+}
+__device__ __forceinline__ void lds_write_u32(uint32_t a, uint32_t v) { asm volatile("ds_write_b32 %0, %1" ::"v"(a), "v"(v) : "memory"); }
 // LDS accesses and the workgroup barrier as explicit instructions (see the item loop for why).
 __device__ __forceinline__ void lds_write_f4(uint32_t a, const f32x4_t& v) { asm volatile("ds_write_b128 %0, %1" ::"v"(a), "v"(v) : "memory"); }
 __device__ __forceinline__ f32x4_t lds_read_f4(uint32_t a) {
@@ -214,7 +226,8 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     __shared__ __attribute__((aligned(1024))) char s_mem[LDS_BYTES];
     __shared__ int32_t s_slot_e[FFN_MAX_E];
     __shared__ int32_t s_off[FFN_MAX_E + 1];
-    __shared__ int32_t s_sorted[FFN_LAYER_MAX_ROWS];     // token of every row, when the kernel groups the routing table itself
+    __shared__ uint16_t s_sorted[FFN_LAYER_MAX_ROWS];    // token of every row (0xffff: none), when the table fits
+    __shared__ uint32_t s_hbuf[H_BUF_ITEMS][NT][WAVE];   // h of the gate/up items of the current slot run, until it is published
     __shared__ int32_t s_nact;
 
     const int tid = threadIdx.x;
@@ -233,7 +246,10 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         for (int i = tid; i < E; i += FFN_THREADS) s_slot_e[i] = active[i];
         for (int i = tid; i <= E; i += FFN_THREADS) s_off[i] = min(max(offsets[i], 0), A);
         if (lds_tokens)
-            for (int i = tid; i < A; i += FFN_THREADS) s_sorted[i] = sorted_token[i];
+            for (int i = tid; i < A; i += FFN_THREADS) {
+                const int t = sorted_token[i];
+                s_sorted[i] = (t >= 0 && t < T) ? (uint16_t)t : (uint16_t)0xffffu;
+            }
     } else {
         // ---- small calls (T <= 64, at most FFN_LAYER_MAX_ROWS pairs): every workgroup groups the routing table itself,
         // in LDS, instead of waiting for a separate grouping kernel.  Same method and same result as that kernel: a token
@@ -294,7 +310,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                 const uint32_t b0 = bits[2 * e], b1 = bits[2 * e + 1];
                 const int rank = t < 32 ? __popc(b0 & ((1u << t) - 1u)) : __popc(b0) + __popc(b1 & ((1u << (t - 32)) - 1u));
                 pos = s_off[e] + rank;
-                s_sorted[pos] = t;
+                s_sorted[pos] = (uint16_t)t;
             }
             if (blockIdx.x == 0) inv_pos_out[r] = pos;         // the combine kernel that follows needs the rows of every pair
         }
@@ -322,6 +338,8 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     int cur_key = -1;                        // (phase, slot) the operand registers hold; -1: nothing
     int ready_slot = -1;                     // slot whose h this workgroup has already acquired
     int pend = 0;                            // finished gate/up items of the current slot not yet published
+    int held = 0, held_it0 = 0;              // items whose h is still in s_hbuf, and the tile index of the first of them
+    const uint32_t hbuf_base = tiled::lds_addr(s_hbuf);
 
     // While direct-to-LDS loads of the NEXT item are in flight, every LDS read below is written as explicit
     // instructions: the compiler would otherwise wait for all outstanding direct-to-LDS loads before any LDS read it
@@ -336,7 +354,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     auto token_of_row = [&](int r0, int m, int row) {
         int tok = -1;
         if (row < m) {
-            if (lds_tokens) tok = tiled::lds_read_i32(tab_sorted + 4 * (r0 + row));
+            if (lds_tokens) tok = lds_read_u16(tab_sorted + 2 * (r0 + row));
             else tok = global_read_i32(sorted_token, 4u * (uint32_t)(r0 + row));
         }
         return tok >= T ? -1 : tok;
@@ -449,22 +467,36 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                 lds_write_f4(red_base + ((wave * NT + 0) * WAVE + ln) * 16, acc[0][0]);
                 lds_write_f4(red_base + ((wave * NT + 1) * WAVE + ln) * 16, acc[0][1]);
                 lds_barrier();
+                if (chunks == 1 && held == 0) held_it0 = it;
                 if (wave < NT && (wave == 0 || two)) {        // wavefront nt finishes token tile nt
                     f32x4_t v = lds_read_f4(red_base + ((0 * NT + wave) * WAVE + ln) * 16);
 #pragma unroll
                     for (int w = 1; w < FFN_WAVES; ++w) v += lds_read_f4(red_base + ((w * NT + wave) * WAVE + ln) * 16);
                     const int row = row_base + wave * 16 + n;
-                    if (row < m) {
-                        // lane holds (g_a, g_b, u_a, u_b) of intermediate indices it*8 + 2*q, +1 for token row `row`
-                        const float h0 = silu_f32(v[0]) * v[2];
-                        const float h1 = silu_f32(v[1]) * v[3];
-                        const uint32_t packed = f32_to_bf16_bits(h0) | (f32_to_bf16_bits(h1) << 16);
-                        store_coherent(reinterpret_cast<uint32_t*>(h + (size_t)(r0 + row) * I + it * 8 + 2 * q), packed);
+                    // lane holds (g_a, g_b, u_a, u_b) of intermediate indices it*8 + 2*q, +1 for token row `row`
+                    const float h0 = silu_f32(v[0]) * v[2];
+                    const float h1 = silu_f32(v[1]) * v[3];
+                    const uint32_t packed = f32_to_bf16_bits(h0) | (f32_to_bf16_bits(h1) << 16);
+                    uint32_t* hrow = reinterpret_cast<uint32_t*>(h + (size_t)(r0 + (row < m ? row : 0)) * I + 2 * q);
+                    if (chunks > 1) {
+                        if (row < m) store_coherent(hrow + it * 4, packed);
+                    } else {
+                        // A store between the weight loads holds up this wavefront's load pipeline until it is acknowledged
+                        // (loads and stores complete in order), and an item's h is only needed once the whole slot run is
+                        // published: keep it in LDS (every lane re-reads only what it wrote) and store the run in one go.
+                        lds_write_u32(hbuf_base + ((held * NT + wave) * WAVE + ln) * 4, packed);
+                        if (publish_now || held + 1 == H_BUF_ITEMS) {
+                            for (int j = 0; j <= held; ++j) {
+                                const uint32_t pv = lds_read_u32(hbuf_base + ((j * NT + wave) * WAVE + ln) * 4);
+                                if (row < m) store_coherent(hrow + (held_it0 + j) * 4, pv);
+                            }
+                        }
                     }
                 }
+                if (chunks == 1) held = (publish_now || held + 1 == H_BUF_ITEMS) ? 0 : held + 1;
                 // vmcnt counts stores too.  Before a publication every h store of this workgroup must have been
-                // acknowledged: the stores of earlier items were covered by the wait for the following item's weights,
-                // the stores of this last item are waited for here (nothing else is in flight then).
+                // acknowledged; nothing else is in flight then (the next item's weights are not requested before a
+                // publication), so this waits for exactly those stores.
                 if (publish_now && last_chunk) wait_all_loads();
                 lds_barrier();            // partial-sum buffer is free; with the wait above, h of this workgroup is complete
             }
