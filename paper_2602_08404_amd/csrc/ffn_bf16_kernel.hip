@@ -19,20 +19,20 @@
 // Gate/up items never wait and every workgroup is resident (the host sizes the grid from the occupancy the
 // runtime reports), so every wait ends.
 //
-// Inside a workgroup the reduction dimension is split over the 4 wavefronts.  Each wavefront pulls its
-// slice of the item's weight rows HBM -> LDS with 16-byte-per-lane direct-to-LDS loads (lanes consecutive
-// along the contiguous dimension), keeps the whole slice in flight at once, then feeds v_mfma_f32_16x16x32
-// bf16 with the weights as the 16-row operand and up to 32 token rows as the 16-column operand.  Partial
-// sums of the 4 wavefronts are added in a fixed order through LDS (deterministic, no float atomics).
+// Inside a workgroup the reduction dimension is split over the 4 wavefronts.  Each wavefront pulls its slice of the
+// item's weight rows HBM -> LDS with 16-byte-per-lane direct-to-LDS loads into a region of its own, as one continuous
+// stream: the slice is cut into stages of two MFMA K-steps, and as soon as a stage has been read the same stage of the
+// NEXT item is requested into the same bytes, so a wavefront's loads never stop - not during the reduction or the
+// epilogue, not at item boundaries (only a publication of h drains them).  The loads carry the non-temporal hint.
+// v_mfma_f32_16x16x32 bf16 takes the weights as the 16-row operand and up to 32 token rows as the 16-column operand
+// (held in registers).  Partial sums of the 4 wavefronts are added in a fixed order through LDS (deterministic, no
+// float atomics).  h of a run of gate/up items is kept in LDS and stored in one go when the run is published, because
+// a store between weight loads holds up the in-order load pipeline until it is acknowledged.
 //
 // Two more things happen in this kernel.  (1) For small calls (at most 64 tokens) started by
 // team_moe_layer_forward, every workgroup groups the routing table itself in LDS during its prologue (the same
 // bitset / popcount / prefix-sum method as the dispatch kernel, which is then not launched).  (2) When a call
 // averages many rows per expert, all workgroups switch to the streaming body in ffn_bf16_tiled.hpp.
-//
-// LDS slice layout: a wavefront's slice of a 16-row sub-tile is 16 rows x C chunks of 16 bytes
-// (C = 4 * K-steps).  Chunk (r, c) sits at position r*C + (c ^ (r >> (4 - V))), V = min(4, ctz(C)), which
-// makes the 16 rows of one MFMA operand read hit 16 different 16-byte bank groups.
 #include "ffn_bf16.hpp"
 #include "ffn_bf16_tiled.hpp"
 
