@@ -137,6 +137,21 @@ def test_cfg2_no_renormalisation(cfg2_case):
     say("renorm0", hz.full_parity(case, c12_mask(case, 32)))
 
 
+@pytest.mark.parametrize("M", [32, 24, 16, 7])
+def test_cfg2_repeated_calls_are_bitwise_stable(cfg2_case, M):
+    """The expert FFN overlaps loads, matrix instructions and hand-overs between workgroups; whatever the timing of a
+    particular launch, the result must be the same bits.  60 calls per set size (24 and 7 give shares that cross expert
+    boundaries inside a workgroup), alternating with a call on another set so that scratch contents change in between."""
+    mask, other = c12_mask(cfg2_case, M), c12_mask(cfg2_case, 40)
+    ws = torch.empty(tm.team_moe_workspace_size(cfg2_case.cfg), dtype=torch.uint8, device=hz.DEV)
+    _, first = hz.gpu_layer(cfg2_case, mask, ws)
+    for i in range(60):
+        if i % 3 == 0:
+            hz.gpu_layer(cfg2_case, other, ws)
+        _, again = hz.gpu_layer(cfg2_case, mask, ws)
+        assert torch.equal(first, again), i
+
+
 # ----------------------------------------------------------------------------- cfg 3: 4 speculative candidates x 32 tokens, one shared set
 def test_cfg3_speculative_candidates(cfg2_case):
     s = gen.CFG3
