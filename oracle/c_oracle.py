@@ -20,6 +20,8 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(_build.build(force=False))
         _lib.oracle_max_threads.restype = C.c_int
+        _lib.oracle_classify_tokens.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_uint8), C.c_int, C.c_int, C.POINTER(C.c_int32),
+                                                C.c_int, C.c_float, C.c_int, C.POINTER(C.c_uint8)]
     return _lib
 
 
@@ -74,6 +76,23 @@ def route_two_round(logits, k: int, first_round, renormalize: int = 1):
     lib().oracle_route_two_round(_p(logits, C.c_float), T, E, k, int(renormalize), _p(fr, C.c_uint8), _p(mask, C.c_uint8),
                                  _p(idx, C.c_int32), _p(gate, C.c_double))
     return mask, idx, gate
+
+
+def classify_tokens(conf, state, block_len: int, tau_h: float, L_h: int, live_index=None):
+    """Step 1 of Algorithm 1 / Eq. 4: uint8 [T], 1 = first-round token (newly accepted or hot), 0 = cold."""
+    conf = _f32(conf)
+    state = np.ascontiguousarray(state, dtype=np.uint8)
+    n = conf.shape[0]
+    assert state.shape == (n,)
+    if live_index is None:
+        T, li = n, None
+    else:
+        li = np.ascontiguousarray(live_index, dtype=np.int32)
+        T = li.shape[0]
+    out = np.empty(T, np.uint8)
+    lib().oracle_classify_tokens(_p(conf, C.c_float), _p(state, C.c_uint8), n, int(block_len),
+                                 None if li is None else _p(li, C.c_int32), T, float(tau_h), int(L_h), _p(out, C.c_uint8))
+    return out
 
 
 def dispatch(topk_idx, E: int):

@@ -25,7 +25,7 @@
  * to fp32, the precision the kernels select in.
  *
  * oracle_route_two_round is Algorithm 1 itself (first-round tokens over all experts, E_A = union of their picks,
- * cold tokens inside E_A).
+ * cold tokens inside E_A); oracle_classify_tokens is its step 1 (hot/cold classification, Eq. 4).
  *
  * Pins (tests/test_oracle_pins.py): hand-worked example (tests/golden), dense-SwiGLU special case,
  * mask-free top-k MoE written separately, brute-force subset enumeration, superset invariance from
@@ -110,6 +110,33 @@ void oracle_route_two_round(const float *logits, int T, int E, int k, int renorm
     for (int t = 0; t < T; ++t) {
         if (first_round[t]) continue;
         route_token(logits + (size_t)t * E, E, k, renormalize, mask_out, topk_idx + (size_t)t * k, topk_gate + (size_t)t * k);
+    }
+}
+
+/* Classification of the live tokens of a step (Algorithm 1, step 1; hot tokens as in Eq. 4 of Section "Speculative Exploration
+ * for Hot Tokens", with the wording of Section "Experimental Setup": a masked token is hot if its confidence exceeds tau_h or
+ * if it is no more than L_h positions away from a decoded token of its block).
+ *   state[p]: 0 masked, 1 decoded in an earlier step, 2 newly accepted in the previous step; conf[p]: confidence of the
+ *   current decoding attempt (used for masked positions only); positions p of one block are the rows
+ *   [b*block_len, (b+1)*block_len) and distances are taken inside a block.
+ *   token_class[t] for the live row p = live_index[t] (or p = t when live_index is NULL):
+ *     1 = takes part in the first routing round (newly accepted, or masked and hot; a row decoded earlier that is listed
+ *         anyway is routed freely as well), 0 = cold. */
+void oracle_classify_tokens(const float *conf, const uint8_t *state, int n_rows, int block_len, const int32_t *live_index, int T,
+                            float tau_h, int L_h, uint8_t *token_class) {
+    for (int t = 0; t < T; ++t) {
+        int p = live_index ? live_index[t] : t;
+        if (p < 0 || p >= n_rows) { token_class[t] = 0; continue; }     /* not a row: nothing to route freely */
+        if (state[p] != 0) { token_class[t] = 1; continue; }
+        int hot = conf[p] > tau_h;
+        int b0 = (p / block_len) * block_len, b1 = b0 + block_len;
+        if (b1 > n_rows) b1 = n_rows;
+        for (int j = b0; j < b1 && !hot; ++j)
+            if (state[j] != 0) {
+                int d = p > j ? p - j : j - p;
+                if (d <= L_h) hot = 1;
+            }
+        token_class[t] = (uint8_t)hot;
     }
 }
 

@@ -226,6 +226,66 @@ def test_two_round_routing_degenerate():
     assert mask3.sum() == 3 and (idx3[1:] >= 0).all() and mask3[idx3].all()
 
 
+# ----------------------------------------------------------------------------- Eq. 4 / Algorithm 1 step 1 (hot and cold tokens)
+def classify_by_sets(conf, state, block_len, tau_h, L_h, live):
+    """The definition written with sets: hot = masked and (confident or within L_h of a decoded position of its block)."""
+    out = []
+    n = len(state)
+    for p in live:
+        if state[p] != 0:
+            out.append(1)
+            continue
+        blk = range((p // block_len) * block_len, min(n, (p // block_len + 1) * block_len))
+        near = {q for j in blk if state[j] != 0 for q in range(j - L_h, j + L_h + 1)}
+        out.append(int(np.float32(conf[p]) > np.float32(tau_h) or p in near))
+    return np.array(out, np.uint8)
+
+
+@pytest.mark.parametrize("tau_h,L_h", [(0.4, 6), (0.5, 5), (0.6, 4), (0.7, 3), (0.8, 2)])      # the settings of the sensitivity study
+def test_token_classes_match_the_set_definition(tau_h, L_h):
+    r = np.random.default_rng(int(tau_h * 10))
+    block_len, n = 32, 96                                   # three branches of one block
+    state = np.zeros(n, np.uint8)
+    for b in range(3):                                      # near-autoregressive acceptance: a decoded prefix, one stray, one new
+        state[b * 32: b * 32 + 5 + b] = 1
+        state[b * 32 + 12 + b] = 1
+        state[b * 32 + 5 + b] = 2
+    conf = r.random(n).astype(np.float32)
+    live = np.nonzero(state != 1)[0].astype(np.int32)       # masked and newly accepted rows
+    got = orc.classify_tokens(conf, state, block_len, tau_h, L_h, live)
+    np.testing.assert_array_equal(got, classify_by_sets(conf, state, block_len, tau_h, L_h, live))
+    assert got[state[live] == 2].all()                      # newly accepted tokens always route freely
+    # all rows at once (live_index omitted) gives the same classes for those rows
+    np.testing.assert_array_equal(orc.classify_tokens(conf, state, block_len, tau_h, L_h)[live], got)
+
+
+def test_token_classes_closed_forms_and_monotonicity():
+    block_len = 16
+    state = np.zeros(32, np.uint8)
+    state[3] = 1
+    state[16 + 15] = 2
+    conf = np.linspace(0.0, 0.99, 32).astype(np.float32)
+    masked = state == 0
+    # no confidence can exceed 1 and distance 0 only matches decoded positions themselves: every masked token is cold
+    assert not orc.classify_tokens(conf, state, block_len, 1.0, 0)[masked].any()
+    # a reach of a whole block makes every masked token of a block with a decoded token hot
+    assert orc.classify_tokens(conf, state, block_len, 1.0, block_len)[masked].all()
+    # distances stop at the block border: row 16 is 13 rows from row 3 but in another block
+    c = orc.classify_tokens(conf, state, block_len, 1.0, 3)
+    assert c[:8].tolist() == [1, 1, 1, 1, 1, 1, 1, 0] and c[16:28].sum() == 0 and c[28:].all()
+    # strict comparison with the threshold, as in Eq. 4
+    assert orc.classify_tokens(np.full(4, 0.7, np.float32), np.zeros(4, np.uint8), 4, 0.7, 3).sum() == 0
+    # the hot set only grows when the threshold drops or the reach grows
+    prev = None
+    for tau_h, L_h in [(0.8, 2), (0.7, 3), (0.6, 4), (0.5, 5), (0.4, 6)]:
+        cur = orc.classify_tokens(conf, state, block_len, tau_h, L_h)
+        if prev is not None:
+            assert (cur >= prev).all()
+        prev = cur
+    # rows that do not exist are never first-round
+    assert orc.classify_tokens(conf, state, block_len, 0.0, 99, np.array([-1, 32, 5], np.int32)).tolist() == [0, 0, 1]
+
+
 # ----------------------------------------------------------------------------- P7 sub-model equivalence
 def test_masked_layer_equals_compacted_model():
     x, wr, wg, wu, wd = tiny(T=7, E=8, seed=8)
