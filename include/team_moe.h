@@ -136,6 +136,23 @@ int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T,
                            const uint8_t* expert_mask, void* y, void* workspace, size_t ws_bytes, void* stream);
 
 /*
+ * Step 1 of Algorithm 1: classification of the live tokens of a denoising step (Eq. 4 of Section "Speculative Exploration for
+ * Hot Tokens", with the reading of Section "Experimental Setup": "no more than L_h positions away").
+ *   conf  [n_rows] float : confidence c_k of the current decoding attempt of every row (read for masked rows only)
+ *   state [n_rows] bytes : 0 = masked, 1 = decoded in an earlier step, 2 = newly accepted in the previous step (D_a)
+ *   rows [b*block_len, (b+1)*block_len) form one block (or one speculative branch of it); distances are taken inside a block
+ *   live_index [T] int32 : the rows that are computed in this step (masked and newly accepted ones), or NULL for rows 0..T-1
+ *   token_class [T] bytes: 1 = first-round token: newly accepted, or masked and hot, i.e. conf > tau_h (strictly) or a row of
+ *                          its block with state != 0 at distance <= L_h; 0 = cold token.  A listed row that was decoded earlier
+ *                          is classed 1 (routed freely); a listed index outside [0, n_rows) is classed 0.
+ * The output is what team_moe_route_two_round / team_moe_layer_forward_two_round take as token_class.
+ * Needs no cfg and no workspace.  n_rows, block_len, T >= 1, L_h >= 0, tau_h not NaN, else TEAM_ERR_INVALID_ARG.
+ */
+int team_moe_classify_tokens(const float* conf, const uint8_t* state, int32_t n_rows, int32_t block_len,
+                             const int32_t* live_index /* [T] or NULL */, int32_t T, float tau_h, int32_t L_h,
+                             uint8_t* token_class /* [T] */, void* stream);
+
+/*
  * Two-round routing of Algorithm 1 ("Limited Activation for cold tokens") in one call.
  *   token_class [T] bytes: non-zero = first-round token (a newly accepted token of D_a or a hot token of H, which may
  *                          activate experts); zero = cold token of C.

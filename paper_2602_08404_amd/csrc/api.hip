@@ -188,6 +188,17 @@ int team_moe_route_two_round(const team_moe_config* cfg, const void* x, int32_t 
                                                    (hipStream_t)stream));
 }
 
+int team_moe_classify_tokens(const float* conf, const uint8_t* state, int32_t n_rows, int32_t block_len, const int32_t* live_index,
+                             int32_t T, float tau_h, int32_t L_h, uint8_t* token_class, void* stream) {
+    if (!conf || !state || !token_class) return TEAM_ERR_INVALID_ARG;
+    if (n_rows < 1 || block_len < 1 || T < 1 || L_h < 0) return TEAM_ERR_INVALID_ARG;
+    if (!(tau_h == tau_h)) return TEAM_ERR_INVALID_ARG;                 // NaN threshold
+    if (!live_index && T > n_rows) return TEAM_ERR_INVALID_ARG;
+    clear_stale_error();
+    return hip_status(team::launch_classify_tokens(conf, state, n_rows, block_len, live_index, T, tau_h, L_h, token_class,
+                                                   (hipStream_t)stream));
+}
+
 namespace {
 
 // The whole layer; the routing step is either the single-round router confined to expert_mask (token_class == nullptr) or

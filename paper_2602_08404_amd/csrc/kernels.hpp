@@ -28,6 +28,9 @@ hipError_t launch_route(const Dims& d, const void* x, const void* w_router, cons
 hipError_t launch_route_two_round(const Dims& d, const void* x, const void* w_router, const uint8_t* token_class, uint8_t* mask_out,
                                   int32_t* n_activated_out, int32_t* topk_idx, float* topk_gate, float* logits, void* state,
                                   CtrlZero ctrl, hipStream_t s);
+// Hot/cold classification of live tokens (Algorithm 1 step 1, Eq. 4): token_class[t] = 1 first-round, 0 cold.
+hipError_t launch_classify_tokens(const float* conf, const uint8_t* state, int n_rows, int block_len, const int32_t* live_index, int T,
+                                  float tau_h, int L_h, uint8_t* token_class, hipStream_t s);
 // ctrl: control block the dispatch kernel also clears for the expert FFN that follows (words == nullptr: none).
 hipError_t launch_dispatch(const Dims& d, const int32_t* topk_idx, int32_t* offsets, int32_t* sorted_token,
                            int32_t* inv_pos, int32_t* active, int32_t* n_active, CtrlZero ctrl, hipStream_t s);

@@ -26,7 +26,7 @@ from typing import Dict, Optional
 import numpy as np
 
 # tensor tags of the Philox key
-TAG_X_BASE, TAG_X_NOISE, TAG_W_ROUTER, TAG_W_GATE, TAG_W_UP, TAG_W_DOWN, TAG_MASK, TAG_PERM, TAG_CLASS = range(1, 10)
+TAG_X_BASE, TAG_X_NOISE, TAG_W_ROUTER, TAG_W_GATE, TAG_W_UP, TAG_W_DOWN, TAG_MASK, TAG_PERM, TAG_CLASS, TAG_STATE, TAG_CONF = range(1, 12)
 
 WEIGHT_STD = 0.02          # "weights ~ N(0, 0.02)" read as standard deviation 0.02
 RMS_EPS = 1e-6
@@ -217,3 +217,27 @@ def token_classes(T: int, n_first: int, seed: int = 0, layer: int = 0) -> np.nda
     c = np.zeros(T, np.uint8)
     c[perm[:n_first]] = 1
     return c
+
+
+def block_states(n_blocks: int, block_len: int, n_decoded: int, n_new: int, seed: int = 0) -> np.ndarray:
+    """Byte vector [n_blocks*block_len]: per block a decoded prefix of about n_decoded positions (near-autoregressive
+    acceptance: a contiguous prefix plus one or two stray positions further right), n_new of the decoded positions marked
+    newly accepted (2), the rest decoded earlier (1), everything else masked (0)."""
+    out = np.zeros(n_blocks * block_len, np.uint8)
+    for b in range(n_blocks):
+        r = _stream(seed, TAG_STATE, b, n_decoded)
+        pre = max(0, min(block_len, n_decoded - 2 + int(r.integers(0, 3))))
+        dec = set(range(pre))
+        for _ in range(min(2, max(0, n_decoded - pre))):
+            dec.add(int(r.integers(pre, block_len)))
+        dec = sorted(dec)
+        new = set(r.permutation(len(dec))[:min(n_new, len(dec))].tolist())
+        for i, p in enumerate(dec):
+            out[b * block_len + p] = 2 if i in new else 1
+    return out
+
+
+def confidences(n: int, seed: int = 0) -> np.ndarray:
+    """fp32 [n] confidences in (0, 1), skewed towards small values the way re-masked attempts are."""
+    u = _stream(seed, TAG_CONF, 0, n).random(n)
+    return (u ** 2).astype(np.float32)

@@ -158,6 +158,16 @@ def gpu_layer_two_round(case: Case, token_class: np.ndarray, ws=None):
     return y_to_host(y), y, mask.cpu().numpy(), int(n_act.cpu().numpy()[0])
 
 
+def gpu_classify_tokens(conf: np.ndarray, state: np.ndarray, block_len: int, tau_h: float, L_h: int, live_index=None) -> np.ndarray:
+    n = conf.shape[0]
+    T = n if live_index is None else live_index.shape[0]
+    out = torch.full((T,), 9, dtype=torch.uint8, device=DEV)
+    d_live = None if live_index is None else torch.from_numpy(np.ascontiguousarray(live_index, np.int32)).to(DEV)
+    tm.team_moe_classify_tokens(torch.from_numpy(conf).to(DEV), torch.from_numpy(state).to(DEV), n, block_len, d_live, T, tau_h, L_h, out)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
 # ----------------------------------------------------------------------------- oracle side
 def oracle_layer(case: Case, mask, threads=0):
     s = case.shape

@@ -93,6 +93,14 @@ def test_bad_call_arguments_are_rejected_before_any_launch():
                                                 1 << 30, st) == -1
     assert lib.team_moe_layer_forward_two_round(C.byref(cfg), fake, 8, fake, fake, fake, fake, fake, None, None, fake, None,
                                                 0, st) == -3
+    # token classification: required pointers, sizes, threshold
+    f32 = C.c_float
+    assert lib.team_moe_classify_tokens(None, fake, 32, 32, None, 32, f32(0.7), 3, fake, st) == -1
+    assert lib.team_moe_classify_tokens(fake, fake, 32, 32, None, 32, f32(0.7), 3, None, st) == -1
+    assert lib.team_moe_classify_tokens(fake, fake, 32, 0, None, 32, f32(0.7), 3, fake, st) == -1
+    assert lib.team_moe_classify_tokens(fake, fake, 32, 32, None, 33, f32(0.7), 3, fake, st) == -1      # more tokens than rows
+    assert lib.team_moe_classify_tokens(fake, fake, 32, 32, None, 32, f32(0.7), -1, fake, st) == -1
+    assert lib.team_moe_classify_tokens(fake, fake, 32, 32, None, 32, f32(float("nan")), 3, fake, st) == -1
     # NULL cfg / NULL size pointer
     assert lib.team_moe_workspace_size(None, C.byref(C.c_size_t())) == -1
     assert lib.team_moe_workspace_size(C.byref(cfg), None) == -1

@@ -285,3 +285,31 @@ def test_two_round_limits_and_ragged_counts():
         sT = gen.scaled(s, T=T)
         caseT = hz.Case.make(sT, gen.make_x(sT, seed=4), case.w, case.wf, case.d_w)
         say("two-round ragged", T, hz.two_round_parity(caseT, gen.token_classes(T, n_first, seed=T)))
+
+
+# ----------------------------------------------------------------------------- hot / cold token classification (Eq. 4)
+@pytest.mark.parametrize("tau_h,L_h", [(0.4, 6), (0.5, 5), (0.6, 4), (0.7, 3), (0.8, 2), (0.0, 0), (1.0, 40)])
+def test_token_classification_is_bit_exact(tau_h, L_h):
+    for n_blocks, n_dec, n_new, seed in ((1, 6, 2, 0), (4, 9, 3, 1), (32, 14, 1, 2), (3, 0, 0, 3), (2, 32, 4, 4)):
+        state = gen.block_states(n_blocks, 32, n_dec, n_new, seed=seed)
+        conf = gen.confidences(state.size, seed=seed)
+        live = np.nonzero(state != 1)[0].astype(np.int32)          # masked and newly accepted rows are computed
+        if live.size == 0:
+            live = np.array([0], np.int32)
+        assert np.array_equal(hz.gpu_classify_tokens(conf, state, 32, tau_h, L_h, live), orc.classify_tokens(conf, state, 32, tau_h, L_h, live))
+        assert np.array_equal(hz.gpu_classify_tokens(conf, state, 32, tau_h, L_h), orc.classify_tokens(conf, state, 32, tau_h, L_h))
+    # a ragged last block and indices that are not rows
+    state = gen.block_states(3, 32, 7, 2, seed=9)[:77]
+    conf = gen.confidences(77, seed=9)
+    live = np.array([76, -1, 77, 0, 40, 1000000, 33], np.int32)
+    assert np.array_equal(hz.gpu_classify_tokens(conf, state, 32, tau_h, L_h, live), orc.classify_tokens(conf, state, 32, tau_h, L_h, live))
+
+
+def test_classification_feeds_two_round_routing(cfg2_case):
+    """The chain of Algorithm 1 on the device: classes from confidences and decoded positions, then two-round routing."""
+    state = gen.block_states(1, 32, 6, 2, seed=0)
+    conf = gen.confidences(32, seed=0)
+    cls_gpu = hz.gpu_classify_tokens(conf, state, 32, 0.7, 3)
+    assert np.array_equal(cls_gpu, orc.classify_tokens(conf, state, 32, 0.7, 3))
+    rep = hz.two_round_parity(cfg2_case, cls_gpu)
+    say("classified block:", int(cls_gpu.sum()), "first-round tokens ->", rep)
