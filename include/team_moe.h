@@ -182,6 +182,25 @@ int team_moe_layer_forward_two_round(const team_moe_config* cfg, const void* x, 
                                      int32_t* n_activated_out /* [1] or NULL */, void* y, void* workspace,
                                      size_t ws_bytes, void* stream);
 
+/*
+ * The layer over the live rows of larger tensors, without a gather by the caller (Section "Delayed Caching for Decoded
+ * Tokens": at each iteration only the masked tokens and the tokens newly accepted in the previous step are computed; the
+ * other rows of the block keep their cached results).
+ *   x_rows, y_rows [n_rows, H] in cfg->dtype; row_index [T] int32 lists the rows this call computes: token t of the call
+ *   reads x_rows[row_index[t]] and writes y_rows[row_index[t]].  Rows that are not listed are neither read nor written.
+ *   Entries outside [0, n_rows) are clamped into that range on the device; if a row is listed twice, which of the two equal
+ *   results is stored last is not defined.
+ * Routing: with token_class == NULL as in team_moe_layer_forward (expert_mask may be NULL), otherwise as in
+ * team_moe_layer_forward_two_round (expert_mask must then be NULL); token_class, like every per-token table, is indexed by
+ * the position t in row_index.  activated_mask_out / n_activated_out are written in the two-round mode only (optional).
+ * T <= cfg->max_tokens; n_rows is only bounded by the tensors.
+ */
+int team_moe_layer_forward_rows(const team_moe_config* cfg, const void* x_rows, void* y_rows, int32_t n_rows,
+                                const int32_t* row_index /* [T] */, int32_t T, const void* w_router, const void* w_gate,
+                                const void* w_up, const void* w_down, const uint8_t* expert_mask /* [E] or NULL */,
+                                const uint8_t* token_class /* [T] or NULL */, uint8_t* activated_mask_out /* [E] or NULL */,
+                                int32_t* n_activated_out /* [1] or NULL */, void* workspace, size_t ws_bytes, void* stream);
+
 /* Static, NUL-terminated description of a team_status value. */
 const char* team_moe_status_string(int status);
 

@@ -19,7 +19,7 @@ STATUS_OK = 0
 
 EXPORTS = ["team_moe_workspace_size", "team_moe_route", "team_moe_build_dispatch", "team_moe_expert_ffn",
            "team_moe_combine", "team_moe_layer_forward", "team_moe_route_two_round", "team_moe_layer_forward_two_round",
-           "team_moe_classify_tokens", "team_moe_status_string"]
+           "team_moe_classify_tokens", "team_moe_layer_forward_rows", "team_moe_status_string"]
 
 
 class TeamMoeError(RuntimeError):
@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         L.team_moe_route_two_round.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_layer_forward_two_round.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_classify_tokens.argtypes = [vp, vp, i32, i32, vp, i32, C.c_float, i32, vp, vp]
+        L.team_moe_layer_forward_rows.argtypes = [cfgp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_status_string.argtypes = [C.c_int]
         L.team_moe_status_string.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -148,3 +149,12 @@ def team_moe_classify_tokens(conf, state, n_rows: int, block_len: int, live_inde
                              stream=None) -> None:
     _check(lib().team_moe_classify_tokens(_ptr(conf), _ptr(state), n_rows, block_len, _ptr(live_index), T, float(tau_h), L_h,
                                           _ptr(token_class), stream if stream is not None else _stream()), "team_moe_classify_tokens")
+
+
+def team_moe_layer_forward_rows(cfg: Config, x_rows, y_rows, n_rows: int, row_index, T: int, w_router, w_gate, w_up, w_down,
+                                expert_mask, token_class, activated_mask_out, n_activated_out, workspace, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().team_moe_layer_forward_rows(C.byref(cfg), _ptr(x_rows), _ptr(y_rows), n_rows, _ptr(row_index), T, _ptr(w_router),
+                                             _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(expert_mask), _ptr(token_class),
+                                             _ptr(activated_mask_out), _ptr(n_activated_out), _ptr(workspace), ws_bytes,
+                                             stream if stream is not None else _stream()), "team_moe_layer_forward_rows")

@@ -47,7 +47,7 @@ Dims dims_of(const team_moe_config* c, int32_t T) {
 // Workspace layout, sized for max_tokens.  The expert FFN's scratch (control block, h) comes first so that
 // team_moe_expert_ffn and team_moe_layer_forward agree on where it is.
 struct Layout {
-    size_t ctrl, h, logits, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, two_round, total;
+    size_t ctrl, h, logits, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, two_round, x_dense, total;
 };
 Layout layout_of(const team_moe_config* c) {
     const size_t A = (size_t)c->max_tokens * c->top_k;
@@ -66,6 +66,7 @@ Layout layout_of(const team_moe_config* c) {
     L.n_active = off;     off += 256;
     L.expert_out = off;   off += align256(A * c->hidden * 4);
     L.two_round = off;    off += 256;                       // bit set E_A and arrival counter of two-round routing
+    L.x_dense = off;      off += align256((size_t)c->max_tokens * c->hidden * elem);   // live rows gathered by the router (row-index calls)
     L.total = off;
     return L;
 }
@@ -205,7 +206,8 @@ namespace {
 // the two-round router driven by token_class.
 int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const void* w_gate, const void* w_up,
                   const void* w_down, const uint8_t* expert_mask, const uint8_t* token_class, uint8_t* activated_mask_out,
-                  int32_t* n_activated_out, void* y, void* workspace, size_t ws_bytes, void* stream) {
+                  int32_t* n_activated_out, void* y, void* workspace, size_t ws_bytes, void* stream,
+                  const int32_t* row_index = nullptr, int32_t n_rows = 0) {
     int st = check_cfg(cfg);
     if (st != TEAM_OK) return st;
     if ((st = check_T(cfg, T)) != TEAM_OK) return st;
@@ -224,7 +226,14 @@ int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const vo
     int32_t* n_active = (int32_t*)(ws + L.n_active);
     float* expert_out = (float*)(ws + L.expert_out);
     float* logits = (float*)(ws + L.logits);
-    const Dims d = dims_of(cfg, T);
+    const void* x_ffn = x;
+    Dims d = dims_of(cfg, T);
+    d.row_index = row_index;
+    d.n_rows = n_rows;
+    if (row_index) {                     // the router gathers the live rows once; the expert FFN reads the dense copy
+        d.x_dense = ws + L.x_dense;
+        x_ffn = d.x_dense;
+    }
     hipStream_t s = (hipStream_t)stream;
     clear_stale_error();
     // Small calls (the block-decoding regime): route -> expert FFN -> combine.  The FFN kernel groups the routing table itself
@@ -240,7 +249,7 @@ int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const vo
         st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, logits, short_path ? cz : none, s));
     if (st != TEAM_OK) return st;
     if (short_path) {
-        if ((st = hip_status(team::launch_ffn_bf16_from_routing(d, (const uint16_t*)x, topk_idx, inv_pos, (const uint16_t*)w_gate,
+        if ((st = hip_status(team::launch_ffn_bf16_from_routing(d, (const uint16_t*)x_ffn, topk_idx, inv_pos, (const uint16_t*)w_gate,
                                                                 (const uint16_t*)w_up, (const uint16_t*)w_down, ws + L.ctrl,
                                                                 (uint16_t*)(ws + L.h), expert_out, s))) != TEAM_OK)
             return st;
@@ -248,7 +257,7 @@ int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const vo
     }
     if ((st = hip_status(team::launch_dispatch(d, topk_idx, offsets, sorted_token, inv_pos, active, n_active, cz, s))) != TEAM_OK)
         return st;
-    if ((st = run_ffn(cfg, d, x, offsets, sorted_token, active, n_active, w_gate, w_up, w_down, expert_out, ws + L.ctrl,
+    if ((st = run_ffn(cfg, d, x_ffn, offsets, sorted_token, active, n_active, w_gate, w_up, w_down, expert_out, ws + L.ctrl,
                       ws + L.h, s)) != TEAM_OK)
         return st;
     return hip_status(team::launch_combine(d, expert_out, topk_gate, inv_pos, y, s));
@@ -269,6 +278,16 @@ int team_moe_layer_forward_two_round(const team_moe_config* cfg, const void* x, 
     if (!token_class) return TEAM_ERR_INVALID_ARG;
     return layer_forward(cfg, x, T, w_router, w_gate, w_up, w_down, nullptr, token_class, activated_mask_out, n_activated_out, y,
                          workspace, ws_bytes, stream);
+}
+
+int team_moe_layer_forward_rows(const team_moe_config* cfg, const void* x_rows, void* y_rows, int32_t n_rows, const int32_t* row_index,
+                                int32_t T, const void* w_router, const void* w_gate, const void* w_up, const void* w_down,
+                                const uint8_t* expert_mask, const uint8_t* token_class, uint8_t* activated_mask_out,
+                                int32_t* n_activated_out, void* workspace, size_t ws_bytes, void* stream) {
+    if (!row_index || n_rows < 1) return TEAM_ERR_INVALID_ARG;
+    if (expert_mask && token_class) return TEAM_ERR_INVALID_ARG;       // one routing mode per call
+    return layer_forward(cfg, x_rows, T, w_router, w_gate, w_up, w_down, expert_mask, token_class, activated_mask_out, n_activated_out,
+                         y_rows, workspace, ws_bytes, stream, row_index, n_rows);
 }
 
 const char* team_moe_status_string(int status) {

@@ -11,8 +11,10 @@ constexpr int C_MAX_K = 16;      // top_k limit of the library
 
 template <bool BF16>
 __global__ __launch_bounds__(COMBINE_THREADS) void combine_kernel(const float* __restrict__ expert_out, const float* __restrict__ gate,
-                                                                  const int32_t* __restrict__ inv_pos, void* __restrict__ y, int H, int k) {
+                                                                  const int32_t* __restrict__ inv_pos, void* __restrict__ y, int H, int k,
+                                                                  const int32_t* __restrict__ row_index, int n_rows) {
     const int t = blockIdx.y;
+    const size_t yrow = (size_t)token_row(row_index, n_rows, t);
     const int h4 = (blockIdx.x * COMBINE_THREADS + threadIdx.x) * 4;
     if (h4 >= H) return;
     // all slot indices and gates first, then all expert rows, then the sum in slot order: the loads of the
@@ -38,18 +40,18 @@ __global__ __launch_bounds__(COMBINE_THREADS) void combine_kernel(const float* _
         uint2 packed;
         packed.x = f32_to_bf16_bits(acc.x) | (f32_to_bf16_bits(acc.y) << 16);
         packed.y = f32_to_bf16_bits(acc.z) | (f32_to_bf16_bits(acc.w) << 16);
-        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(y) + (size_t)t * H + h4) = packed;
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(y) + yrow * H + h4) = packed;
     } else {
-        *reinterpret_cast<float4*>(reinterpret_cast<float*>(y) + (size_t)t * H + h4) = acc;
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(y) + yrow * H + h4) = acc;
     }
 }
 
 hipError_t launch_combine(const Dims& d, const float* expert_out, const float* gate, const int32_t* inv_pos, void* y, hipStream_t s) {
     dim3 grid((d.H / 4 + COMBINE_THREADS - 1) / COMBINE_THREADS, d.T), block(COMBINE_THREADS);
     if (d.bf16)
-        hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, s, expert_out, gate, inv_pos, y, d.H, d.k);
+        hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, s, expert_out, gate, inv_pos, y, d.H, d.k, d.row_index, d.n_rows);
     else
-        hipLaunchKernelGGL(combine_kernel<false>, grid, block, 0, s, expert_out, gate, inv_pos, y, d.H, d.k);
+        hipLaunchKernelGGL(combine_kernel<false>, grid, block, 0, s, expert_out, gate, inv_pos, y, d.H, d.k, d.row_index, d.n_rows);
     return hipGetLastError();
 }
 

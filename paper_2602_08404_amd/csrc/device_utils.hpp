@@ -95,4 +95,11 @@ __device__ __forceinline__ void load4(const float* p, float* out) {      // 4 fl
 
 __device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + expf(-z)); }
 
+// Row of the caller's x / y tensors that holds token t of the call: t itself, or row_index[t] clamped into [0, n_rows).
+__device__ __forceinline__ int token_row(const int32_t* __restrict__ row_index, int n_rows, int t) {
+    if (!row_index) return t;
+    const int r = row_index[t];
+    return r < 0 ? 0 : (r >= n_rows ? n_rows - 1 : r);
+}
+
 }  // namespace team

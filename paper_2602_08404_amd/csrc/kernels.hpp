@@ -10,6 +10,13 @@ struct Dims {
     int T, H, I, E, k;
     int bf16;          // 1: bf16 storage, 0: float storage
     int renormalize;
+    // Token t of the call lives in row row_index[t] of the caller's x and y tensors, which have n_rows rows
+    // (row_index == nullptr: row t; the call's tensors are dense [T,H]).  The router's logits kernel reads x through the
+    // index and leaves a dense [T,H] copy of the live rows in x_dense for the expert FFN; the combine kernel writes y
+    // through the index.
+    const int32_t* row_index = nullptr;
+    int n_rows = 0;
+    void* x_dense = nullptr;
 };
 
 // Words of the FFN control block that must be zero before an FFN launch: `header` leading words, then one word

@@ -59,7 +59,9 @@ template <> __device__ __forceinline__ void unpack_chunk<float>(const uint4& v, 
 template <typename ST>
 __global__ __launch_bounds__(LOGIT_THREADS) void route_logits_kernel(const ST* __restrict__ x, const ST* __restrict__ w_router,
                                                                      float* __restrict__ logits, int H, int E,
-                                                                     uint32_t* __restrict__ zero_words, int n_zero) {
+                                                                     uint32_t* __restrict__ zero_words, int n_zero,
+                                                                     const int32_t* __restrict__ row_index, int n_rows,
+                                                                     ST* __restrict__ x_dense) {
     constexpr int CN = Chunk<ST>::N;
     // state the selection kernel that follows starts from (two-round routing: bit set and arrival counter)
     if (zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < n_zero) zero_words[threadIdx.x] = 0u;
@@ -68,7 +70,7 @@ __global__ __launch_bounds__(LOGIT_THREADS) void route_logits_kernel(const ST* _
     const int lane = threadIdx.x & (WAVE - 1);
     const int wave = threadIdx.x / WAVE;
     const int n_chunks = H / CN;   // chunks of CN consecutive elements; lane takes chunk lane, lane+64, ...
-    const ST* xt = x + (size_t)t * H;
+    const ST* xt = x + (size_t)token_row(row_index, n_rows, t) * H;
     const int e0 = blockIdx.x * LOGIT_GROUP + wave;     // this wavefront: experts e0, e0+4, ..., e0+28
 
     // fixed summation order (per lane ascending, then the cross-lane tree) -> deterministic
@@ -82,6 +84,9 @@ __global__ __launch_bounds__(LOGIT_THREADS) void route_logits_kernel(const ST* _
         for (int j = 0; j < XC; ++j) {
             const int c = cb + j * WAVE + lane;
             xp[j] = c < n_chunks ? *reinterpret_cast<const uint4*>(xt + (size_t)c * CN) : make_uint4(0u, 0u, 0u, 0u);
+            // dense copy of the live rows for the kernels that follow (one wavefront per token writes it)
+            if (x_dense && blockIdx.x == 0 && wave == 0 && c < n_chunks)
+                *reinterpret_cast<uint4*>(x_dense + (size_t)t * H + (size_t)c * CN) = xp[j];
         }
 #pragma unroll
         for (int g = 0; g < EG; ++g) {
@@ -320,10 +325,10 @@ static hipError_t launch_logits(const Dims& d, const void* x, const void* w_rout
     dim3 grid((d.E + LOGIT_GROUP - 1) / LOGIT_GROUP, d.T), block(LOGIT_THREADS);
     if (d.bf16)
         hipLaunchKernelGGL(route_logits_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)x, (const uint16_t*)w_router, logits, d.H,
-                           d.E, zero_words, n_zero);
+                           d.E, zero_words, n_zero, d.row_index, d.n_rows, (uint16_t*)d.x_dense);
     else
         hipLaunchKernelGGL(route_logits_kernel<float>, grid, block, 0, s, (const float*)x, (const float*)w_router, logits, d.H, d.E,
-                           zero_words, n_zero);
+                           zero_words, n_zero, d.row_index, d.n_rows, (float*)d.x_dense);
     return hipGetLastError();
 }
 

@@ -168,6 +168,25 @@ def gpu_classify_tokens(conf: np.ndarray, state: np.ndarray, block_len: int, tau
     return out.cpu().numpy()
 
 
+def gpu_layer_rows(case: Case, x_rows: np.ndarray, row_index: np.ndarray, mask=None, token_class=None, ws=None, max_tokens=None):
+    """team_moe_layer_forward_rows over rows `row_index` of x_rows [n_rows, H] (storage dtype); returns y_rows (device tensor,
+    pre-filled with a sentinel so that untouched rows can be recognised), E_A and its size (two-round mode)."""
+    s = case.shape
+    T, n_rows = int(row_index.shape[0]), int(x_rows.shape[0])
+    cfg = tm.make_config(s.H, s.I, s.E, s.k, s.dtype, s.renormalize, max_tokens or max(T, 1))
+    if ws is None:
+        ws = torch.empty(tm.team_moe_workspace_size(cfg), dtype=torch.uint8, device=DEV)
+    y = torch.full((n_rows, s.H), 7.0, dtype=out_dtype(s), device=DEV)
+    d_mask = None if mask is None else torch.from_numpy(mask).to(DEV)
+    d_cls = None if token_class is None else torch.from_numpy(token_class).to(DEV)
+    e_a = torch.full((s.E,), 9, dtype=torch.uint8, device=DEV)
+    n_act = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+    tm.team_moe_layer_forward_rows(cfg, to_dev(x_rows), y, n_rows, torch.from_numpy(np.ascontiguousarray(row_index, np.int32)).to(DEV), T,
+                                   case.d_w["router"], case.d_w["gate"], case.d_w["up"], case.d_w["down"], d_mask, d_cls, e_a, n_act, ws)
+    torch.cuda.synchronize()
+    return y, e_a.cpu().numpy(), int(n_act.cpu().numpy()[0])
+
+
 # ----------------------------------------------------------------------------- oracle side
 def oracle_layer(case: Case, mask, threads=0):
     s = case.shape

@@ -101,6 +101,12 @@ def test_bad_call_arguments_are_rejected_before_any_launch():
     assert lib.team_moe_classify_tokens(fake, fake, 32, 32, None, 33, f32(0.7), 3, fake, st) == -1      # more tokens than rows
     assert lib.team_moe_classify_tokens(fake, fake, 32, 32, None, 32, f32(0.7), -1, fake, st) == -1
     assert lib.team_moe_classify_tokens(fake, fake, 32, 32, None, 32, f32(float("nan")), 3, fake, st) == -1
+    # layer over live rows: the index list and a positive row count are required, one routing mode per call
+    rows_args = (8, fake, fake, fake, fake)
+    assert lib.team_moe_layer_forward_rows(C.byref(cfg), fake, fake, 32, None, *rows_args, None, None, None, None, fake, 1 << 30, st) == -1
+    assert lib.team_moe_layer_forward_rows(C.byref(cfg), fake, fake, 0, fake, *rows_args, None, None, None, None, fake, 1 << 30, st) == -1
+    assert lib.team_moe_layer_forward_rows(C.byref(cfg), fake, fake, 32, fake, *rows_args, fake, fake, None, None, fake, 1 << 30, st) == -1
+    assert lib.team_moe_layer_forward_rows(C.byref(cfg), fake, fake, 32, fake, *rows_args, None, None, None, None, None, 0, st) == -3
     # NULL cfg / NULL size pointer
     assert lib.team_moe_workspace_size(None, C.byref(C.c_size_t())) == -1
     assert lib.team_moe_workspace_size(C.byref(cfg), None) == -1

@@ -313,3 +313,74 @@ def test_classification_feeds_two_round_routing(cfg2_case):
     assert np.array_equal(cls_gpu, orc.classify_tokens(conf, state, 32, 0.7, 3))
     rep = hz.two_round_parity(cfg2_case, cls_gpu)
     say("classified block:", int(cls_gpu.sum()), "first-round tokens ->", rep)
+
+
+# ----------------------------------------------------------------------------- the layer over a list of live rows
+def rows_case(base, n_rows, T, seed, kind="iid"):
+    """x of n_rows rows (same generator as the dense cases) and T distinct live rows in ascending order."""
+    s_all = gen.scaled(base.shape, T=n_rows)
+    x_rows = gen.make_x(s_all, seed=seed, kind=kind, noise_std=0.1)
+    live = np.sort(gen.token_permutation(n_rows, seed=seed)[:T]).astype(np.int32)
+    s_live = gen.scaled(base.shape, T=T)
+    return x_rows, live, hz.Case.make(s_live, x_rows[live], base.w, base.wf, base.d_w)
+
+
+@pytest.mark.parametrize("n_rows,T", [(32, 9), (128, 40), (128, 100), (32, 32)])
+def test_layer_over_live_rows_equals_layer_on_gathered_rows(cfg2_case, n_rows, T):
+    """Only the listed rows are read and written; their results are the bits team_moe_layer_forward gives on the gathered
+    rows (which the other tests check against the oracle), in both routing modes."""
+    x_rows, live, dense = rows_case(cfg2_case, n_rows, T, seed=n_rows + T, kind="candidates" if n_rows == 128 else "iid")
+    mask = c12_mask(dense, 32)
+    _, y_dense = hz.gpu_layer(dense, mask)
+    y_rows, _, _ = hz.gpu_layer_rows(dense, x_rows, live, mask=mask)
+    assert torch.equal(y_rows[torch.from_numpy(live).long().to(hz.DEV)], y_dense)
+    untouched = np.setdiff1d(np.arange(n_rows), live)
+    assert (y_rows[torch.from_numpy(untouched).long().to(hz.DEV)] == 7.0).all()
+    # direct check of the listed rows against the oracle as well
+    o_y, o_idx, _ = hz.oracle_layer(dense, mask)
+    set_safe, _ = hz.safe_tokens(hz.oracle_logits(dense), mask, dense.shape.k)
+    g_idx, g_gate, _ = hz.gpu_route(dense, mask)
+    hz.check_layer(dense, mask, hz.y_to_host(y_rows)[live], g_idx, g_gate, o_y, o_idx, set_safe)
+    # two-round mode on the same rows
+    cls = gen.token_classes(T, max(1, T // 8), seed=T)
+    y2_dense, _, e_a, n_a = hz.gpu_layer_two_round(dense, cls)
+    y2_rows, e_a_rows, n_a_rows = hz.gpu_layer_rows(dense, x_rows, live, token_class=cls)
+    assert np.array_equal(hz.y_to_host(y2_rows)[live], y2_dense) and np.array_equal(e_a, e_a_rows) and n_a == n_a_rows
+
+
+def test_layer_over_live_rows_other_shapes_and_index_handling(cfg5_case, cfg1_case):
+    # fp32 path
+    x_rows, live, dense = rows_case(cfg1_case, 20, 8, seed=1)
+    mask = gen.random_mask(16, 6, seed=0)
+    _, y_dense = hz.gpu_layer(dense, mask)
+    y_rows, _, _ = hz.gpu_layer_rows(dense, x_rows, live, mask=mask)
+    assert torch.equal(y_rows[torch.from_numpy(live).long().to(hz.DEV)], y_dense)
+    # 256 experts, more than 64 tokens (dispatch kernel + both FFN bodies): 96 and 200 live rows of 256
+    for T, M in ((96, 256), (200, 48)):
+        x_rows, live, dense = rows_case(cfg5_case, 256, T, seed=T)
+        mask = None if M == 256 else c12_mask(dense, M)
+        _, y_dense = hz.gpu_layer(dense, mask)
+        y_rows, _, _ = hz.gpu_layer_rows(dense, x_rows, live, mask=mask)
+        assert torch.equal(y_rows[torch.from_numpy(live).long().to(hz.DEV)], y_dense)
+    # rows in any order, and indices outside the tensor are clamped (here: -5 -> row 0, 999 -> last row)
+    x_rows, live, dense = rows_case(cfg1_case, 20, 8, seed=2)
+    order = live[::-1].copy()
+    y_a, _, _ = hz.gpu_layer_rows(dense, x_rows, order, mask=mask if False else None)
+    y_b, _, _ = hz.gpu_layer_rows(dense, x_rows, live, mask=None)
+    assert torch.equal(y_a, y_b)
+    odd = np.array([-5, 3, 999], np.int32)
+    y_c, _, _ = hz.gpu_layer_rows(dense, x_rows, odd, mask=None)
+    y_d, _, _ = hz.gpu_layer_rows(dense, x_rows, np.array([0, 3, 19], np.int32), mask=None)
+    assert torch.equal(y_c, y_d)
+
+
+def test_layer_over_live_rows_rejects_bad_arguments(cfg1_case):
+    s = cfg1_case.shape
+    x_rows = gen.make_x(gen.scaled(s, T=12), seed=0)
+    live = np.array([1, 2], np.int32)
+    with pytest.raises(tm.TeamMoeError) as e:
+        hz.gpu_layer_rows(cfg1_case, x_rows, live, mask=np.ones(s.E, np.uint8), token_class=np.ones(2, np.uint8))
+    assert e.value.status == -1                          # one routing mode per call
+    with pytest.raises(tm.TeamMoeError) as e:
+        hz.gpu_layer_rows(cfg1_case, x_rows, np.arange(12, dtype=np.int32), max_tokens=8)
+    assert e.value.status == -1                          # more live rows than cfg.max_tokens
