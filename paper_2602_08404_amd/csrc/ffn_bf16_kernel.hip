@@ -80,9 +80,14 @@ __device__ __forceinline__ int opaque(int v) {
 }
 
 // One 32-bit load at (uniform base + per-lane byte offset), complete on return.
+// The five idle cycles in front of the load are required, not tuning: under register pressure the compiler keeps the base
+// pointer in lanes of a vector register and moves it back into scalar registers (v_readlane) directly in front of this
+// statement.  A scalar register written by a vector instruction may only be read as a memory instruction's base address five
+// cycles later; the compiler keeps that distance for loads it emits itself but cannot see into this one, and a load issued
+// too early uses a stale base: an access to an arbitrary address.
 __device__ __forceinline__ int global_read_i32(const int32_t* base_uniform, uint32_t byte_off) {
     int v;
-    asm volatile("global_load_dword %0, %1, %2\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(byte_off), "s"(base_uniform) : "memory");
+    asm volatile("s_nop 4\n\tglobal_load_dword %0, %1, %2\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(byte_off), "s"(base_uniform) : "memory");
     return v;
 }
 __device__ __forceinline__ int lds_read_u16(uint32_t a) {
