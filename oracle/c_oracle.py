@@ -22,6 +22,7 @@ def lib():
         _lib.oracle_max_threads.restype = C.c_int
         _lib.oracle_classify_tokens.argtypes = [C.POINTER(C.c_float), C.POINTER(C.c_uint8), C.c_int, C.c_int, C.POINTER(C.c_int32),
                                                 C.c_int, C.c_float, C.c_int, C.POINTER(C.c_uint8)]
+        _lib.oracle_row_representatives.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_int32)]
     return _lib
 
 
@@ -93,6 +94,16 @@ def classify_tokens(conf, state, block_len: int, tau_h: float, L_h: int, live_in
     lib().oracle_classify_tokens(_p(conf, C.c_float), _p(state, C.c_uint8), n, int(block_len),
                                  None if li is None else _p(li, C.c_int32), T, float(tau_h), int(L_h), _p(out, C.c_uint8))
     return out
+
+
+def row_representatives(x_stored: np.ndarray) -> np.ndarray:
+    """rep[t] = first row with the same stored bytes as row t (x_stored: [T,H] array of the storage type, e.g. uint16 bf16 bits)."""
+    x_stored = np.ascontiguousarray(x_stored)
+    T = x_stored.shape[0]
+    row_bytes = x_stored.strides[0]
+    rep = np.empty(T, np.int32)
+    lib().oracle_row_representatives(x_stored.ctypes.data_as(C.c_void_p), T, int(row_bytes), _p(rep, C.c_int32))
+    return rep
 
 
 def dispatch(topk_idx, E: int):

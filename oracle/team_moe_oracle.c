@@ -26,6 +26,9 @@
  *
  * oracle_route_two_round is Algorithm 1 itself (first-round tokens over all experts, E_A = union of their picks,
  * cold tokens inside E_A); oracle_classify_tokens is its step 1 (hot/cold classification, Eq. 4).
+ * oracle_row_representatives names, for every row of a call, the first row with exactly the same stored bytes (candidate
+ * branches of Section "Speculative Exploration for Hot Tokens (SEH)" repeat most rows of the base branch); a layer that
+ * computes each distinct row once must return what oracle_moe_layer returns for all rows.
  *
  * Pins (tests/test_oracle_pins.py): hand-worked example (tests/golden), dense-SwiGLU special case,
  * mask-free top-k MoE written separately, brute-force subset enumeration, superset invariance from
@@ -241,6 +244,23 @@ void oracle_moe_layer(const float *x, int T, int H, int E, int k, int I, int ren
             }
         }
         free(logit); free(hbuf); free(out);
+    }
+}
+
+/* Section "Speculative Exploration for Hot Tokens (SEH)" / "Aligned Token Candidates in SEH": the extra branches are the
+ * base block with one or two more positions accepted, so a call over several branches may hold the same row more than
+ * once.  rep[t] = the smallest j <= t whose row consists of exactly the same row_bytes bytes as row t (stored bits, so
+ * +0 and -0 differ and equal NaN patterns match). */
+void oracle_row_representatives(const void *x, int T, int row_bytes, int32_t *rep) {
+    const unsigned char *rows = (const unsigned char *)x;
+    for (int t = 0; t < T; ++t) {
+        rep[t] = t;
+        for (int j = 0; j < t; ++j) {
+            if (memcmp(rows + (size_t)j * row_bytes, rows + (size_t)t * row_bytes, (size_t)row_bytes) == 0) {
+                rep[t] = j;
+                break;
+            }
+        }
     }
 }
 

@@ -122,6 +122,11 @@ def make_x(shape: MoEShape, seed: int = 0, layer: int = 0, step: int = 0, kind: 
                        Section "Speculative Exploration for Hot Tokens").
     kind="drift":      base ~N(0,1) for the layer plus per-step noise of std ``noise_std`` (hidden states of
                        the same block at successive denoising steps; Section "Temporal Consistency").
+    kind="branches":   T = 4*32 rows: a 32-row base branch and the three extra branches of Section "Aligned Token
+                       Candidates in SEH" as they look where rows do not depend on each other yet (token embeddings):
+                       branch 1 replaces the row of the first candidate position, branch 2 that of the second, branch 3
+                       both (with the same two new rows); every other row repeats the base branch bit for bit.
+                       34 distinct rows out of 128.
     """
     T, H = shape.T, shape.H
     if kind == "iid":
@@ -132,6 +137,17 @@ def make_x(shape: MoEShape, seed: int = 0, layer: int = 0, step: int = 0, kind: 
         base = normal(seed, TAG_X_BASE, layer, 0, L * H).reshape(L, H)
         parts = [base + normal(seed, TAG_X_NOISE, layer, c, L * H, noise_std).reshape(L, H) for c in range(T // L)]
         x = np.concatenate(parts, axis=0)
+    elif kind == "branches":
+        L = 32
+        assert T == 4 * L
+        base = normal(seed, TAG_X_BASE, layer, 0, L * H).reshape(L, H)
+        new_rows = normal(seed, TAG_X_NOISE, layer, step, 2 * H).reshape(2, H)
+        p1, p2 = (int(v) for v in _stream(seed, TAG_X_NOISE, layer, 1000 + step).permutation(L)[:2])
+        b1, b2, b3 = base.copy(), base.copy(), base.copy()
+        b1[p1] = new_rows[0]
+        b2[p2] = new_rows[1]
+        b3[p1], b3[p2] = new_rows[0], new_rows[1]
+        x = np.concatenate([base, b1, b2, b3], axis=0)
     elif kind == "drift":
         base = normal(seed, TAG_X_BASE, layer, 0, T * H).reshape(T, H)
         x = base + normal(seed, TAG_X_NOISE, layer, step, T * H, noise_std).reshape(T, H)

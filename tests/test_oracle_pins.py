@@ -437,3 +437,43 @@ def test_summed_probability_mask():
     assert gen.activated_set_by_summed_probability(logits, 2).tolist() == [1, 0, 1, 0]
     assert gen.activated_set_by_summed_probability(logits, 3).tolist() == [1, 0, 1, 1]
     assert gen.activated_set_by_summed_probability(np.zeros((3, 4), np.float32), 2).tolist() == [1, 1, 0, 0]
+
+
+# ----------------------------------------------------------------------------- repeated rows of candidate branches
+def test_row_representatives_hand_cases():
+    """Worked by hand: rows A B A C B A -> 0 1 0 3 1 0; +0 and -0 are different stored rows; equal NaN patterns match."""
+    a, b, c = np.float32([1, 2, 3, 4]), np.float32([1, 2, 3, 5]), np.float32([0, 0, 0, 0])
+    x = np.stack([a, b, a, c, b, a])
+    assert orc.row_representatives(x).tolist() == [0, 1, 0, 3, 1, 0]
+    z = np.zeros((3, 4), np.float32)
+    z[1, 2] = -0.0
+    assert orc.row_representatives(z).tolist() == [0, 1, 0]
+    n = np.full((2, 4), np.nan, np.float32)
+    assert orc.row_representatives(n).tolist() == [0, 0]
+    # a difference in the last byte of the row only, and in the first only
+    u = np.zeros((3, 8), np.uint16)
+    u[1, 7] = 0x0100
+    u[2, 0] = 0x0001
+    assert orc.row_representatives(u).tolist() == [0, 1, 2]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_row_representatives_match_numpy_unique(seed):
+    """First occurrence per distinct row from NumPy's unique() over the stored bit patterns."""
+    rng = np.random.default_rng(seed)
+    pool = rng.integers(0, 1 << 16, size=(7, 24), dtype=np.uint16)
+    x = pool[rng.integers(0, 7, size=60)]
+    _, first, inverse = np.unique(x, axis=0, return_index=True, return_inverse=True)
+    rep = orc.row_representatives(x)
+    assert rep.tolist() == first[np.ravel(inverse)].tolist()
+    assert np.all(rep <= np.arange(60)) and np.all(rep[rep] == rep)
+
+
+def test_branch_inputs_have_34_distinct_rows_and_equal_rows_give_equal_outputs():
+    s = gen.scaled(gen.CFG3, H=64, I=32, E=8, k=2)
+    x = gen.make_x(s, seed=3, kind="branches")
+    rep = orc.row_representatives(x)
+    assert len(set(rep.tolist())) == 34 and np.all(rep[:32] == np.arange(32))
+    w = gen.make_weights(s, seed=3)
+    y, idx, gate = orc.moe_layer(gen.as_f32(x), *(gen.as_f32(w[n]) for n in ("router", "gate", "up", "down")), s.k)
+    assert np.array_equal(y, y[rep]) and np.array_equal(idx, idx[rep]) and np.array_equal(gate, gate[rep])
