@@ -233,6 +233,46 @@ def main() -> int:
         two_round = {"first_round_tokens": n_first, "activated": float(np.mean(n_act)), "ms_per_layer": s2 * 1e3, "tokens_per_s": T / s2}
         log(f"[bench] {wl} two-round routing: {n_first} first-round tokens -> |E_A| = {np.mean(n_act):.1f}, layer {s2 * 1e6:.1f} us")
 
+    # ---- candidate branches with repeated rows (Section "Aligned Token Candidates in SEH"): the same layer over 4 x 32 rows of
+    #      which 34 are distinct, computed row by row and with every distinct row computed once
+    branches = None
+    if wl == "cfg3" and not args.masks:
+        bx, bm = [], []
+        for c in range(n_sets):
+            d_x = dev_t(gen.make_x(shape, seed=0, layer=0, step=c, kind="branches"))
+            bx.append(d_x)
+            bm.append(torch.from_numpy(gen.activated_set_by_summed_probability(gpu_logits(d_x, sets[c][0]["router"]), headline)).to(dev))
+        d_rep = torch.zeros((T,), dtype=torch.int32, device=dev)
+        d_nu = torch.zeros((1,), dtype=torch.int32, device=dev)
+
+        def plain(i):
+            d_w = sets[i % n_sets][0]
+            tm.team_moe_layer_forward(cfg, bx[i % n_sets], T, d_w["router"], d_w["gate"], d_w["up"], d_w["down"], bm[i % n_sets], y, ws)
+
+        def unique(i):
+            d_w = sets[i % n_sets][0]
+            tm.team_moe_layer_forward_unique_rows(cfg, bx[i % n_sets], T, d_w["router"], d_w["gate"], d_w["up"], d_w["down"],
+                                                  bm[i % n_sets], y, d_rep, d_nu, ws)
+
+        def timed(fn, n):
+            for i in range(10):
+                fn(i)
+            torch.cuda.synchronize()
+            t_begin = time.perf_counter()
+            for i in range(n):
+                fn(i)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t_begin) / n
+
+        nb = max(50, steps // 2)
+        s_plain, s_unique = timed(plain, nb), timed(unique, nb)
+        n_unique = int(d_nu.item())
+        branches = {"rows": T, "distinct_rows": n_unique, "rows_per_expert": A / headline, "distinct_rows_per_expert": n_unique * k / headline,
+                    "ms_per_layer_all_rows": s_plain * 1e3, "ms_per_layer_distinct_rows": s_unique * 1e3,
+                    "tokens_per_s_all_rows": T / s_plain, "tokens_per_s_distinct_rows": T / s_unique}
+        log(f"[bench] cfg3 branches with repeated rows: {n_unique} distinct of {T}; layer {s_plain * 1e6:.1f} us row by row, "
+            f"{s_unique * 1e6:.1f} us with distinct rows computed once")
+
     # ---- context: plain device-to-device copy rate (read + write bytes) of 1 GiB, the practical streaming ceiling
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
@@ -278,7 +318,8 @@ def main() -> int:
            "warmup": warmup, "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16", "data": "synthetic",
            "config": {"workload": desc, "tokens": T, "activated": headline, "touched": touched[headline], "layers_per_step": layers_per_step},
-           "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep, "two_round": two_round, "device_copy_GBps": copy_gbps}
+           "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep, "two_round": two_round, "branches": branches,
+           "device_copy_GBps": copy_gbps}
     if wl == "cfg4":
         out["ms_per_block_16_steps"] = sec_per_step * 1e3 * 16
     print(json.dumps(out), flush=True)

@@ -201,6 +201,25 @@ int team_moe_layer_forward_rows(const team_moe_config* cfg, const void* x_rows, 
                                 const uint8_t* token_class /* [T] or NULL */, uint8_t* activated_mask_out /* [E] or NULL */,
                                 int32_t* n_activated_out /* [1] or NULL */, void* workspace, size_t ws_bytes, void* stream);
 
+/*
+ * team_moe_layer_forward for calls that hold the same row more than once (Section "Speculative Exploration for Hot Tokens
+ * (SEH)" and "Aligned Token Candidates in SEH": the extra branches are the base block with one or two more positions
+ * accepted, so where rows do not yet depend on each other most rows of a multi-branch call repeat the base branch).
+ * Every distinct row is routed and run through its experts once; repeated rows receive a copy of that result.
+ *   Two rows are the same when all their stored bytes are equal (so +0 and -0 differ).  The router finds them on the
+ *   device: a hash per row, then a byte-wise comparison of rows whose hashes match.
+ *   row_rep_out [T] int32 or NULL: row_rep_out[t] = the first token whose row equals token t's (t itself if none before).
+ *   n_unique_out [1] int32 or NULL: number of distinct rows.
+ * y is what team_moe_layer_forward returns for the same arguments, up to the rounding differences between the kernel
+ * variants the two calls may choose (the choice depends on the number of rows per expert); y[t] and y[row_rep[t]] are
+ * bit-identical.  Routing is single-round (expert_mask may be NULL).
+ */
+int team_moe_layer_forward_unique_rows(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router,
+                                       const void* w_gate, const void* w_up, const void* w_down,
+                                       const uint8_t* expert_mask /* [E] or NULL */, void* y,
+                                       int32_t* row_rep_out /* [T] or NULL */, int32_t* n_unique_out /* [1] or NULL */,
+                                       void* workspace, size_t ws_bytes, void* stream);
+
 /* Static, NUL-terminated description of a team_status value. */
 const char* team_moe_status_string(int status);
 

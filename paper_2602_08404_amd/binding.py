@@ -19,7 +19,8 @@ STATUS_OK = 0
 
 EXPORTS = ["team_moe_workspace_size", "team_moe_route", "team_moe_build_dispatch", "team_moe_expert_ffn",
            "team_moe_combine", "team_moe_layer_forward", "team_moe_route_two_round", "team_moe_layer_forward_two_round",
-           "team_moe_classify_tokens", "team_moe_layer_forward_rows", "team_moe_status_string"]
+           "team_moe_classify_tokens", "team_moe_layer_forward_rows", "team_moe_layer_forward_unique_rows",
+           "team_moe_status_string"]
 
 
 class TeamMoeError(RuntimeError):
@@ -60,6 +61,7 @@ def lib() -> C.CDLL:
         L.team_moe_layer_forward_two_round.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_classify_tokens.argtypes = [vp, vp, i32, i32, vp, i32, C.c_float, i32, vp, vp]
         L.team_moe_layer_forward_rows.argtypes = [cfgp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.team_moe_layer_forward_unique_rows.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_status_string.argtypes = [C.c_int]
         L.team_moe_status_string.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -158,3 +160,12 @@ def team_moe_layer_forward_rows(cfg: Config, x_rows, y_rows, n_rows: int, row_in
                                              _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(expert_mask), _ptr(token_class),
                                              _ptr(activated_mask_out), _ptr(n_activated_out), _ptr(workspace), ws_bytes,
                                              stream if stream is not None else _stream()), "team_moe_layer_forward_rows")
+
+
+def team_moe_layer_forward_unique_rows(cfg: Config, x, T: int, w_router, w_gate, w_up, w_down, expert_mask, y, row_rep_out,
+                                       n_unique_out, workspace, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().team_moe_layer_forward_unique_rows(C.byref(cfg), _ptr(x), T, _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+                                                    _ptr(expert_mask), _ptr(y), _ptr(row_rep_out), _ptr(n_unique_out),
+                                                    _ptr(workspace), ws_bytes, stream if stream is not None else _stream()),
+           "team_moe_layer_forward_unique_rows")

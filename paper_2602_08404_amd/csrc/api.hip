@@ -47,7 +47,7 @@ Dims dims_of(const team_moe_config* c, int32_t T) {
 // Workspace layout, sized for max_tokens.  The expert FFN's scratch (control block, h) comes first so that
 // team_moe_expert_ffn and team_moe_layer_forward agree on where it is.
 struct Layout {
-    size_t ctrl, h, logits, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, two_round, x_dense, total;
+    size_t ctrl, h, logits, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, two_round, x_dense, row_hash, row_rep, n_unique, total;
 };
 Layout layout_of(const team_moe_config* c) {
     const size_t A = (size_t)c->max_tokens * c->top_k;
@@ -67,6 +67,9 @@ Layout layout_of(const team_moe_config* c) {
     L.expert_out = off;   off += align256(A * c->hidden * 4);
     L.two_round = off;    off += 256;                       // bit set E_A and arrival counter of two-round routing
     L.x_dense = off;      off += align256((size_t)c->max_tokens * c->hidden * elem);   // live rows gathered by the router (row-index calls)
+    L.row_hash = off;     off += align256((size_t)c->max_tokens * 8);                  // repeated-row search of the router
+    L.row_rep = off;      off += align256((size_t)c->max_tokens * 4);
+    L.n_unique = off;     off += 256;
     L.total = off;
     return L;
 }
@@ -207,7 +210,8 @@ namespace {
 int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const void* w_gate, const void* w_up,
                   const void* w_down, const uint8_t* expert_mask, const uint8_t* token_class, uint8_t* activated_mask_out,
                   int32_t* n_activated_out, void* y, void* workspace, size_t ws_bytes, void* stream,
-                  const int32_t* row_index = nullptr, int32_t n_rows = 0) {
+                  const int32_t* row_index = nullptr, int32_t n_rows = 0, bool unique_rows = false, int32_t* row_rep_out = nullptr,
+                  int32_t* n_unique_out = nullptr) {
     int st = check_cfg(cfg);
     if (st != TEAM_OK) return st;
     if ((st = check_T(cfg, T)) != TEAM_OK) return st;
@@ -234,6 +238,16 @@ int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const vo
         d.x_dense = ws + L.x_dense;
         x_ffn = d.x_dense;
     }
+    team::RowDedup dedup;
+    if (unique_rows) {                   // the router finds repeated rows; only the first of each is routed and computed
+        dedup.hash = (unsigned long long*)(ws + L.row_hash);
+        dedup.rep = row_rep_out ? row_rep_out : (int32_t*)(ws + L.row_rep);
+        dedup.n_unique = n_unique_out ? n_unique_out : (int32_t*)(ws + L.n_unique);
+        const char* bits = getenv("TEAM_MOE_ROW_HASH_BITS");           // testing aid: compare fewer bits of the row hashes
+        const int nb = bits ? atoi(bits) : 64;
+        dedup.hash_mask = nb >= 64 ? ~0ull : (nb <= 0 ? 0ull : ((1ull << nb) - 1ull));
+        d.row_rep = dedup.rep;
+    }
     hipStream_t s = (hipStream_t)stream;
     clear_stale_error();
     // Small calls (the block-decoding regime): route -> expert FFN -> combine.  The FFN kernel groups the routing table itself
@@ -246,7 +260,7 @@ int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const vo
         st = hip_status(team::launch_route_two_round(d, x, w_router, token_class, activated_mask_out, n_activated_out, topk_idx,
                                                      topk_gate, logits, ws + L.two_round, short_path ? cz : none, s));
     else
-        st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, logits, short_path ? cz : none, s));
+        st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, logits, short_path ? cz : none, s, dedup));
     if (st != TEAM_OK) return st;
     if (short_path) {
         if ((st = hip_status(team::launch_ffn_bf16_from_routing(d, (const uint16_t*)x_ffn, topk_idx, inv_pos, (const uint16_t*)w_gate,
@@ -288,6 +302,13 @@ int team_moe_layer_forward_rows(const team_moe_config* cfg, const void* x_rows, 
     if (expert_mask && token_class) return TEAM_ERR_INVALID_ARG;       // one routing mode per call
     return layer_forward(cfg, x_rows, T, w_router, w_gate, w_up, w_down, expert_mask, token_class, activated_mask_out, n_activated_out,
                          y_rows, workspace, ws_bytes, stream, row_index, n_rows);
+}
+
+int team_moe_layer_forward_unique_rows(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const void* w_gate,
+                                       const void* w_up, const void* w_down, const uint8_t* expert_mask, void* y, int32_t* row_rep_out,
+                                       int32_t* n_unique_out, void* workspace, size_t ws_bytes, void* stream) {
+    return layer_forward(cfg, x, T, w_router, w_gate, w_up, w_down, expert_mask, nullptr, nullptr, nullptr, y, workspace, ws_bytes,
+                         stream, nullptr, 0, true, row_rep_out, n_unique_out);
 }
 
 const char* team_moe_status_string(int status) {

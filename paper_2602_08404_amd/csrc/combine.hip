@@ -12,8 +12,10 @@ constexpr int C_MAX_K = 16;      // top_k limit of the library
 template <bool BF16>
 __global__ __launch_bounds__(COMBINE_THREADS) void combine_kernel(const float* __restrict__ expert_out, const float* __restrict__ gate,
                                                                   const int32_t* __restrict__ inv_pos, void* __restrict__ y, int H, int k,
-                                                                  const int32_t* __restrict__ row_index, int n_rows) {
+                                                                  const int32_t* __restrict__ row_index, int n_rows,
+                                                                  const int32_t* __restrict__ row_rep) {
     const int t = blockIdx.y;
+    const int src = row_rep ? row_rep[t] : t;           // token whose expert rows and gates this token's result is made of
     const size_t yrow = (size_t)token_row(row_index, n_rows, t);
     const int h4 = (blockIdx.x * COMBINE_THREADS + threadIdx.x) * 4;
     if (h4 >= H) return;
@@ -24,8 +26,8 @@ __global__ __launch_bounds__(COMBINE_THREADS) void combine_kernel(const float* _
     float4 o[C_MAX_K];
 #pragma unroll
     for (int s = 0; s < C_MAX_K; ++s) {
-        p[s] = s < k ? inv_pos[(size_t)t * k + s] : -1;
-        g[s] = s < k ? gate[(size_t)t * k + s] : 0.f;
+        p[s] = s < k ? inv_pos[(size_t)src * k + s] : -1;
+        g[s] = s < k ? gate[(size_t)src * k + s] : 0.f;
     }
 #pragma unroll
     for (int s = 0; s < C_MAX_K; ++s)
@@ -49,9 +51,9 @@ __global__ __launch_bounds__(COMBINE_THREADS) void combine_kernel(const float* _
 hipError_t launch_combine(const Dims& d, const float* expert_out, const float* gate, const int32_t* inv_pos, void* y, hipStream_t s) {
     dim3 grid((d.H / 4 + COMBINE_THREADS - 1) / COMBINE_THREADS, d.T), block(COMBINE_THREADS);
     if (d.bf16)
-        hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, s, expert_out, gate, inv_pos, y, d.H, d.k, d.row_index, d.n_rows);
+        hipLaunchKernelGGL(combine_kernel<true>, grid, block, 0, s, expert_out, gate, inv_pos, y, d.H, d.k, d.row_index, d.n_rows, d.row_rep);
     else
-        hipLaunchKernelGGL(combine_kernel<false>, grid, block, 0, s, expert_out, gate, inv_pos, y, d.H, d.k, d.row_index, d.n_rows);
+        hipLaunchKernelGGL(combine_kernel<false>, grid, block, 0, s, expert_out, gate, inv_pos, y, d.H, d.k, d.row_index, d.n_rows, d.row_rep);
     return hipGetLastError();
 }
 

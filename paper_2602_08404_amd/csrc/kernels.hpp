@@ -17,6 +17,19 @@ struct Dims {
     const int32_t* row_index = nullptr;
     int n_rows = 0;
     void* x_dense = nullptr;
+    // Repeated rows (row_rep != nullptr): row_rep[t] is the first token whose row holds the same bytes as token t's.  Only
+    // tokens with row_rep[t] == t are routed and computed; the combine kernel gives every token the result of row_rep[t].
+    const int32_t* row_rep = nullptr;
+};
+
+// Search for repeated rows inside the router (hash == nullptr: off).  The logits kernel writes a 64-bit hash of every row and
+// clears *n_unique; the selection kernel of token t compares hashes with the tokens before it, confirms a match byte by byte,
+// writes rep[t], counts the tokens that are their own representative and leaves the routing table of the others empty.
+struct RowDedup {
+    unsigned long long* hash = nullptr;   // [T]
+    int32_t* rep = nullptr;               // [T]
+    int32_t* n_unique = nullptr;          // [1]
+    unsigned long long hash_mask = ~0ull; // bits of the hash that are compared (fewer bits: more byte-wise confirmations)
 };
 
 // Words of the FFN control block that must be zero before an FFN launch: `header` leading words, then one word
@@ -28,7 +41,7 @@ struct CtrlZero {
 // logits: [T,E] floats, required (scratch of the selection kernel and, for the caller, the router scores).
 // ctrl: control block the selection kernel also clears for an expert FFN that follows without a dispatch kernel.
 hipError_t launch_route(const Dims& d, const void* x, const void* w_router, const uint8_t* mask, int32_t* topk_idx,
-                        float* topk_gate, float* logits, CtrlZero ctrl, hipStream_t s);
+                        float* topk_gate, float* logits, CtrlZero ctrl, hipStream_t s, RowDedup dedup = RowDedup());
 // Two-round routing (Algorithm 1): tokens with token_class != 0 are routed over all experts, E_A = union of their picks,
 // the other tokens are routed inside E_A.  state: 256 bytes of device memory (cleared by the call); mask_out [E] bytes and
 // n_activated_out [1] may be null.  T <= 1024.

@@ -9,6 +9,10 @@
 //            allowed experts that beat it (larger logit, or equal logit and lower id): every thread counts its
 //            own rank against the logits in LDS, so there is no serial arg-max loop; experts with rank < k write
 //            themselves into their slot.  One wavefront then turns the selected logits into gates.
+//   repeated rows : optionally the logits kernel also hashes every row and the selection kernel of a token looks for an
+//            earlier token with the same row (hash match, then a byte-wise comparison); such a token gets an empty
+//            routing table and later the result of the earlier one (candidate branches of Section "Speculative
+//            Exploration for Hot Tokens (SEH)" repeat most rows of the base branch).
 //   two-round select : Algorithm 1 in one launch.  Workgroups are ordered first-round tokens (newly accepted and
 //            hot) before cold tokens.  A first-round workgroup selects over all experts, ORs its picks into a
 //            device-wide bit set E_A and counts itself done; a cold workgroup waits until every first-round
@@ -56,12 +60,33 @@ template <> __device__ __forceinline__ void unpack_chunk<float>(const uint4& v, 
     out[0] = __uint_as_float(v.x); out[1] = __uint_as_float(v.y); out[2] = __uint_as_float(v.z); out[3] = __uint_as_float(v.w);
 }
 
+// Hash of one 16-byte chunk and its position in the row (multiply / shift-xor mixing).  Rows with equal bytes have equal
+// hashes; the converse is confirmed byte by byte where it matters.
+__device__ __forceinline__ unsigned long long chunk_hash(const uint4& v, uint32_t pos) {
+    unsigned long long a = ((unsigned long long)v.y << 32 | v.x) + 0x9E3779B97F4A7C15ull * (pos + 1u);
+    unsigned long long b = ((unsigned long long)v.w << 32 | v.z) ^ 0xC2B2AE3D27D4EB4Full;
+    a ^= a >> 31; a *= 0xBF58476D1CE4E5B9ull;
+    b ^= b >> 29; b *= 0x94D049BB133111EBull;
+    unsigned long long h = a ^ (b + (a << 7) + (a >> 3));
+    h ^= h >> 32; h *= 0xD6E8FEB86659FD93ull; h ^= h >> 29;
+    return h;
+}
+__device__ __forceinline__ uint32_t wave_xor_u32(uint32_t v) {
+    v ^= dpp_u32<DPP_XOR1>(v);
+    v ^= dpp_u32<DPP_XOR2>(v);
+    v ^= dpp_u32<DPP_HALF_MIRROR>(v);
+    v ^= dpp_u32<DPP_MIRROR>(v);
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 0) ^ (uint32_t)__builtin_amdgcn_readlane((int)v, 16) ^
+           (uint32_t)__builtin_amdgcn_readlane((int)v, 32) ^ (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+}
+
 template <typename ST>
 __global__ __launch_bounds__(LOGIT_THREADS) void route_logits_kernel(const ST* __restrict__ x, const ST* __restrict__ w_router,
                                                                      float* __restrict__ logits, int H, int E,
                                                                      uint32_t* __restrict__ zero_words, int n_zero,
                                                                      const int32_t* __restrict__ row_index, int n_rows,
-                                                                     ST* __restrict__ x_dense) {
+                                                                     ST* __restrict__ x_dense,
+                                                                     unsigned long long* __restrict__ row_hash) {
     constexpr int CN = Chunk<ST>::N;
     // state the selection kernel that follows starts from (two-round routing: bit set and arrival counter)
     if (zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < n_zero) zero_words[threadIdx.x] = 0u;
@@ -77,6 +102,8 @@ __global__ __launch_bounds__(LOGIT_THREADS) void route_logits_kernel(const ST* _
     float acc[EG];
 #pragma unroll
     for (int g = 0; g < EG; ++g) acc[g] = 0.f;
+    const bool first_wave_of_token = blockIdx.x == 0 && wave == 0;
+    unsigned long long hash = 0ull;
     for (int cb = 0; cb < n_chunks; cb += WAVE * XC) {
         // 16-byte packed chunks stay packed in registers until they are multiplied
         uint4 xp[XC], wp[EG][XC];
@@ -85,8 +112,9 @@ __global__ __launch_bounds__(LOGIT_THREADS) void route_logits_kernel(const ST* _
             const int c = cb + j * WAVE + lane;
             xp[j] = c < n_chunks ? *reinterpret_cast<const uint4*>(xt + (size_t)c * CN) : make_uint4(0u, 0u, 0u, 0u);
             // dense copy of the live rows for the kernels that follow (one wavefront per token writes it)
-            if (x_dense && blockIdx.x == 0 && wave == 0 && c < n_chunks)
+            if (x_dense && first_wave_of_token && c < n_chunks)
                 *reinterpret_cast<uint4*>(x_dense + (size_t)t * H + (size_t)c * CN) = xp[j];
+            if (row_hash && first_wave_of_token && c < n_chunks) hash ^= chunk_hash(xp[j], (uint32_t)c);
         }
 #pragma unroll
         for (int g = 0; g < EG; ++g) {
@@ -116,6 +144,10 @@ __global__ __launch_bounds__(LOGIT_THREADS) void route_logits_kernel(const ST* _
         const float v = wave_sum(acc[g]);
         const int e = e0 + g * LOGIT_WAVES;
         if (lane == 0 && e < E) logits[(size_t)t * E + e] = v;
+    }
+    if (row_hash && first_wave_of_token) {              // exclusive-or of the chunk hashes: any order gives the same value
+        const uint32_t lo = wave_xor_u32((uint32_t)hash), hi = wave_xor_u32((uint32_t)(hash >> 32));
+        if (lane == 0) row_hash[t] = ((unsigned long long)hi << 32) | lo;
     }
 }
 
@@ -195,13 +227,52 @@ __device__ __forceinline__ void clear_ffn_ctrl(const CtrlZero& ctrl, int tid, in
     if (tid < E) ctrl.words[ctrl.header + tid * ctrl.stride] = 0;
 }
 
+// First token j < t whose row holds the same row_bytes bytes as token t's (t itself if there is none); all threads of the
+// workgroup take part and get the result.  Candidates are the tokens with the same (masked) hash, in ascending order; each is
+// confirmed by comparing the rows.
+__device__ __forceinline__ int first_equal_row(const RowDedup& dd, const unsigned char* __restrict__ x, int row_bytes, int t, int tid) {
+    __shared__ int s_best;
+    const unsigned long long my_hash = dd.hash[t] & dd.hash_mask;
+    const uint4* mine = reinterpret_cast<const uint4*>(x + (size_t)t * row_bytes);
+    int after = -1;                                      // candidates up to here have been looked at
+    while (true) {
+        if (tid == 0) s_best = t;
+        __syncthreads();
+        for (int j = after + 1 + tid; j < t; j += SELECT_THREADS)
+            if ((dd.hash[j] & dd.hash_mask) == my_hash) { atomicMin(&s_best, j); break; }
+        __syncthreads();
+        const int cand = s_best;
+        if (cand >= t) return t;
+        const uint4* other = reinterpret_cast<const uint4*>(x + (size_t)cand * row_bytes);
+        bool same = true;
+        for (int c = tid; c < row_bytes / 16; c += SELECT_THREADS) {
+            const uint4 a = mine[c], b = other[c];
+            same = same && a.x == b.x && a.y == b.y && a.z == b.z && a.w == b.w;
+        }
+        if (__syncthreads_and(same)) return cand;        // (also orders this round's reads of s_best before the next write)
+        after = cand;
+    }
+}
+
 __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(const float* __restrict__ logits, const uint8_t* __restrict__ mask,
                                                                       int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate,
-                                                                      int E, int k, int renormalize, CtrlZero ctrl) {
+                                                                      int E, int k, int renormalize, CtrlZero ctrl, RowDedup dd,
+                                                                      const unsigned char* __restrict__ x, int row_bytes) {
     __shared__ SelectLds sm;
     const int t = blockIdx.x;
     const int e = threadIdx.x;
     if (ctrl.words && t == 0) clear_ffn_ctrl(ctrl, e, E);   // control block of an expert FFN that follows without a dispatch kernel
+    if (dd.hash) {
+        const int rep = first_equal_row(dd, x, row_bytes, t, e);
+        if (e == 0) {
+            dd.rep[t] = rep;
+            if (rep == t) atomicAdd(dd.n_unique, 1);
+        }
+        if (rep != t) {                                  // computed once, for token rep: this token takes no part in the expert FFN
+            if (e < k) { topk_idx[(size_t)t * k + e] = -1; topk_gate[(size_t)t * k + e] = 0.f; }
+            return;
+        }
+    }
     float v = 0.f;
     bool ok = false;
     if (e < E) {
@@ -321,23 +392,25 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_two_round_kernel(
 }
 
 static hipError_t launch_logits(const Dims& d, const void* x, const void* w_router, float* logits, uint32_t* zero_words, int n_zero,
-                                hipStream_t s) {
+                                hipStream_t s, unsigned long long* row_hash = nullptr) {
     dim3 grid((d.E + LOGIT_GROUP - 1) / LOGIT_GROUP, d.T), block(LOGIT_THREADS);
     if (d.bf16)
         hipLaunchKernelGGL(route_logits_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)x, (const uint16_t*)w_router, logits, d.H,
-                           d.E, zero_words, n_zero, d.row_index, d.n_rows, (uint16_t*)d.x_dense);
+                           d.E, zero_words, n_zero, d.row_index, d.n_rows, (uint16_t*)d.x_dense, row_hash);
     else
         hipLaunchKernelGGL(route_logits_kernel<float>, grid, block, 0, s, (const float*)x, (const float*)w_router, logits, d.H, d.E,
-                           zero_words, n_zero, d.row_index, d.n_rows, (float*)d.x_dense);
+                           zero_words, n_zero, d.row_index, d.n_rows, (float*)d.x_dense, row_hash);
     return hipGetLastError();
 }
 
 hipError_t launch_route(const Dims& d, const void* x, const void* w_router, const uint8_t* mask, int32_t* topk_idx,
-                        float* topk_gate, float* logits, CtrlZero ctrl, hipStream_t s) {
-    hipError_t err = launch_logits(d, x, w_router, logits, nullptr, 0, s);
+                        float* topk_gate, float* logits, CtrlZero ctrl, hipStream_t s, RowDedup dedup) {
+    const int row_bytes = d.H * (d.bf16 ? 2 : 4);
+    if (dedup.hash && (d.row_index || row_bytes % 16 != 0 || !dedup.rep || !dedup.n_unique)) return hipErrorInvalidValue;
+    hipError_t err = launch_logits(d, x, w_router, logits, (uint32_t*)dedup.n_unique, dedup.hash ? 1 : 0, s, dedup.hash);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(route_select_kernel, dim3(d.T), dim3(SELECT_THREADS), 0, s, logits, mask, topk_idx, topk_gate, d.E, d.k,
-                       d.renormalize, ctrl);
+                       d.renormalize, ctrl, dedup, (const unsigned char*)x, row_bytes);
     return hipGetLastError();
 }
 

@@ -187,6 +187,23 @@ def gpu_layer_rows(case: Case, x_rows: np.ndarray, row_index: np.ndarray, mask=N
     return y, e_a.cpu().numpy(), int(n_act.cpu().numpy()[0])
 
 
+def gpu_layer_unique_rows(case: Case, mask: Optional[np.ndarray], want_tables=True, ws=None):
+    """team_moe_layer_forward_unique_rows; returns (y host fp64, y device, row_rep, n_unique) (tables None when not requested)."""
+    s = case.shape
+    if ws is None:
+        ws = torch.empty(tm.team_moe_workspace_size(case.cfg), dtype=torch.uint8, device=DEV)
+    y = torch.full((s.T, s.H), 7.0, dtype=out_dtype(s), device=DEV)
+    d_mask = None if mask is None else torch.from_numpy(mask).to(DEV)
+    rep = torch.full((s.T,), -7, dtype=torch.int32, device=DEV) if want_tables else None
+    n_unique = torch.full((1,), -7, dtype=torch.int32, device=DEV) if want_tables else None
+    tm.team_moe_layer_forward_unique_rows(case.cfg, case.d_x, s.T, case.d_w["router"], case.d_w["gate"], case.d_w["up"],
+                                          case.d_w["down"], d_mask, y, rep, n_unique, ws)
+    torch.cuda.synchronize()
+    if not want_tables:
+        return y_to_host(y), y, None, None
+    return y_to_host(y), y, rep.cpu().numpy(), int(n_unique.cpu().numpy()[0])
+
+
 # ----------------------------------------------------------------------------- oracle side
 def oracle_layer(case: Case, mask, threads=0):
     s = case.shape
@@ -299,6 +316,26 @@ def full_parity(case: Case, mask, threads=0):
     layer_err, n_band = check_layer(case, mask, y_gpu, g_idx, g_gate, o_y, o_idx, set_safe)
     return {"ffn_err": float(ffn_err), "layer_err": layer_err, "band_tokens": n_band, "unsafe": int((~set_safe).sum()),
             "n_active": n_active}
+
+
+def unique_rows_parity(case: Case, mask, threads=0):
+    """team_moe_layer_forward_unique_rows: the table of first equal rows is bit-exact against the oracle's byte-wise
+    definition; y is compared, for every row, with the oracle's plain layer over all rows; repeated rows carry the bits of
+    their first occurrence; the call without the optional outputs gives the same bits."""
+    s = case.shape
+    o_rep = orc.row_representatives(case.x)
+    y_gpu, y_dev, rep, n_unique = gpu_layer_unique_rows(case, mask)
+    assert np.array_equal(rep, o_rep)
+    assert n_unique == int((o_rep == np.arange(s.T)).sum())
+    assert torch.equal(y_dev, y_dev[torch.from_numpy(o_rep).long().to(DEV)])
+    _, y_dev2, _, _ = gpu_layer_unique_rows(case, mask, want_tables=False)
+    assert torch.equal(y_dev, y_dev2)
+    o_y, o_idx, _ = oracle_layer(case, mask, threads)
+    o_logits = oracle_logits(case)
+    g_idx, g_gate, _ = gpu_route(case, mask)
+    set_safe, _ = safe_tokens(o_logits, mask, s.k)
+    layer_err, n_band = check_layer(case, mask, y_gpu, g_idx, g_gate, o_y, o_idx, set_safe)
+    return {"n_unique": n_unique, "layer_err": layer_err, "band_tokens": n_band}
 
 
 def two_round_parity(case: Case, token_class: np.ndarray, threads=0):

@@ -394,3 +394,67 @@ def test_layer_over_live_rows_rejects_bad_arguments(cfg1_case):
     with pytest.raises(tm.TeamMoeError) as e:
         hz.gpu_layer_rows(cfg1_case, x_rows, np.arange(12, dtype=np.int32), max_tokens=8)
     assert e.value.status == -1                          # more live rows than cfg.max_tokens
+
+
+# ----------------------------------------------------------------------------- repeated rows of candidate branches
+def branch_case(cfg2_case, seed=0):
+    s = gen.CFG3
+    return cfg2_case.with_x(s, gen.make_x(s, seed=seed, kind="branches"))
+
+
+def test_cfg3_branches_with_repeated_rows(cfg2_case):
+    """Four branches of 32 positions, 34 distinct rows: one pass over the distinct rows, copies for the others."""
+    case = branch_case(cfg2_case)
+    r = hz.unique_rows_parity(case, c12_mask(case, 32))
+    assert r["n_unique"] == 34
+    say("branches M=32", r)
+    say("branches no mask", hz.unique_rows_parity(case, None))
+
+
+@pytest.mark.parametrize("bits", ["0", "3"])
+def test_repeated_rows_with_colliding_hashes(cfg2_case, bits, monkeypatch):
+    """With only a few hash bits compared, most candidates are different rows and the byte-wise comparison decides."""
+    monkeypatch.setenv("TEAM_MOE_ROW_HASH_BITS", bits)
+    case = branch_case(cfg2_case, seed=1)
+    say("hash bits", bits, hz.unique_rows_parity(case, c12_mask(case, 32)))
+
+
+def test_repeated_rows_edge_cases(cfg2_case, cfg1_case):
+    s2 = gen.CFG2
+    # no repeated row at all: same bits as the plain layer (same rows, same tables, same kernels)
+    mask = c12_mask(cfg2_case, 32)
+    y_gpu, y_dev, rep, n = hz.gpu_layer_unique_rows(cfg2_case, mask)
+    assert rep.tolist() == list(range(s2.T)) and n == s2.T
+    assert torch.equal(y_dev, hz.gpu_layer(cfg2_case, mask)[1])
+    # every row the same; a single token
+    x = gen.make_x(s2, seed=6)
+    same = cfg2_case.with_x(gen.scaled(s2, T=40), np.repeat(x[:1], 40, axis=0))
+    r = hz.unique_rows_parity(same, mask)
+    assert r["n_unique"] == 1
+    one = cfg2_case.with_x(gen.scaled(s2, T=1), x[:1])
+    assert hz.unique_rows_parity(one, None)["n_unique"] == 1
+    # rows that differ only in the first or only in the last element, and a pair that differs in the sign of a zero
+    x3 = np.repeat(x[:1], 6, axis=0)
+    x3[1, 0] ^= 0x0001
+    x3[2, -1] ^= 0x0001
+    x3[3, 5] = 0x0000
+    x3[4, 5] = 0x8000
+    x3[5, 5] = 0x0000
+    r = hz.unique_rows_parity(cfg2_case.with_x(gen.scaled(s2, T=6), x3), mask)
+    assert r["n_unique"] == 5
+    # float storage (1 KB rows), interleaved repeats
+    s1 = gen.CFG1
+    x1 = gen.make_x(s1, seed=7)
+    x1 = x1[[0, 1, 0, 2, 1, 3, 3, 0]]
+    say("f32 repeats", hz.unique_rows_parity(cfg1_case.with_x(s1, x1), gen.random_mask(s1.E, 6, seed=1)))
+
+
+def test_repeated_rows_at_the_token_limit():
+    """T = 1024 rows drawn from 50 distinct ones (k = 2, small matrices): the search over up to 1023 earlier rows."""
+    s = gen.MoEShape("limits", T=1024, H=256, E=64, k=2, I=128, dtype="bf16")
+    pool = gen.make_x(gen.scaled(s, T=50), seed=8)
+    pick = gen.token_permutation(1024, seed=8) % 50
+    case = hz.Case.make(s, np.ascontiguousarray(pool[pick]), gen.make_weights(s, seed=8))
+    r = hz.unique_rows_parity(case, gen.random_mask(64, 40, seed=8))
+    assert r["n_unique"] == 50
+    say("1024 rows, 50 distinct", r)
