@@ -104,6 +104,42 @@ def as_f32(stored: np.ndarray) -> np.ndarray:
     return bf16_widen(stored) if stored.dtype == np.uint16 else np.asarray(stored, dtype=np.float32)
 
 
+# --------------------------------------------------------------------------- 8-bit weight storage
+def e4m3_values() -> np.ndarray:
+    """The 256 fp32 values of the OCP 8-bit floating-point format E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa
+    bits; exponent field 0 holds the subnormals m/8 * 2^-6; there are no infinities; 0x7f and 0xff are NaN; largest
+    finite magnitude 448), indexed by the code."""
+    code = np.arange(256)
+    e, m = (code >> 3) & 15, code & 7
+    mag = np.where(e == 0, m / 8.0 * 2.0 ** -6, (1.0 + m / 8.0) * 2.0 ** (e.astype(np.float64) - 7))
+    mag = np.where((e == 15) & (m == 7), np.nan, mag)
+    return np.where(code >= 128, -mag, mag).astype(np.float32)
+
+
+def quantize_rows_e4m3(w: np.ndarray):
+    """fp32 matrix [..., R, C] -> (codes uint8 [..., R, C], scale fp32 [..., R]): every row is stored as E4M3 codes times one
+    scale per row.  scale = max|row| / 448 rounded to 8 significant bits (so that code value x scale is exact in fp32; 1 for an
+    all-zero row); code = E4M3 value nearest to w / scale (ties to the even code, magnitudes above 448 saturate)."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    amax = np.abs(w).max(axis=-1)
+    scale = bf16_widen(bf16_round(np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)))
+    v = (w / scale[..., None]).astype(np.float32)
+    pos = e4m3_values()[:127].astype(np.float64)            # codes 0..126 ascending in value
+    a = np.minimum(np.abs(v).astype(np.float64), 448.0)
+    hi = np.clip(np.searchsorted(pos, a, side="left"), 1, 126)
+    lo = hi - 1
+    d_lo, d_hi = a - pos[lo], pos[hi] - a
+    take_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (hi % 2 == 0))
+    code = np.where(take_hi, hi, lo).astype(np.uint8)
+    code = np.where(np.signbit(v), code | np.uint8(0x80), code).astype(np.uint8)
+    return code, scale.astype(np.float32)
+
+
+def dequantize_rows_e4m3(code: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """The fp32 weights that (code, scale) stand for: value of the code times the row's scale (exact in fp32)."""
+    return (e4m3_values()[code] * scale[..., None]).astype(np.float32)
+
+
 # --------------------------------------------------------------------------- hidden states
 def rms_normalise(x: np.ndarray) -> np.ndarray:
     """Unit-gain RMS normalisation of each row, fp32 (the pre-MoE norm of the model; input recipe only)."""

@@ -477,3 +477,39 @@ def test_branch_inputs_have_34_distinct_rows_and_equal_rows_give_equal_outputs()
     w = gen.make_weights(s, seed=3)
     y, idx, gate = orc.moe_layer(gen.as_f32(x), *(gen.as_f32(w[n]) for n in ("router", "gate", "up", "down")), s.k)
     assert np.array_equal(y, y[rep]) and np.array_equal(idx, idx[rep]) and np.array_equal(gate, gate[rep])
+
+
+# ----------------------------------------------------------------------------- 8-bit weight storage (input recipe)
+def test_e4m3_code_values_are_the_ocp_format():
+    """Values fixed by the OCP 8-bit floating point specification (E4M3: bias 7, no infinities, one NaN per sign, max 448)."""
+    v = gen.e4m3_values()
+    known = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x0F: 1.875 * 2.0 ** -6, 0x30: 0.5, 0x38: 1.0, 0x39: 1.125,
+             0x40: 2.0, 0x77: 240.0, 0x78: 256.0, 0x7E: 448.0, 0xB8: -1.0, 0xFE: -448.0}
+    for code, val in known.items():
+        assert v[code] == np.float32(val), hex(code)
+    assert np.isnan(v[0x7F]) and np.isnan(v[0xFF]) and np.isfinite(np.delete(v, [0x7F, 0xFF])).all()
+    assert np.signbit(v[0x80]) and v[0x80] == 0
+    assert np.all(np.diff(v[:127]) > 0) and np.array_equal(v[128:255], -v[:127])
+
+
+def test_e4m3_row_quantisation():
+    v = gen.e4m3_values()
+    # representable rows come back unchanged (scale 1 when the row maximum is 448)
+    row = np.concatenate([v[:127], v[128:255]])[None, :]
+    code, scale = gen.quantize_rows_e4m3(row)
+    assert scale[0] == 1.0 and np.array_equal(gen.dequantize_rows_e4m3(code, scale), row)
+    # nearest value, ties to the even code, saturation is not needed by construction (|w/scale| <= 448 up to the scale's rounding)
+    mid = np.float32([448.0, (v[0x38] + v[0x39]) / 2, (v[0x39] + v[0x3A]) / 2, -(v[0x38] + v[0x39]) / 2, 1.0 + 1.0 / 64])[None, :]
+    code, scale = gen.quantize_rows_e4m3(mid)
+    assert code[0].tolist() == [0x7E, 0x38, 0x3A, 0xB8, 0x38]
+    # random rows: error at most half a step of the format at that magnitude, scale has 8 significant bits, products exact
+    w = gen.normal(3, 1, 0, 0, 64 * 300, 0.02).reshape(64, 300)
+    code, scale = gen.quantize_rows_e4m3(w)
+    deq = gen.dequantize_rows_e4m3(code, scale)
+    assert np.array_equal(gen.bf16_widen(gen.bf16_round(scale)), scale)
+    assert np.array_equal(deq.astype(np.float64), v[code].astype(np.float64) * scale[:, None].astype(np.float64))
+    step = np.maximum(np.abs(w) / scale[:, None], 2.0 ** -6) * 2.0 ** -3 * scale[:, None]     # spacing of the format near |w|
+    assert np.all(np.abs(deq - w) <= 0.5 * step * 1.0001 + 1e-12)
+    zero = np.zeros((2, 16), np.float32)
+    code, scale = gen.quantize_rows_e4m3(zero)
+    assert (code == 0).all() and (scale == 1).all()
