@@ -220,6 +220,31 @@ int team_moe_layer_forward_unique_rows(const team_moe_config* cfg, const void* x
                                        int32_t* row_rep_out /* [T] or NULL */, int32_t* n_unique_out /* [1] or NULL */,
                                        void* workspace, size_t ws_bytes, void* stream);
 
+/*
+ * 8-bit expert weights (a variant outside the paper: it halves the bytes the memory-bound path of Section "Delayed Caching for
+ * Decoded Tokens" / "Speculative Exploration for Hot Tokens (SEH)" has to read).  Storage: w_*_q hold OCP E4M3 codes (1 sign,
+ * 4 exponent bits with bias 7, 3 mantissa bits, no infinities, largest magnitude 448) in the layouts of the bf16 weights
+ * ([E,I,H], [E,I,H], [E,H,I]); scale_gate [E,I], scale_up [E,I], scale_down [E,H] hold one float per matrix row; the weight a
+ * code stands for is (value of the code) x (scale of its row).  x, h, the router weights and y stay as in the bf16 configuration
+ * (cfg->dtype must be TEAM_BF16; hidden 1024 or 2048, inter a multiple of 256); products are formed on bf16 operands (every
+ * E4M3 value is a bf16 value) with float accumulation, and the row scale multiplies the finished sum.
+ *
+ * team_moe_expert_ffn_w8 / team_moe_layer_forward_w8: as team_moe_expert_ffn / team_moe_layer_forward, with these weights.
+ * team_moe_dequantize_w8: out[r, c] = value(codes[r, c]) * scale[r] as float, for a [rows, cols] matrix (cols a multiple of 16;
+ *   codes and out 16-byte aligned) - the conversion the expert FFN applies to its operands, exposed for checking a quantiser.
+ */
+int team_moe_expert_ffn_w8(const team_moe_config* cfg, const void* x, int32_t T, const int32_t* expert_offsets,
+                           const int32_t* sorted_token, const int32_t* active_experts, const int32_t* n_active,
+                           const uint8_t* w_gate_q, const uint8_t* w_up_q, const uint8_t* w_down_q, const float* scale_gate,
+                           const float* scale_up, const float* scale_down, float* expert_out, void* workspace,
+                           size_t ws_bytes, void* stream);
+int team_moe_layer_forward_w8(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router,
+                              const uint8_t* w_gate_q, const uint8_t* w_up_q, const uint8_t* w_down_q,
+                              const float* scale_gate, const float* scale_up, const float* scale_down,
+                              const uint8_t* expert_mask /* [E] or NULL */, void* y, void* workspace, size_t ws_bytes,
+                              void* stream);
+int team_moe_dequantize_w8(const uint8_t* codes, const float* scale, int64_t rows, int64_t cols, float* out, void* stream);
+
 /* Static, NUL-terminated description of a team_status value. */
 const char* team_moe_status_string(int status);
 

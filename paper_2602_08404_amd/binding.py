@@ -20,7 +20,7 @@ STATUS_OK = 0
 EXPORTS = ["team_moe_workspace_size", "team_moe_route", "team_moe_build_dispatch", "team_moe_expert_ffn",
            "team_moe_combine", "team_moe_layer_forward", "team_moe_route_two_round", "team_moe_layer_forward_two_round",
            "team_moe_classify_tokens", "team_moe_layer_forward_rows", "team_moe_layer_forward_unique_rows",
-           "team_moe_status_string"]
+           "team_moe_expert_ffn_w8", "team_moe_layer_forward_w8", "team_moe_dequantize_w8", "team_moe_status_string"]
 
 
 class TeamMoeError(RuntimeError):
@@ -62,6 +62,9 @@ def lib() -> C.CDLL:
         L.team_moe_classify_tokens.argtypes = [vp, vp, i32, i32, vp, i32, C.c_float, i32, vp, vp]
         L.team_moe_layer_forward_rows.argtypes = [cfgp, vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_layer_forward_unique_rows.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.team_moe_expert_ffn_w8.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.team_moe_layer_forward_w8.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.team_moe_dequantize_w8.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, vp]
         L.team_moe_status_string.argtypes = [C.c_int]
         L.team_moe_status_string.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -169,3 +172,26 @@ def team_moe_layer_forward_unique_rows(cfg: Config, x, T: int, w_router, w_gate,
                                                     _ptr(expert_mask), _ptr(y), _ptr(row_rep_out), _ptr(n_unique_out),
                                                     _ptr(workspace), ws_bytes, stream if stream is not None else _stream()),
            "team_moe_layer_forward_unique_rows")
+
+
+def team_moe_expert_ffn_w8(cfg: Config, x, T: int, expert_offsets, sorted_token, active_experts, n_active, w_gate_q, w_up_q, w_down_q,
+                           scale_gate, scale_up, scale_down, expert_out, workspace, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().team_moe_expert_ffn_w8(C.byref(cfg), _ptr(x), T, _ptr(expert_offsets), _ptr(sorted_token), _ptr(active_experts),
+                                        _ptr(n_active), _ptr(w_gate_q), _ptr(w_up_q), _ptr(w_down_q), _ptr(scale_gate), _ptr(scale_up),
+                                        _ptr(scale_down), _ptr(expert_out), _ptr(workspace), ws_bytes,
+                                        stream if stream is not None else _stream()), "team_moe_expert_ffn_w8")
+
+
+def team_moe_layer_forward_w8(cfg: Config, x, T: int, w_router, w_gate_q, w_up_q, w_down_q, scale_gate, scale_up, scale_down,
+                              expert_mask, y, workspace, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().team_moe_layer_forward_w8(C.byref(cfg), _ptr(x), T, _ptr(w_router), _ptr(w_gate_q), _ptr(w_up_q), _ptr(w_down_q),
+                                           _ptr(scale_gate), _ptr(scale_up), _ptr(scale_down), _ptr(expert_mask), _ptr(y),
+                                           _ptr(workspace), ws_bytes, stream if stream is not None else _stream()),
+           "team_moe_layer_forward_w8")
+
+
+def team_moe_dequantize_w8(codes, scale, rows: int, cols: int, out, stream=None) -> None:
+    _check(lib().team_moe_dequantize_w8(_ptr(codes), _ptr(scale), rows, cols, _ptr(out), stream if stream is not None else _stream()),
+           "team_moe_dequantize_w8")

@@ -85,10 +85,11 @@ inline int hip_status(hipError_t e) {
 
 int run_ffn(const team_moe_config* cfg, const Dims& d, const void* x, const int32_t* offsets, const int32_t* sorted_token,
             const int32_t* active, const int32_t* n_active, const void* wg, const void* wu, const void* wd, float* expert_out,
-            void* ctrl, void* h_ws, hipStream_t s) {
+            void* ctrl, void* h_ws, hipStream_t s, const team::W8Scales* w8 = nullptr) {
     if (cfg->dtype == TEAM_BF16)
-        return hip_status(team::launch_ffn_bf16(d, (const uint16_t*)x, offsets, sorted_token, active, n_active, (const uint16_t*)wg,
-                                                (const uint16_t*)wu, (const uint16_t*)wd, ctrl, (uint16_t*)h_ws, expert_out, s));
+        return hip_status(team::launch_ffn_bf16(d, (const uint16_t*)x, offsets, sorted_token, active, n_active, wg, wu, wd, ctrl,
+                                                (uint16_t*)h_ws, expert_out, s, w8));
+    if (w8) return TEAM_ERR_UNSUPPORTED;
     return hip_status(team::launch_ffn_f32(d, (const float*)x, offsets, sorted_token, active, n_active, (const float*)wg,
                                            (const float*)wu, (const float*)wd, (float*)h_ws, expert_out, s));
 }
@@ -145,12 +146,23 @@ int team_moe_build_dispatch(const team_moe_config* cfg, const int32_t* topk_idx,
                                             cz, (hipStream_t)stream));
 }
 
-int team_moe_expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, const int32_t* expert_offsets,
-                        const int32_t* sorted_token, const int32_t* active_experts, const int32_t* n_active, const void* w_gate,
-                        const void* w_up, const void* w_down, float* expert_out, void* workspace, size_t ws_bytes, void* stream) {
+namespace {
+int check_w8(const team_moe_config* cfg, const team::W8Scales& w8) {
+    if (!w8.gate || !w8.up || !w8.down) return TEAM_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(w8.gate) | reinterpret_cast<uintptr_t>(w8.up) | reinterpret_cast<uintptr_t>(w8.down)) & 3u)
+        return TEAM_ERR_INVALID_ARG;
+    if (cfg->dtype != TEAM_BF16 || !team::ffn_w8_supported(cfg->hidden, cfg->inter)) return TEAM_ERR_UNSUPPORTED;
+    return TEAM_OK;
+}
+
+int expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, const int32_t* expert_offsets,
+               const int32_t* sorted_token, const int32_t* active_experts, const int32_t* n_active, const void* w_gate,
+               const void* w_up, const void* w_down, float* expert_out, void* workspace, size_t ws_bytes, void* stream,
+               const team::W8Scales* w8) {
     int st = check_cfg(cfg);
     if (st != TEAM_OK) return st;
     if ((st = check_T(cfg, T)) != TEAM_OK) return st;
+    if (w8 && (st = check_w8(cfg, *w8)) != TEAM_OK) return st;
     if (!x || !expert_offsets || !sorted_token || !active_experts || !n_active || !w_gate || !w_up || !w_down || !expert_out)
         return TEAM_ERR_INVALID_ARG;
     if (!aligned16(x) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) || !aligned16(expert_out))
@@ -159,7 +171,32 @@ int team_moe_expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, co
     if (!workspace || !aligned16(workspace) || ws_bytes < L.logits /* = end of the control block + h segments */) return TEAM_ERR_WORKSPACE;
     clear_stale_error();
     return run_ffn(cfg, dims_of(cfg, T), x, expert_offsets, sorted_token, active_experts, n_active, w_gate, w_up, w_down, expert_out,
-                   (char*)workspace + L.ctrl, (char*)workspace + L.h, (hipStream_t)stream);
+                   (char*)workspace + L.ctrl, (char*)workspace + L.h, (hipStream_t)stream, w8);
+}
+}  // namespace
+
+int team_moe_expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, const int32_t* expert_offsets,
+                        const int32_t* sorted_token, const int32_t* active_experts, const int32_t* n_active, const void* w_gate,
+                        const void* w_up, const void* w_down, float* expert_out, void* workspace, size_t ws_bytes, void* stream) {
+    return expert_ffn(cfg, x, T, expert_offsets, sorted_token, active_experts, n_active, w_gate, w_up, w_down, expert_out, workspace,
+                      ws_bytes, stream, nullptr);
+}
+
+int team_moe_expert_ffn_w8(const team_moe_config* cfg, const void* x, int32_t T, const int32_t* expert_offsets,
+                           const int32_t* sorted_token, const int32_t* active_experts, const int32_t* n_active, const uint8_t* w_gate_q,
+                           const uint8_t* w_up_q, const uint8_t* w_down_q, const float* scale_gate, const float* scale_up,
+                           const float* scale_down, float* expert_out, void* workspace, size_t ws_bytes, void* stream) {
+    const team::W8Scales w8{scale_gate, scale_up, scale_down};
+    return expert_ffn(cfg, x, T, expert_offsets, sorted_token, active_experts, n_active, w_gate_q, w_up_q, w_down_q, expert_out, workspace,
+                      ws_bytes, stream, &w8);
+}
+
+int team_moe_dequantize_w8(const uint8_t* codes, const float* scale, int64_t rows, int64_t cols, float* out, void* stream) {
+    if (!codes || !scale || !out) return TEAM_ERR_INVALID_ARG;
+    if (rows < 1 || cols < 16 || cols % 16 != 0) return TEAM_ERR_INVALID_ARG;
+    if (!aligned16(codes) || !aligned16(out)) return TEAM_ERR_INVALID_ARG;
+    clear_stale_error();
+    return hip_status(team::launch_dequantize_w8(codes, scale, rows, cols, out, (hipStream_t)stream));
 }
 
 int team_moe_combine(const team_moe_config* cfg, const float* expert_out, const float* topk_gate, const int32_t* inv_pos, int32_t T,
@@ -211,10 +248,11 @@ int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const vo
                   const void* w_down, const uint8_t* expert_mask, const uint8_t* token_class, uint8_t* activated_mask_out,
                   int32_t* n_activated_out, void* y, void* workspace, size_t ws_bytes, void* stream,
                   const int32_t* row_index = nullptr, int32_t n_rows = 0, bool unique_rows = false, int32_t* row_rep_out = nullptr,
-                  int32_t* n_unique_out = nullptr) {
+                  int32_t* n_unique_out = nullptr, const team::W8Scales* w8 = nullptr) {
     int st = check_cfg(cfg);
     if (st != TEAM_OK) return st;
     if ((st = check_T(cfg, T)) != TEAM_OK) return st;
+    if (w8 && (st = check_w8(cfg, *w8)) != TEAM_OK) return st;
     if (!x || !w_router || !w_gate || !w_up || !w_down || !y) return TEAM_ERR_INVALID_ARG;
     if (!aligned16(x) || !aligned16(w_router) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) || !aligned16(y))
         return TEAM_ERR_INVALID_ARG;
@@ -263,16 +301,15 @@ int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const vo
         st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, logits, short_path ? cz : none, s, dedup));
     if (st != TEAM_OK) return st;
     if (short_path) {
-        if ((st = hip_status(team::launch_ffn_bf16_from_routing(d, (const uint16_t*)x_ffn, topk_idx, inv_pos, (const uint16_t*)w_gate,
-                                                                (const uint16_t*)w_up, (const uint16_t*)w_down, ws + L.ctrl,
-                                                                (uint16_t*)(ws + L.h), expert_out, s))) != TEAM_OK)
+        if ((st = hip_status(team::launch_ffn_bf16_from_routing(d, (const uint16_t*)x_ffn, topk_idx, inv_pos, w_gate, w_up, w_down,
+                                                                ws + L.ctrl, (uint16_t*)(ws + L.h), expert_out, s, w8))) != TEAM_OK)
             return st;
         return hip_status(team::launch_combine(d, expert_out, topk_gate, inv_pos, y, s));
     }
     if ((st = hip_status(team::launch_dispatch(d, topk_idx, offsets, sorted_token, inv_pos, active, n_active, cz, s))) != TEAM_OK)
         return st;
     if ((st = run_ffn(cfg, d, x_ffn, offsets, sorted_token, active, n_active, w_gate, w_up, w_down, expert_out, ws + L.ctrl,
-                      ws + L.h, s)) != TEAM_OK)
+                      ws + L.h, s, w8)) != TEAM_OK)
         return st;
     return hip_status(team::launch_combine(d, expert_out, topk_gate, inv_pos, y, s));
 }
@@ -309,6 +346,15 @@ int team_moe_layer_forward_unique_rows(const team_moe_config* cfg, const void* x
                                        int32_t* n_unique_out, void* workspace, size_t ws_bytes, void* stream) {
     return layer_forward(cfg, x, T, w_router, w_gate, w_up, w_down, expert_mask, nullptr, nullptr, nullptr, y, workspace, ws_bytes,
                          stream, nullptr, 0, true, row_rep_out, n_unique_out);
+}
+
+int team_moe_layer_forward_w8(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const uint8_t* w_gate_q,
+                              const uint8_t* w_up_q, const uint8_t* w_down_q, const float* scale_gate, const float* scale_up,
+                              const float* scale_down, const uint8_t* expert_mask, void* y, void* workspace, size_t ws_bytes,
+                              void* stream) {
+    const team::W8Scales w8{scale_gate, scale_up, scale_down};
+    return layer_forward(cfg, x, T, w_router, w_gate_q, w_up_q, w_down_q, expert_mask, nullptr, nullptr, nullptr, y, workspace, ws_bytes,
+                         stream, nullptr, 0, false, nullptr, nullptr, &w8);
 }
 
 const char* team_moe_status_string(int status) {

@@ -93,6 +93,26 @@ __device__ __forceinline__ void load4(const float* p, float* out) {      // 4 fl
     out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
 }
 
+// 16 E4M3 codes (as read from LDS) -> two MFMA operands of 8 bf16: codes 0-7 and codes 8-15.  Every E4M3 value is a bf16 value.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ void widen_e4m3(const bf16x8_t& raw, bf16x8_t& first, bf16x8_t& second) {
+    const u32x4_t r = __builtin_bit_cast(u32x4_t, raw);
+    union {
+        bf16x2_t p[4];
+        bf16x8_t v;
+    } a, b;
+    a.p[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r[0], 1.0f, false);
+    a.p[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r[0], 1.0f, true);
+    a.p[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r[1], 1.0f, false);
+    a.p[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r[1], 1.0f, true);
+    b.p[0] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r[2], 1.0f, false);
+    b.p[1] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r[2], 1.0f, true);
+    b.p[2] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r[3], 1.0f, false);
+    b.p[3] = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(r[3], 1.0f, true);
+    first = a.v;
+    second = b.v;
+}
 __device__ __forceinline__ float silu_f32(float z) { return z / (1.0f + expf(-z)); }
 
 // Row of the caller's x / y tensors that holds token t of the call: t itself, or row_index[t] clamped into [0, n_rows).

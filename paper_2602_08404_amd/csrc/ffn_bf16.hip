@@ -34,6 +34,8 @@ bool ffn_bf16_supported(int H, int I) {
     return h_ok && i_ok;
 }
 
+bool ffn_w8_supported(int H, int I) { return (H == 1024 || H == 2048) && I % 256 == 0 && I >= 256 && I <= 1024; }
+
 bool ffn_bf16_groups_itself(const Dims& d) {
     return d.bf16 && d.T <= FFN_LAYER_MAX_TOKENS && d.T * d.k <= FFN_LAYER_MAX_ROWS && d.E <= FFN_MAX_E && ffn_bf16_supported(d.H, d.I);
 }
@@ -47,6 +49,10 @@ static hipError_t launch_common(const Dims& d, FfnArgs& p, hipStream_t s) {
     // across its items; beyond that the kernel decides on the device from the average number of rows per expert.
     p.tiled_min_avg_rows = d.T > 64 ? env_int("TEAM_MOE_FFN_TILED_ROWS", 26) : 0;      // override is a tuning aid only
     p.stream = s;
+    if (p.sg) {                       // 8-bit weights
+        if (!p.su || !p.sd || !ffn_w8_supported(d.H, d.I)) return hipErrorInvalidValue;
+        return d.H == 2048 ? launch_ffn_fused_w8_ksa<16>(p, d.I / 128) : launch_ffn_fused_w8_ksa<8>(p, d.I / 128);
+    }
     switch (d.H / 128) {
         case 2: return launch_ffn_fused_ksa<2>(p, d.I / 128);
         case 4: return launch_ffn_fused_ksa<4>(p, d.I / 128);
@@ -57,10 +63,11 @@ static hipError_t launch_common(const Dims& d, FfnArgs& p, hipStream_t s) {
 }
 
 hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offsets, const int32_t* sorted_token, const int32_t* active,
-                           const int32_t* n_active, const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, void* ctrl,
-                           uint16_t* h_ws, float* expert_out, hipStream_t s) {
+                           const int32_t* n_active, const void* wg, const void* wu, const void* wd, void* ctrl,
+                           uint16_t* h_ws, float* expert_out, hipStream_t s, const W8Scales* w8) {
     if (!ffn_bf16_supported(d.H, d.I) || d.E > FFN_MAX_E) return hipErrorInvalidValue;
     FfnArgs p;
+    if (w8) { p.sg = w8->gate; p.su = w8->up; p.sd = w8->down; }
     p.x = x; p.offsets = offsets; p.sorted_token = sorted_token; p.active = active; p.n_active = n_active;
     p.wg = wg; p.wu = wu; p.wd = wd; p.h = h_ws; p.out = expert_out; p.ctrl = (FfnCtrl*)ctrl;
     p.topk_idx = nullptr; p.inv_pos_out = nullptr;
@@ -68,14 +75,43 @@ hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offs
 }
 
 hipError_t launch_ffn_bf16_from_routing(const Dims& d, const uint16_t* x, const int32_t* topk_idx, int32_t* inv_pos_out,
-                                        const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, void* ctrl, uint16_t* h_ws,
-                                        float* expert_out, hipStream_t s) {
+                                        const void* wg, const void* wu, const void* wd, void* ctrl, uint16_t* h_ws,
+                                        float* expert_out, hipStream_t s, const W8Scales* w8) {
     if (!ffn_bf16_groups_itself(d)) return hipErrorInvalidValue;
     FfnArgs p;
+    if (w8) { p.sg = w8->gate; p.su = w8->up; p.sd = w8->down; }
     p.x = x; p.offsets = nullptr; p.sorted_token = nullptr; p.active = nullptr; p.n_active = nullptr;
     p.wg = wg; p.wu = wu; p.wd = wd; p.h = h_ws; p.out = expert_out; p.ctrl = (FfnCtrl*)ctrl;
     p.topk_idx = topk_idx; p.inv_pos_out = inv_pos_out;
     return launch_common(d, p, s);
+}
+
+// ---- the 8-bit weight format as this library reads it (also what the FFN kernel's operands are widened with)
+__global__ __launch_bounds__(256) void dequantize_w8_kernel(const uint8_t* __restrict__ codes, const float* __restrict__ scale,
+                                                            long long rows, long long cols, float* __restrict__ out) {
+    const long long chunks_per_row = cols / 16;
+    const long long c = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (c >= rows * chunks_per_row) return;
+    const long long row = c / chunks_per_row;
+    const bf16x8_t raw = *reinterpret_cast<const bf16x8_t*>(codes + c * 16);
+    bf16x8_t lo, hi;
+    widen_e4m3(raw, lo, hi);
+    const float sc = scale[row];
+    float* o = out + c * 16;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        o[i] = (float)lo[i] * sc;
+        o[8 + i] = (float)hi[i] * sc;
+    }
+}
+
+hipError_t launch_dequantize_w8(const uint8_t* codes, const float* scale, long long rows, long long cols, float* out, hipStream_t s) {
+    if (rows < 1 || cols < 16 || cols % 16 != 0) return hipErrorInvalidValue;
+    const long long chunks = rows * (cols / 16);
+    const long long blocks = (chunks + 255) / 256;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(dequantize_w8_kernel, dim3((unsigned)blocks), dim3(256), 0, s, codes, scale, rows, cols, out);
+    return hipGetLastError();
 }
 
 }  // namespace team

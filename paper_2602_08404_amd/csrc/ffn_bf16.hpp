@@ -28,9 +28,12 @@ struct FfnArgs {
     const int32_t* sorted_token;
     const int32_t* active;
     const int32_t* n_active;
-    const uint16_t* wg;
-    const uint16_t* wu;
-    const uint16_t* wd;
+    const void* wg;             // bf16 elements, or E4M3 codes when sg / su / sd are given
+    const void* wu;
+    const void* wd;
+    const float* sg = nullptr;  // 8-bit weights: one scale per row of w_gate [E,I], w_up [E,I], w_down [E,H]
+    const float* su = nullptr;
+    const float* sd = nullptr;
     uint16_t* h;
     float* out;
     FfnCtrl* ctrl;
@@ -52,5 +55,10 @@ extern template hipError_t launch_ffn_fused_ksa<2>(const FfnArgs&, int);
 extern template hipError_t launch_ffn_fused_ksa<4>(const FfnArgs&, int);
 extern template hipError_t launch_ffn_fused_ksa<8>(const FfnArgs&, int);
 extern template hipError_t launch_ffn_fused_ksa<16>(const FfnArgs&, int);
+// 8-bit weights (hidden 1024 or 2048; inter a multiple of 256): same dispatch.
+template <int KSA>
+hipError_t launch_ffn_fused_w8_ksa(const FfnArgs& p, int ksb);
+extern template hipError_t launch_ffn_fused_w8_ksa<8>(const FfnArgs&, int);
+extern template hipError_t launch_ffn_fused_w8_ksa<16>(const FfnArgs&, int);
 
 }  // namespace team

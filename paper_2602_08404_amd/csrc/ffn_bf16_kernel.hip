@@ -29,6 +29,11 @@
 // float atomics).  h of a run of gate/up items is kept in LDS and stored in one go when the run is published, because
 // a store between weight loads holds up the in-order load pipeline until it is acknowledged.
 //
+// Weights may also be stored as 8-bit E4M3 codes with one float scale per matrix row (template parameter WB = bytes per
+// weight).  The stream, the LDS layout and the waits are the same with half the bytes; a 16-byte LDS read then carries the
+// operands of two MFMA K-steps, which are widened to bf16 in registers (exactly), the token operand is laid out to match,
+// and the row scales multiply the fp32 sums in the epilogues.
+//
 // Two more things happen in this kernel.  (1) For small calls (at most 64 tokens) started by
 // team_moe_layer_forward, every workgroup groups the routing table itself in LDS during its prologue (the same
 // bitset / popcount / prefix-sum method as the dispatch kernel, which is then not launched).  (2) When a call
@@ -165,6 +170,21 @@ __device__ __forceinline__ void lds_read1(uint32_t a0, bf16x8_t& w0) {
     asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(w0) : "v"(a0) : "memory");
 }
 
+// Row scales are read through the scalar cache (same address in every lane; the tables are never written by the kernel): that
+// path has its own counter, so waiting for a scale does not wait for the weight loads in flight.
+typedef const __attribute__((address_space(4))) float* const_f32_ptr;
+template <int N>
+__device__ __forceinline__ void load_uniform(const float* base_uniform, float (&v)[N]) {
+    const_f32_ptr p = (const_f32_ptr)base_uniform;
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = p[i];
+}
+// v[4*q + j] for a lane-dependent q in 0..3 out of 16 uniform values
+[[maybe_unused]] __device__ __forceinline__ float pick4(const float (&v)[16], int q, int j) {
+    const float lo = q == 0 ? v[j] : v[4 + j], hi = q == 2 ? v[8 + j] : v[12 + j];
+    return q < 2 ? lo : hi;
+}
+
 // A use of every operand register, placed in the branch that has just loaded them: the compiler's wait for those loads then
 // sits in that branch, and not in front of the first matrix instruction of every item, where it would also wait for all the
 // weights in flight.
@@ -183,7 +203,8 @@ __device__ __forceinline__ void settle(bf16x8_t (&opr)[NT][KSM_]) {
 // issued after the stage only make the wait stricter than needed.
 //   PREFETCH : right after stage g has been read, next_stage(g) requests stage g of the next item into the same LDS bytes
 //              (it must issue exactly two slab loads).
-template <class ST, int KS, int RBN, bool PREFETCH, bool TWO, int KSM_, class NextStage>
+//   WB == 1  : KS counts 64-byte units of E4M3 codes; a unit is two K-steps (see widen_e4m3 and the token operand's layout).
+template <class ST, int KS, int RBN, bool PREFETCH, bool TWO, int WB, int KSM_, class NextStage>
 __device__ __forceinline__ void stream_item(uint32_t region, int n, int q, const bf16x8_t (&opr)[NT][KSM_], f32x4_t (&acc)[RBN][NT],
                                             NextStage&& next_stage) {
     constexpr int NST = RBN * ST::S;
@@ -197,11 +218,25 @@ __device__ __forceinline__ void stream_item(uint32_t region, int n, int q, const
         if (second) lds_read2(base + ST::read_off(n, st, 0, q), base + ST::read_off(n, st, 1, q), w0, w1);
         else lds_read1(base + ST::read_off(n, st, 0, q), w0);
         if (PREFETCH) next_stage(g);
-        acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, opr[0][2 * st], acc[rb][0], 0, 0, 0);
-        if (TWO) acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, opr[1][2 * st], acc[rb][1], 0, 0, 0);
-        if (second) {
-            acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, opr[0][2 * st + 1], acc[rb][0], 0, 0, 0);
-            if (TWO) acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, opr[1][2 * st + 1], acc[rb][1], 0, 0, 0);
+        if constexpr (WB == 2) {
+            acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, opr[0][2 * st], acc[rb][0], 0, 0, 0);
+            if (TWO) acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, opr[1][2 * st], acc[rb][1], 0, 0, 0);
+            if (second) {
+                acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, opr[0][2 * st + 1], acc[rb][0], 0, 0, 0);
+                if (TWO) acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, opr[1][2 * st + 1], acc[rb][1], 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                if (u == 1 && !second) break;
+                bf16x8_t wa, wb;
+                widen_e4m3(u == 0 ? w0 : w1, wa, wb);
+                const int s0 = 4 * st + 2 * u;                 // K-steps of unit 2*st + u
+                acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, opr[0][s0], acc[rb][0], 0, 0, 0);
+                if (TWO) acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, opr[1][s0], acc[rb][1], 0, 0, 0);
+                acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, opr[0][s0 + 1], acc[rb][0], 0, 0, 0);
+                if (TWO) acc[rb][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, opr[1][s0 + 1], acc[rb][1], 0, 0, 0);
+            }
         }
     }
 }
@@ -209,24 +244,28 @@ __device__ __forceinline__ void stream_item(uint32_t region, int n, int q, const
 }  // namespace
 
 // KSA = H / 128 and KSB = I / 128: MFMA K-steps (of 32) per wavefront in the two GEMMs; RB = 16-row sub-tiles
-// of w_down per down item.
-template <int KSA, int KSB, int RB>
+// of w_down per down item; WB = bytes per weight (2: bf16; 1: E4M3 codes with the row scales sg, su, sd).
+template <int KSA, int KSB, int RB, int WB>
 __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_t* __restrict__ x, const int32_t* __restrict__ offsets,
                                                                    const int32_t* __restrict__ sorted_token,
                                                                    const int32_t* __restrict__ active, const int32_t* __restrict__ n_active,
-                                                                   const uint16_t* __restrict__ wg, const uint16_t* __restrict__ wu,
-                                                                   const uint16_t* __restrict__ wd, uint16_t* __restrict__ h,
+                                                                   const unsigned char* __restrict__ wg, const unsigned char* __restrict__ wu,
+                                                                   const unsigned char* __restrict__ wd, uint16_t* __restrict__ h,
                                                                    float* __restrict__ out, FfnCtrl* __restrict__ ctrl, int T, int k, int E,
                                                                    int spin_limit, int tiled_min_avg_rows,
-                                                                   const int32_t* __restrict__ topk_idx, int32_t* __restrict__ inv_pos_out) {
-    using SA = Staged<KSA>;
-    using SB = Staged<KSB>;
+                                                                   const int32_t* __restrict__ topk_idx, int32_t* __restrict__ inv_pos_out,
+                                                                   const float* __restrict__ sg, const float* __restrict__ su,
+                                                                   const float* __restrict__ sd) {
+    static_assert(WB == 2 || (WB == 1 && KSA % 2 == 0 && KSB % 2 == 0), "8-bit weights: whole 64-byte units per wavefront");
+    constexpr int UA = KSA * WB / 2, UB = KSB * WB / 2;           // 64-byte units of a weight row per wavefront
+    using SA = Staged<UA>;
+    using SB = Staged<UB>;
     constexpr int H = KSA * 128, I = KSB * 128;
     constexpr int KSLICE_A = KSA * 32, KSLICE_B = KSB * 32;       // columns per wavefront
     constexpr int KSM = cmax(KSA, KSB);
     constexpr int W_A = FFN_WAVES * SA::BYTES, W_B = FFN_WAVES * RB * SB::BYTES;
     constexpr int RED_A = FFN_WAVES * NT * WAVE * 16, RED_B = FFN_WAVES * RB * NT * WAVE * 16;
-    constexpr int LDS_BYTES = cmax(cmax(W_A + RED_A, W_B + RED_B), tiled::RING_BYTES);   // the streaming variant reuses s_mem
+    constexpr int LDS_BYTES = cmax(cmax(W_A + RED_A, W_B + RED_B), WB == 2 ? tiled::RING_BYTES : 0);   // the streaming variant reuses s_mem
     constexpr int TILES_A = I / 8, TILES_B = H / (16 * RB);
     __shared__ __attribute__((aligned(1024))) char s_mem[LDS_BYTES];
     __shared__ int32_t s_slot_e[FFN_MAX_E];
@@ -321,15 +360,15 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         }
         __syncthreads();                                        // s_mem is handed to the weight stream from here on
     }
-    if (tiled_min_avg_rows > 0) {
+    if (WB == 2 && tiled_min_avg_rows > 0) {
         // Many rows per expert on average: the register-resident token operand below would have to be re-gathered for
         // every item; stream both operands through LDS instead.  The decision depends on the tables only, so every
         // workgroup of the launch takes the same branch.
         __syncthreads();
         const int total_rows = s_off[E];
         if (n_act > 0 && (long long)total_rows >= (long long)tiled_min_avg_rows * n_act) {
-            tiled::ffn_tiled_body<tiled::RING_STAGES>(s_mem, s_slot_e, s_off, n_act, x, sorted_token, wg, wu, wd, h, out, ctrl, T, E, H, I,
-                                                      spin_limit);
+            tiled::ffn_tiled_body<tiled::RING_STAGES>(s_mem, s_slot_e, s_off, n_act, x, sorted_token, (const uint16_t*)wg, (const uint16_t*)wu,
+                                                      (const uint16_t*)wd, h, out, ctrl, T, E, H, I, spin_limit);
             return;
         }
     }
@@ -364,6 +403,11 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         }
         return tok >= T ? -1 : tok;
     };
+    // First column (relative to the lane's base column) of the 8 token elements that meet the weights of K-step s.
+    // bf16 weights: lane q of K-step s holds weight columns 32 s + 8 q .. + 7.  E4M3 weights: a lane's 16-byte LDS read holds
+    // columns 64 j + 16 q .. + 15 of unit j, used as K-steps 2 j (first 8) and 2 j + 1 (last 8); any assignment of columns
+    // to K-steps is a valid order of the sum as long as both operands use the same one.
+    auto kstep_col = [](int s) { return WB == 2 ? s * 32 : (s >> 1) * 64 + (s & 1) * 8; };
     auto item_at = [&](int step) {
         Item t;
         t.is_a = step < n_a;
@@ -386,9 +430,9 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         for (int half = 0; half < 2; ++half) {
             const int r = SA::slab_row(half, ln), c = SA::slab_chunk(g, half, ln);
             // MFMA row r = 4*qq + j2: j2 in {0,1} -> gate rows, {2,3} -> up rows of intermediate index 2*qq + (j2 & 1)
-            const uint16_t* mat = (r & 2) ? wu : wg;
+            const unsigned char* mat = (r & 2) ? wu : wg;
             const int irow = t.it * 8 + 2 * (r >> 2) + (r & 1);
-            if (SA::C % 8 == 0 || c < SA::C) slab_load(mat + (ebase + irow) * H + wave * KSLICE_A + c * 8, dst + half * 1024);
+            if (SA::C % 8 == 0 || c < SA::C) slab_load(mat + ((ebase + irow) * H + wave * KSLICE_A) * WB + c * 16, dst + half * 1024);
         }
     };
     auto issue_stage_b = [&](const Item& t, int g) {
@@ -399,7 +443,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             const int r = SB::slab_row(half, ln), c = SB::slab_chunk(st, half, ln);
-            if (SB::C % 8 == 0 || c < SB::C) slab_load(wd + (ebase + r) * I + wave * KSLICE_B + c * 8, dst + half * 1024);
+            if (SB::C % 8 == 0 || c < SB::C) slab_load(wd + ((ebase + r) * I + wave * KSLICE_B) * WB + c * 16, dst + half * 1024);
         }
     };
     // All stages of an item at once (nothing of it has been requested yet).
@@ -435,6 +479,13 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
             const uint32_t region = tiled::lds_addr(s_mem + wave * SA::BYTES);
             // Items of one slot are published together after the last of them; that one waits for its h stores.
             const bool publish_now = step + 1 >= n_a || (li + 1) / TILES_A != a;
+            float sc_g[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f}, sc_u[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
+            if constexpr (WB == 1) {     // scales of this item's 8 gate rows and 8 up rows (requested now, needed in the epilogue)
+                if (m > 0) {
+                    load_uniform(sg + (size_t)cur.e * I + it * 8, sc_g);
+                    load_uniform(su + (size_t)cur.e * I + it * 8, sc_u);
+                }
+            }
             for (int ch = 0; ch < chunks; ++ch) {
                 const int row_base = ch * 16 * NT;
                 const bool last_chunk = ch + 1 == chunks;
@@ -442,10 +493,10 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
 #pragma unroll
                     for (int nt = 0; nt < NT; ++nt) {
                         const int tok = token_of_row(r0, m, row_base + nt * 16 + n);
-                        const uint16_t* xp = x + (size_t)(tok < 0 ? 0 : tok) * H + wave * KSLICE_A + q * 8;
+                        const uint16_t* xp = x + (size_t)(tok < 0 ? 0 : tok) * H + wave * KSLICE_A + q * (16 / WB);
                         if (tok >= 0) {
 #pragma unroll
-                            for (int s = 0; s < KSA; ++s) opr[nt][s] = *reinterpret_cast<const bf16x8_t*>(xp + s * 32);
+                            for (int s = 0; s < KSA; ++s) opr[nt][s] = *reinterpret_cast<const bf16x8_t*>(xp + kstep_col(s));
                         } else {
 #pragma unroll
                             for (int s = 0; s < KSA; ++s) opr[nt][s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
@@ -461,12 +512,12 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                 const bool prefetch = last_chunk && has_next && !publish_now && nxt.m > 0;
                 auto next_stage = [&](int g) { issue_stage_a(nxt, g); };
                 if (prefetch) {
-                    if (two) stream_item<SA, KSA, 1, true, true, KSM>(region, n, q, opr, acc, next_stage);
-                    else stream_item<SA, KSA, 1, true, false, KSM>(region, n, q, opr, acc, next_stage);
+                    if (two) stream_item<SA, UA, 1, true, true, WB, KSM>(region, n, q, opr, acc, next_stage);
+                    else stream_item<SA, UA, 1, true, false, WB, KSM>(region, n, q, opr, acc, next_stage);
                     ahead = true;
                 } else {
-                    if (two) stream_item<SA, KSA, 1, false, true, KSM>(region, n, q, opr, acc, next_stage);
-                    else stream_item<SA, KSA, 1, false, false, KSM>(region, n, q, opr, acc, next_stage);
+                    if (two) stream_item<SA, UA, 1, false, true, WB, KSM>(region, n, q, opr, acc, next_stage);
+                    else stream_item<SA, UA, 1, false, false, WB, KSM>(region, n, q, opr, acc, next_stage);
                 }
                 settle_accumulators(acc[0]);
                 lds_write_f4(red_base + ((wave * NT + 0) * WAVE + ln) * 16, acc[0][0]);
@@ -479,6 +530,13 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                     for (int w = 1; w < FFN_WAVES; ++w) v += lds_read_f4(red_base + ((w * NT + wave) * WAVE + ln) * 16);
                     const int row = row_base + wave * 16 + n;
                     // lane holds (g_a, g_b, u_a, u_b) of intermediate indices it*8 + 2*q, +1 for token row `row`
+                    if constexpr (WB == 1) {
+                        const float g0 = q == 0 ? sc_g[0] : q == 1 ? sc_g[2] : q == 2 ? sc_g[4] : sc_g[6];
+                        const float g1 = q == 0 ? sc_g[1] : q == 1 ? sc_g[3] : q == 2 ? sc_g[5] : sc_g[7];
+                        const float u0 = q == 0 ? sc_u[0] : q == 1 ? sc_u[2] : q == 2 ? sc_u[4] : sc_u[6];
+                        const float u1 = q == 0 ? sc_u[1] : q == 1 ? sc_u[3] : q == 2 ? sc_u[5] : sc_u[7];
+                        v[0] *= g0; v[1] *= g1; v[2] *= u0; v[3] *= u1;
+                    }
                     const float h0 = silu_f32(v[0]) * v[2];
                     const float h1 = silu_f32(v[1]) * v[3];
                     const uint32_t packed = f32_to_bf16_bits(h0) | (f32_to_bf16_bits(h1) << 16);
@@ -515,6 +573,10 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         } else {
             // =============================================================== down item
             const uint32_t region = tiled::lds_addr(s_mem + wave * (RB * SB::BYTES));
+            float sc_d[16] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
+            if constexpr (WB == 1) {     // scales of the 16 output rows this wavefront finishes (pair = wave: sub-tile wave / NT)
+                if (m > 0 && wave < RB * NT) load_uniform(sd + (size_t)cur.e * H + it * 16 * RB + (wave / NT) * 16, sc_d);
+            }
             if (a != ready_slot) {       // wait until every gate/up item of this expert has published h
                 if (tid == 0) {
                     int spins = 0;
@@ -537,10 +599,10 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                     for (int nt = 0; nt < NT; ++nt) {
                         const int row = row_base + nt * 16 + n;
                         const bool valid = token_of_row(r0, m, row) >= 0;
-                        const uint16_t* hp = h + (size_t)(valid ? r0 + row : 0) * I + wave * KSLICE_B + q * 8;
+                        const uint16_t* hp = h + (size_t)(valid ? r0 + row : 0) * I + wave * KSLICE_B + q * (16 / WB);
                         if (valid) {
 #pragma unroll
-                            for (int s = 0; s < KSB; ++s) opr[nt][s] = load_coherent_16(hp + s * 32);
+                            for (int s = 0; s < KSB; ++s) opr[nt][s] = load_coherent_16(hp + kstep_col(s));
                         } else {
 #pragma unroll
                             for (int s = 0; s < KSB; ++s) opr[nt][s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
@@ -558,12 +620,12 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                 const bool prefetch = last_chunk && has_next && nxt.m > 0;     // the next item is a down item too
                 auto next_stage = [&](int g) { issue_stage_b(nxt, g); };
                 if (prefetch) {
-                    if (two) stream_item<SB, KSB, RB, true, true, KSM>(region, n, q, opr, acc, next_stage);
-                    else stream_item<SB, KSB, RB, true, false, KSM>(region, n, q, opr, acc, next_stage);
+                    if (two) stream_item<SB, UB, RB, true, true, WB, KSM>(region, n, q, opr, acc, next_stage);
+                    else stream_item<SB, UB, RB, true, false, WB, KSM>(region, n, q, opr, acc, next_stage);
                     ahead = true;
                 } else {
-                    if (two) stream_item<SB, KSB, RB, false, true, KSM>(region, n, q, opr, acc, next_stage);
-                    else stream_item<SB, KSB, RB, false, false, KSM>(region, n, q, opr, acc, next_stage);
+                    if (two) stream_item<SB, UB, RB, false, true, WB, KSM>(region, n, q, opr, acc, next_stage);
+                    else stream_item<SB, UB, RB, false, false, WB, KSM>(region, n, q, opr, acc, next_stage);
                 }
                 settle_accumulators(reinterpret_cast<f32x4_t(&)[RB * NT]>(acc));
 #pragma unroll
@@ -580,6 +642,9 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
 #pragma unroll
                         for (int w = 1; w < FFN_WAVES; ++w) v += lds_read_f4(redb_base + (((w * RB + rb) * NT + nt) * WAVE + ln) * 16);
                         // lane holds output rows it*16*RB + rb*16 + 4*q + (0..3) of token row `row`
+                        if constexpr (WB == 1) {
+                            v[0] *= pick4(sc_d, q, 0); v[1] *= pick4(sc_d, q, 1); v[2] *= pick4(sc_d, q, 2); v[3] *= pick4(sc_d, q, 3);
+                        }
                         *reinterpret_cast<f32x4_t*>(out + (size_t)(r0 + row) * H + it * 16 * RB + rb * 16 + 4 * q) = v;
                     }
                 }
@@ -593,42 +658,56 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
 
 // The kernel's waits need every workgroup of the grid to be resident at once, so the grid is what the runtime
 // says fits: (workgroups per compute unit for this instantiation) x (compute units), never more.
-template <int KSA, int KSB>
+template <int KSA, int KSB, int WB>
 hipError_t launch_ffn_fused(const FfnArgs& p) {
     constexpr int RB = KSB <= 6 ? 2 : 1;      // two sub-tiles per down item while the partial sums fit the register budget
     static int resident = 0;         // per instantiation; same value for every caller, so a benign race
     if (resident == 0) {
         int per_cu = 0;
-        hipError_t err = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, ffn_fused_kernel<KSA, KSB, RB>, FFN_THREADS, 0);
+        hipError_t err = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, ffn_fused_kernel<KSA, KSB, RB, WB>, FFN_THREADS, 0);
         if (err != hipSuccess) return err;
         if (per_cu < 1) return hipErrorLaunchOutOfResources;
         resident = per_cu * p.n_cu;
     }
     const int grid = p.grid_override > 0 && p.grid_override < resident ? p.grid_override : resident;
-    hipLaunchKernelGGL((ffn_fused_kernel<KSA, KSB, RB>), dim3(grid), dim3(FFN_THREADS), 0, p.stream, p.x, p.offsets, p.sorted_token,
-                       p.active, p.n_active, p.wg, p.wu, p.wd, p.h, p.out, p.ctrl, p.T, p.k, p.E, p.spin_limit,
-                       p.tiled_min_avg_rows, p.topk_idx, p.inv_pos_out);
+    hipLaunchKernelGGL((ffn_fused_kernel<KSA, KSB, RB, WB>), dim3(grid), dim3(FFN_THREADS), 0, p.stream, p.x, p.offsets, p.sorted_token,
+                       p.active, p.n_active, (const unsigned char*)p.wg, (const unsigned char*)p.wu, (const unsigned char*)p.wd, p.h, p.out,
+                       p.ctrl, p.T, p.k, p.E, p.spin_limit, WB == 2 ? p.tiled_min_avg_rows : 0, p.topk_idx, p.inv_pos_out, p.sg, p.su,
+                       p.sd);
     return hipGetLastError();
 }
 
+#ifndef FFN_KSA_THIS_FILE
+#error "compile with -DFFN_KSA_THIS_FILE=<hidden/128> (and -DFFN_W8_THIS_FILE for the 8-bit weight kernels of that hidden size)"
+#endif
+#ifndef FFN_W8_THIS_FILE
 template <int KSA>
 hipError_t launch_ffn_fused_ksa(const FfnArgs& p, int ksb) {
     switch (ksb) {
-        case 1: return launch_ffn_fused<KSA, 1>(p);
-        case 2: return launch_ffn_fused<KSA, 2>(p);
-        case 3: return launch_ffn_fused<KSA, 3>(p);
-        case 4: return launch_ffn_fused<KSA, 4>(p);
-        case 5: return launch_ffn_fused<KSA, 5>(p);
-        case 6: return launch_ffn_fused<KSA, 6>(p);
-        case 7: return launch_ffn_fused<KSA, 7>(p);
-        case 8: return launch_ffn_fused<KSA, 8>(p);
+        case 1: return launch_ffn_fused<KSA, 1, 2>(p);
+        case 2: return launch_ffn_fused<KSA, 2, 2>(p);
+        case 3: return launch_ffn_fused<KSA, 3, 2>(p);
+        case 4: return launch_ffn_fused<KSA, 4, 2>(p);
+        case 5: return launch_ffn_fused<KSA, 5, 2>(p);
+        case 6: return launch_ffn_fused<KSA, 6, 2>(p);
+        case 7: return launch_ffn_fused<KSA, 7, 2>(p);
+        case 8: return launch_ffn_fused<KSA, 8, 2>(p);
         default: return hipErrorInvalidValue;
     }
 }
-
-#ifndef FFN_KSA_THIS_FILE
-#error "compile with -DFFN_KSA_THIS_FILE=<hidden/128>"
-#endif
 template hipError_t launch_ffn_fused_ksa<FFN_KSA_THIS_FILE>(const FfnArgs& p, int ksb);
+#else
+template <int KSA>
+hipError_t launch_ffn_fused_w8_ksa(const FfnArgs& p, int ksb) {
+    switch (ksb) {
+        case 2: return launch_ffn_fused<KSA, 2, 1>(p);
+        case 4: return launch_ffn_fused<KSA, 4, 1>(p);
+        case 6: return launch_ffn_fused<KSA, 6, 1>(p);
+        case 8: return launch_ffn_fused<KSA, 8, 1>(p);
+        default: return hipErrorInvalidValue;
+    }
+}
+template hipError_t launch_ffn_fused_w8_ksa<FFN_KSA_THIS_FILE>(const FfnArgs& p, int ksb);
+#endif
 
 }  // namespace team

@@ -63,17 +63,26 @@ hipError_t launch_ffn_f32(const Dims& d, const float* x, const int32_t* offsets,
 // bf16 storage: MFMA grouped FFN streaming the weights of the active experts.
 // ctrl: ffn_ctrl_bytes() of scratch for the kernel's per-expert counters; the words ffn_ctrl_zero() names must be
 // zero when the kernel starts (the dispatch kernel clears them).
+// 8-bit weights: E4M3 codes in the same [E,I,H] / [E,H,I] layouts plus one float scale per matrix row (w = code value x scale).
+struct W8Scales {
+    const float* gate;   // [E,I]
+    const float* up;     // [E,I]
+    const float* down;   // [E,H]
+};
+bool ffn_w8_supported(int H, int I);
+// codes [rows, cols] (cols a multiple of 16), scale [rows] -> out [rows, cols] floats; the conversion the FFN kernel uses.
+hipError_t launch_dequantize_w8(const uint8_t* codes, const float* scale, long long rows, long long cols, float* out, hipStream_t s);
 bool ffn_bf16_supported(int H, int I);
 size_t ffn_ctrl_bytes();
 CtrlZero ffn_ctrl_zero(void* ctrl);
 hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offsets, const int32_t* sorted_token,
-                           const int32_t* active, const int32_t* n_active, const uint16_t* wg, const uint16_t* wu,
-                           const uint16_t* wd, void* ctrl, uint16_t* h_ws, float* expert_out, hipStream_t s);
+                           const int32_t* active, const int32_t* n_active, const void* wg, const void* wu,
+                           const void* wd, void* ctrl, uint16_t* h_ws, float* expert_out, hipStream_t s, const W8Scales* w8 = nullptr);
 // Whole-layer form for small calls: the FFN kernel groups the routing table (topk_idx) itself and writes inv_pos for
 // the combine kernel; no dispatch kernel is needed.  ffn_bf16_groups_itself says whether a call qualifies.
 bool ffn_bf16_groups_itself(const Dims& d);
 hipError_t launch_ffn_bf16_from_routing(const Dims& d, const uint16_t* x, const int32_t* topk_idx, int32_t* inv_pos_out,
-                                        const uint16_t* wg, const uint16_t* wu, const uint16_t* wd, void* ctrl, uint16_t* h_ws,
-                                        float* expert_out, hipStream_t s);
+                                        const void* wg, const void* wu, const void* wd, void* ctrl, uint16_t* h_ws,
+                                        float* expert_out, hipStream_t s, const W8Scales* w8 = nullptr);
 
 }  // namespace team

@@ -204,6 +204,82 @@ def gpu_layer_unique_rows(case: Case, mask: Optional[np.ndarray], want_tables=Tr
     return y_to_host(y), y, rep.cpu().numpy(), int(n_unique.cpu().numpy()[0])
 
 
+# ----------------------------------------------------------------------------- 8-bit weights
+@dataclass
+class W8:
+    """Expert weights of a Case re-stored as E4M3 codes with row scales; `case` carries the exactly dequantised weights
+    for the oracle (and the bf16 router), `q` / `scale` are the device tensors the library reads."""
+    case: Case
+    q: Dict[str, torch.Tensor]
+    scale: Dict[str, torch.Tensor]
+
+    @staticmethod
+    def make(base: Case) -> "W8":
+        q, scale, wf = {}, {}, {"router": base.wf["router"]}
+        for n in ("gate", "up", "down"):
+            code, sc = gen.quantize_rows_e4m3(base.wf[n])
+            wf[n] = gen.dequantize_rows_e4m3(code, sc)
+            q[n] = torch.from_numpy(code).to(DEV)
+            scale[n] = torch.from_numpy(sc).to(DEV)
+        case = Case(base.shape, base.x, base.w, base.xf, wf, base.d_x, base.d_w, base.cfg)
+        return W8(case, q, scale)
+
+    def with_x(self, shape: gen.MoEShape, x: np.ndarray) -> "W8":
+        c = self.case
+        cfg = tm.make_config(shape.H, shape.I, shape.E, shape.k, shape.dtype, shape.renormalize, shape.T)
+        return W8(Case(shape, x, c.w, gen.as_f32(x), c.wf, to_dev(x), c.d_w, cfg), self.q, self.scale)
+
+
+def gpu_layer_w8(w8: W8, mask: Optional[np.ndarray], ws=None):
+    c, s = w8.case, w8.case.shape
+    if ws is None:
+        ws = torch.empty(tm.team_moe_workspace_size(c.cfg), dtype=torch.uint8, device=DEV)
+    y = torch.empty((s.T, s.H), dtype=out_dtype(s), device=DEV)
+    d_mask = None if mask is None else torch.from_numpy(mask).to(DEV)
+    tm.team_moe_layer_forward_w8(c.cfg, c.d_x, s.T, c.d_w["router"], w8.q["gate"], w8.q["up"], w8.q["down"], w8.scale["gate"],
+                                 w8.scale["up"], w8.scale["down"], d_mask, y, ws)
+    torch.cuda.synchronize()
+    return y_to_host(y), y
+
+
+def gpu_expert_ffn_w8(w8: W8, offsets, sorted_token, active, n_active):
+    c, s = w8.case, w8.case.shape
+    A = s.T * s.k
+    ws = torch.empty(tm.team_moe_workspace_size(c.cfg), dtype=torch.uint8, device=DEV)
+    out = torch.full((A, s.H), float("nan"), dtype=torch.float32, device=DEV)
+    scratch = [torch.empty(n, dtype=torch.int32, device=DEV) for n in (s.E + 1, A, A, s.E, 1)]
+    tm.team_moe_build_dispatch(c.cfg, torch.full((s.T, s.k), -1, dtype=torch.int32, device=DEV), s.T, *scratch, workspace=ws)
+    tm.team_moe_expert_ffn_w8(c.cfg, c.d_x, s.T, torch.from_numpy(offsets).to(DEV), torch.from_numpy(sorted_token).to(DEV),
+                              torch.from_numpy(active).to(DEV), torch.tensor([n_active], dtype=torch.int32, device=DEV),
+                              w8.q["gate"], w8.q["up"], w8.q["down"], w8.scale["gate"], w8.scale["up"], w8.scale["down"], out, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def w8_parity(w8: W8, mask, threads=0):
+    """The expert FFN and the whole layer on E4M3 weights against the oracle's plain layer on the exactly dequantised
+    weights (same bars as for bf16 weights: the weights are inputs, the arithmetic is the same)."""
+    c, s = w8.case, w8.case.shape
+    tol = TOL[s.dtype]
+    o_y, o_idx, o_gate = oracle_layer(c, mask, threads)
+    o_logits = oracle_logits(c)
+    g_idx, g_gate, _ = gpu_route(c, mask)
+    set_safe, _ = safe_tokens(o_logits, mask, s.k)
+    offsets, sorted_token, inv_pos, active, n_active = orc.dispatch(o_idx, s.E)
+    g_out = gpu_expert_ffn_w8(w8, offsets, sorted_token, active, n_active)
+    o_rows = orc.expert_rows(c.xf, c.wf["gate"], c.wf["up"], c.wf["down"], o_idx, threads)
+    valid = inv_pos >= 0
+    ref_out = np.zeros((s.T * s.k, s.H))
+    ref_out[inv_pos[valid]] = o_rows[valid]
+    n_rows = int(offsets[s.E])
+    ffn_err = row_rel_err(g_out[:n_rows].astype(np.float64), ref_out[:n_rows]).max() if n_rows else 0.0
+    assert ffn_err <= tol, ffn_err
+    assert np.isnan(g_out[n_rows:]).all()
+    y_gpu, _ = gpu_layer_w8(w8, mask)
+    layer_err, n_band = check_layer(c, mask, y_gpu, g_idx, g_gate, o_y, o_idx, set_safe)
+    return {"ffn_err": float(ffn_err), "layer_err": layer_err, "band_tokens": n_band, "n_active": n_active}
+
+
 # ----------------------------------------------------------------------------- oracle side
 def oracle_layer(case: Case, mask, threads=0):
     s = case.shape

@@ -458,3 +458,83 @@ def test_repeated_rows_at_the_token_limit():
     r = hz.unique_rows_parity(case, gen.random_mask(64, 40, seed=8))
     assert r["n_unique"] == 50
     say("1024 rows, 50 distinct", r)
+
+
+# ----------------------------------------------------------------------------- 8-bit expert weights (E4M3 codes, one scale per row)
+def test_w8_conversion_is_the_e4m3_format():
+    """Every code at every position of a 16-byte group, through the conversion the expert FFN uses: value x row scale."""
+    codes = np.stack([np.roll(np.arange(256, dtype=np.uint8), r) for r in range(16)])
+    scale = (2.0 ** np.arange(-8, 8)).astype(np.float32) * np.float32(1.25)
+    out = torch.full((16, 256), 7.0, dtype=torch.float32, device=hz.DEV)
+    tm.team_moe_dequantize_w8(torch.from_numpy(codes).to(hz.DEV), torch.from_numpy(scale).to(hz.DEV), 16, 256, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want = gen.dequantize_rows_e4m3(codes, scale)
+    nan = np.isnan(want)
+    assert nan.sum() == 32 and np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))       # bit for bit, signed zeros included
+
+
+@pytest.fixture(scope="module")
+def cfg2_w8(cfg2_case):
+    say("quantising cfg2 weights")
+    return hz.W8.make(cfg2_case)
+
+
+@pytest.mark.parametrize("M", [128, 32, 16])
+def test_w8_cfg2_activated_sets(cfg2_w8, M):
+    mask = None if M == 128 else c12_mask(cfg2_w8.case, M)
+    say("w8 cfg2 M", M, hz.w8_parity(cfg2_w8, mask))
+
+
+def test_w8_cfg2_ragged_degenerate_and_repeatable(cfg2_w8):
+    s = gen.scaled(gen.CFG2, T=17)
+    w = cfg2_w8.with_x(s, gen.make_x(s, seed=5))
+    say("w8 T=17", hz.w8_parity(w, c12_mask(w.case, 24)))
+    one = np.zeros(gen.CFG2.E, np.uint8)
+    one[5] = 1
+    say("w8 single expert (32 rows)", hz.w8_parity(cfg2_w8, one))
+    y, _ = hz.gpu_layer_w8(cfg2_w8, np.zeros(gen.CFG2.E, np.uint8))
+    assert (y == 0).all()
+    mask = c12_mask(cfg2_w8.case, 24)
+    ws = torch.empty(tm.team_moe_workspace_size(cfg2_w8.case.cfg), dtype=torch.uint8, device=hz.DEV)
+    _, first = hz.gpu_layer_w8(cfg2_w8, mask, ws)
+    for i in range(20):
+        _, again = hz.gpu_layer_w8(cfg2_w8, mask, ws)
+        assert torch.equal(first, again), i
+
+
+def test_w8_cfg3_many_rows_per_expert(cfg2_w8):
+    """128 tokens over 32 experts: experts with more than 32 rows take several passes over their rows."""
+    s = gen.CFG3
+    w = cfg2_w8.with_x(s, gen.make_x(s, seed=0, kind="candidates", noise_std=0.1))
+    say("w8 cfg3", hz.w8_parity(w, c12_mask(w.case, 32)))
+
+
+@pytest.mark.parametrize("H,I,E,k,T", [(1024, 256, 16, 2, 9), (1024, 1024, 16, 3, 70), (2048, 512, 48, 8, 160), (2048, 1024, 24, 4, 33)])
+def test_w8_other_shapes(H, I, E, k, T):
+    """Every supported (hidden, inter) block count; T*k = 1280 routed rows in the third case (token list in global memory)."""
+    s = gen.MoEShape("w8other", T=T, H=H, E=E, k=k, I=I, dtype="bf16")
+    base = hz.Case.make(s, gen.make_x(s, seed=9), gen.make_weights(s, seed=9))
+    say("w8 shape", (H, I, E, k, T), hz.w8_parity(hz.W8.make(base), gen.random_mask(E, max(k, (3 * E) // 4), seed=9)))
+
+
+def test_w8_rejects_unsupported_configurations(cfg1_case, cfg2_w8):
+    c = cfg2_w8.case
+    q, sc = cfg2_w8.q, cfg2_w8.scale
+    y = torch.empty((32, 2048), dtype=torch.bfloat16, device=hz.DEV)
+    ws = torch.empty(tm.team_moe_workspace_size(c.cfg), dtype=torch.uint8, device=hz.DEV)
+
+    def call(cfg, scale_up=sc["up"]):
+        tm.team_moe_layer_forward_w8(cfg, c.d_x, 32, c.d_w["router"], q["gate"], q["up"], q["down"], sc["gate"], scale_up, sc["down"],
+                                     None, y, ws)
+
+    with pytest.raises(tm.TeamMoeError) as e:
+        call(c.cfg, None)                                                   # a missing scale table
+    assert e.value.status == -1
+    for bad in (tm.make_config(2048, 640, 128, 8, "bf16", 1, 32),           # inter not a multiple of 256
+                tm.make_config(512, 768, 128, 8, "bf16", 1, 32),            # hidden below 1024
+                tm.make_config(2048, 768, 128, 8, "f32", 1, 32)):           # float storage
+        with pytest.raises(tm.TeamMoeError) as e:
+            call(bad)
+        assert e.value.status == -2
