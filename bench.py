@@ -51,6 +51,8 @@ def main() -> int:
     ap.add_argument("--copies", type=int, default=0, help="distinct weight sets rotated over (default 4; cfg4: layers of the stack, default 48)")
     ap.add_argument("--masks", type=str, default="",
                     help="activated-set sizes of the sweep (the headline size is always measured); e.g. --masks 32 for a profile of the headline only")
+    ap.add_argument("--w8", action="store_true",
+                    help="time the layer on 8-bit expert weights (E4M3 codes + row scales) instead of bf16 weights (not the headline)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     args = ap.parse_args()
@@ -123,7 +125,38 @@ def main() -> int:
 
     stream = torch.cuda.current_stream()
 
+    # ---- 8-bit copies of the expert weights (input preparation, on the device): the recipe of inputs.quantize_rows_e4m3 -
+    #      scale = max|row| / 448 rounded to 8 significant bits, code = nearest E4M3 value of w / scale
+    w8_supported = H in (1024, 2048) and I % 256 == 0
+    sets_q = []
+
+    def quantize_on_device(w_bf16):
+        w = w_bf16.float()
+        amax = w.abs().amax(dim=-1)
+        scale = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax)).bfloat16().float()
+        q = (w / scale.unsqueeze(-1)).clamp_(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8)
+        return q.contiguous(), scale.contiguous()
+
+    def w8_sets():
+        if not sets_q:
+            for c in range(n_sets):
+                qs = {n: quantize_on_device(sets[c][0][n]) for n in ("gate", "up", "down")}
+                sets_q.append(({n: v[0] for n, v in qs.items()}, {n: v[1] for n, v in qs.items()}))
+            # same codes and scales as the host recipe (checked on one expert of set 0)
+            wf = gen.as_f32(host_w0["down"][:1])
+            code, sc = gen.quantize_rows_e4m3(wf)
+            assert np.array_equal(sets_q[0][0]["down"][:1].cpu().numpy(), code) and np.array_equal(sets_q[0][1]["down"][:1].cpu().numpy(), sc)
+        return sets_q
+
+    def layer_w8(c, step, M):
+        d_w, xs, ms = sets[c]
+        q, sc = w8_sets()[c]
+        tm.team_moe_layer_forward_w8(cfg, xs[step], T, d_w["router"], q["gate"], q["up"], q["down"], sc["gate"], sc["up"], sc["down"],
+                                     ms[step][M], y, ws)
+
     def layer(c, step, M):
+        if args.w8:
+            return layer_w8(c, step, M)
         d_w, xs, ms = sets[c]
         tm.team_moe_layer_forward(cfg, xs[step], T, d_w["router"], d_w["gate"], d_w["up"], d_w["down"], ms[step][M], y, ws)
 
@@ -161,7 +194,7 @@ def main() -> int:
     st_nact = torch.empty((1,), dtype=torch.int32, device=dev)
     st_out = torch.empty((A, H), dtype=torch.float32, device=dev)
 
-    def time_ffn(M, calls, warmup):
+    def time_ffn(M, calls, warmup, w8=False):
         """Average duration of team_moe_expert_ffn (one launch of the weight-streaming kernel) from HIP events on the launch stream."""
         evs = []
         for i in range(warmup + calls):
@@ -170,8 +203,14 @@ def main() -> int:
             tm.team_moe_route(cfg, xs[step], T, d_w["router"], ms[step][M], r_idx, r_gate, None, ws)
             tm.team_moe_build_dispatch(cfg, r_idx, T, st_off, st_sorted, st_inv, st_act, st_nact, ws)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            tm.team_moe_expert_ffn(cfg, xs[step], T, st_off, st_sorted, st_act, st_nact, d_w["gate"], d_w["up"], d_w["down"], st_out, ws)
+            if w8:
+                q, sc = w8_sets()[i % n_sets]
+                e0.record(stream)
+                tm.team_moe_expert_ffn_w8(cfg, xs[step], T, st_off, st_sorted, st_act, st_nact, q["gate"], q["up"], q["down"], sc["gate"],
+                                          sc["up"], sc["down"], st_out, ws)
+            else:
+                e0.record(stream)
+                tm.team_moe_expert_ffn(cfg, xs[step], T, st_off, st_sorted, st_act, st_nact, d_w["gate"], d_w["up"], d_w["down"], st_out, ws)
             e1.record(stream)
             tm.team_moe_combine(cfg, st_out, r_gate, st_inv, T, y)
             if i >= warmup:
@@ -180,6 +219,9 @@ def main() -> int:
         return float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
 
     # ---- headline: exactly `steps` timed steps between synchronisations
+    if args.w8:
+        assert w8_supported, "8-bit weights need hidden 1024 or 2048 and inter a multiple of 256"
+        bytes_per_expert = 3 * H * I + (2 * I + H) * 4         # codes + row scales
     steps, warmup = (max(2, args.steps // 50), max(1, args.warmup // 20)) if wl == "cfg4" else (args.steps, args.warmup)
     sec_per_step = time_steps(headline, steps, warmup)
     layers_per_step = n_sets if wl == "cfg4" else 1
@@ -189,7 +231,7 @@ def main() -> int:
     for M in mask_sizes:
         s_step = sec_per_step if M == headline else time_steps(M, max(50, steps // 2), max(10, warmup // 2))
         s_layer = s_step / layers_per_step
-        s_ffn = time_ffn(M, max(50, args.steps // 2), max(10, args.warmup // 2))
+        s_ffn = time_ffn(M, max(50, args.steps // 2), max(10, args.warmup // 2), w8=args.w8)
         wbytes = touched[M] * bytes_per_expert
         flops = 2.0 * A * 3 * H * I
         sweep.append({"activated": M, "touched": touched[M], "ms_per_layer": s_layer * 1e3, "tokens_per_s": T / s_step,
@@ -232,6 +274,26 @@ def main() -> int:
         s2 = (time.perf_counter() - t_begin) / n2
         two_round = {"first_round_tokens": n_first, "activated": float(np.mean(n_act)), "ms_per_layer": s2 * 1e3, "tokens_per_s": T / s2}
         log(f"[bench] {wl} two-round routing: {n_first} first-round tokens -> |E_A| = {np.mean(n_act):.1f}, layer {s2 * 1e6:.1f} us")
+
+    # ---- the headline workload on 8-bit expert weights (half the weight bytes; a variant outside the paper)
+    w8 = None
+    if wl == "cfg2" and w8_supported and not args.masks and not args.w8:
+        def timed_w8(n):
+            for i in range(10):
+                layer_w8(i % n_sets, 0, headline)
+            torch.cuda.synchronize()
+            t_begin = time.perf_counter()
+            for i in range(n):
+                layer_w8(i % n_sets, 0, headline)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t_begin) / n
+
+        s8 = timed_w8(max(50, steps // 2))
+        f8 = time_ffn(headline, max(50, args.steps // 2), 10, w8=True)
+        b8 = touched[headline] * (3 * H * I + (2 * I + H) * 4)
+        w8 = {"weights": "E4M3 codes + one float scale per row", "activated": headline, "ms_per_layer": s8 * 1e3, "tokens_per_s": T / s8,
+              "ffn_ms": f8 * 1e3, "weight_bytes_per_launch": b8, "weight_GBps_ffn": b8 / f8 / 1e9, "frac_of_hbm_peak": b8 / f8 / 1e9 / HBM_PEAK_GBS}
+        log(f"[bench] {wl} M={headline} on 8-bit weights: layer {s8 * 1e6:.1f} us, ffn {f8 * 1e6:.1f} us, weight stream {b8 / f8 / 1e9:.0f} GB/s")
 
     # ---- candidate branches with repeated rows (Section "Aligned Token Candidates in SEH"): the same layer over 4 x 32 rows of
     #      which 34 are distinct, computed row by row and with every distinct row computed once
@@ -316,9 +378,9 @@ def main() -> int:
     }[wl]
     out = {"metric": "moe_layer_tokens_per_s", "value": T / sec_per_step, "unit": "tokens/s", "n_gpus": 1, "steps": steps,
            "warmup": warmup, "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "bf16", "data": "synthetic",
+           "dtype": "bf16", "data": "synthetic" + (" (expert weights stored as E4M3 codes with row scales)" if args.w8 else ""),
            "config": {"workload": desc, "tokens": T, "activated": headline, "touched": touched[headline], "layers_per_step": layers_per_step},
-           "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep, "two_round": two_round, "branches": branches,
+           "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep, "two_round": two_round, "branches": branches, "w8": w8,
            "device_copy_GBps": copy_gbps}
     if wl == "cfg4":
         out["ms_per_block_16_steps"] = sec_per_step * 1e3 * 16

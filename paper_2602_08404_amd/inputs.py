@@ -116,28 +116,66 @@ def e4m3_values() -> np.ndarray:
     return np.where(code >= 128, -mag, mag).astype(np.float32)
 
 
+def _e4m3_codes(v: np.ndarray) -> np.ndarray:
+    """Finite fp32 values -> codes of the nearest E4M3 values (ties to the even code, magnitudes above 448 saturate)."""
+    u = np.ascontiguousarray(v, dtype=np.float32).view(np.uint32)
+    mag = u & np.uint32(0x7FFFFFFF)
+    # normal range (>= 2^-6): keep 3 mantissa bits, round to nearest even on the 20 dropped bits -> exponent(8) | mantissa(3),
+    # saturate at the code of 448, then re-bias the exponent from 127 to 7
+    r = (mag + (np.uint32(0x7FFFF) + ((mag >> np.uint32(20)) & np.uint32(1)))) >> np.uint32(20)
+    r = np.minimum(r, np.uint32(0x7E + ((127 - 7) << 3)))
+    r -= np.uint32((127 - 7) << 3)                          # wraps for values below the normal range: replaced next
+    # below 2^-6 the format has the fixed step 2^-9: the code is the number of steps (8 steps = 2^-6 = code 0x08, the first normal)
+    small = mag < np.uint32(0x3C800000)                     # 0x3C800000 = 2^-6
+    if small.any():
+        r[small] = np.rint(mag.view(np.float32)[small] * np.float32(512.0)).astype(np.uint32)
+    code = r.astype(np.uint8)
+    code |= ((u >> np.uint32(24)) & np.uint32(0x80)).astype(np.uint8)
+    return code
+
+
+def _over_slices(fn, n: int) -> None:
+    """fn(i) for i in range(n) on worker threads (NumPy releases the interpreter lock inside its loops)."""
+    workers = min(16, os.cpu_count() or 1)
+    if n > 1 and workers > 1:
+        with ThreadPoolExecutor(workers) as ex:
+            list(ex.map(fn, range(n)))
+    else:
+        for i in range(n):
+            fn(i)
+
+
 def quantize_rows_e4m3(w: np.ndarray):
     """fp32 matrix [..., R, C] -> (codes uint8 [..., R, C], scale fp32 [..., R]): every row is stored as E4M3 codes times one
     scale per row.  scale = max|row| / 448 rounded to 8 significant bits (so that code value x scale is exact in fp32; 1 for an
     all-zero row); code = E4M3 value nearest to w / scale (ties to the even code, magnitudes above 448 saturate)."""
     w = np.ascontiguousarray(w, dtype=np.float32)
-    amax = np.abs(w).max(axis=-1)
-    scale = bf16_widen(bf16_round(np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)))
-    v = (w / scale[..., None]).astype(np.float32)
-    pos = e4m3_values()[:127].astype(np.float64)            # codes 0..126 ascending in value
-    a = np.minimum(np.abs(v).astype(np.float64), 448.0)
-    hi = np.clip(np.searchsorted(pos, a, side="left"), 1, 126)
-    lo = hi - 1
-    d_lo, d_hi = a - pos[lo], pos[hi] - a
-    take_hi = (d_hi < d_lo) | ((d_hi == d_lo) & (hi % 2 == 0))
-    code = np.where(take_hi, hi, lo).astype(np.uint8)
-    code = np.where(np.signbit(v), code | np.uint8(0x80), code).astype(np.uint8)
-    return code, scale.astype(np.float32)
+    w3 = w.reshape((-1,) + w.shape[-2:])
+    code = np.empty(w3.shape, np.uint8)
+    scale = np.empty(w3.shape[:2], np.float32)
+
+    def one(i):
+        amax = np.abs(w3[i]).max(axis=-1)
+        scale[i] = bf16_widen(bf16_round(np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)))
+        code[i] = _e4m3_codes(w3[i] / scale[i][:, None])
+
+    _over_slices(one, w3.shape[0])
+    return code.reshape(w.shape), scale.reshape(w.shape[:-1])
 
 
 def dequantize_rows_e4m3(code: np.ndarray, scale: np.ndarray) -> np.ndarray:
     """The fp32 weights that (code, scale) stand for: value of the code times the row's scale (exact in fp32)."""
-    return (e4m3_values()[code] * scale[..., None]).astype(np.float32)
+    code = np.ascontiguousarray(code)
+    c3 = code.reshape((-1,) + code.shape[-2:])
+    s2 = np.ascontiguousarray(scale, dtype=np.float32).reshape(c3.shape[:2])
+    out = np.empty(c3.shape, np.float32)
+    table = e4m3_values()
+
+    def one(i):
+        np.multiply(table[c3[i]], s2[i][:, None], out=out[i])
+
+    _over_slices(one, c3.shape[0])
+    return out.reshape(code.shape)
 
 
 # --------------------------------------------------------------------------- hidden states

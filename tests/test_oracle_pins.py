@@ -513,3 +513,17 @@ def test_e4m3_row_quantisation():
     zero = np.zeros((2, 16), np.float32)
     code, scale = gen.quantize_rows_e4m3(zero)
     assert (code == 0).all() and (scale == 1).all()
+
+
+def test_e4m3_codes_agree_with_torch_float8_conversion():
+    """The same rounding as the library conversion of PyTorch (float32 -> float8_e4m3fn), on values across the whole range:
+    subnormals, the normal range, exact ties and the saturation region up to the largest finite value."""
+    import torch
+    rng = np.random.default_rng(0)
+    v = np.concatenate([rng.standard_normal(20000).astype(np.float32) * np.float32(s) for s in (1e-3, 0.02, 1.0, 30.0, 200.0)])
+    vals = gen.e4m3_values()[:127]
+    ties = ((vals[:-1].astype(np.float64) + vals[1:]) / 2).astype(np.float32)
+    v = np.clip(np.concatenate([v, ties, -ties, vals, -vals, np.float32([0.0, -0.0, 447.9, 448.0])]), -448, 448)
+    want = torch.from_numpy(v).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = gen._e4m3_codes(v)
+    assert np.array_equal(got, want)
