@@ -107,10 +107,26 @@ __device__ __forceinline__ uint32_t lds_read_u32(uint32_t a) {
 }
 __device__ __forceinline__ void lds_write_u32(uint32_t a, uint32_t v) { asm volatile("ds_write_b32 %0, %1" ::"v"(a), "v"(v) : "memory"); }
 // LDS accesses and the workgroup barrier as explicit instructions (see the item loop for why).
-__device__ __forceinline__ void lds_write_f4(uint32_t a, const f32x4_t& v) { asm volatile("ds_write_b128 %0, %1" ::"v"(a), "v"(v) : "memory"); }
-__device__ __forceinline__ f32x4_t lds_read_f4(uint32_t a) {
+// 16-byte accesses with a constant byte offset in the instruction: the partial sums of the four wavefronts sit at fixed
+// distances from one per-lane address, so one address register serves all of them.
+template <int OFF>
+__device__ __forceinline__ void lds_write_f4_at(uint32_t a, const f32x4_t& v) {
+    asm volatile("ds_write_b128 %0, %1 offset:%2" ::"v"(a), "v"(v), "n"(OFF) : "memory");
+}
+template <int OFF>
+__device__ __forceinline__ f32x4_t lds_read_f4_at(uint32_t a) {
     f32x4_t v;
-    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
+    asm volatile("ds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a), "n"(OFF) : "memory");
+    return v;
+}
+// Sum of the four wavefronts' partial sums, STRIDE bytes apart, added in wavefront order.
+template <int STRIDE>
+__device__ __forceinline__ f32x4_t lds_sum4(uint32_t a) {
+    static_assert(FFN_WAVES == 4 && 3 * STRIDE + 16 <= 65536, "four partial sums within the instruction's offset range");
+    f32x4_t v = lds_read_f4_at<0>(a);
+    v += lds_read_f4_at<STRIDE>(a);
+    v += lds_read_f4_at<2 * STRIDE>(a);
+    v += lds_read_f4_at<3 * STRIDE>(a);
     return v;
 }
 // A matrix instruction's result may only be read by a memory instruction a number of cycles after it was issued.  The compiler
@@ -520,21 +536,23 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                     else stream_item<SA, UA, 1, false, false, WB, KSM>(region, n, q, opr, acc, next_stage);
                 }
                 settle_accumulators(acc[0]);
-                lds_write_f4(red_base + ((wave * NT + 0) * WAVE + ln) * 16, acc[0][0]);
-                lds_write_f4(red_base + ((wave * NT + 1) * WAVE + ln) * 16, acc[0][1]);
+                const uint32_t red_mine = red_base + (uint32_t)(wave * NT * WAVE + ln) * 16;
+                lds_write_f4_at<0>(red_mine, acc[0][0]);
+                lds_write_f4_at<WAVE * 16>(red_mine, acc[0][1]);
                 lds_barrier();
                 if (chunks == 1 && held == 0) held_it0 = it;
                 if (wave < NT && (wave == 0 || two)) {        // wavefront nt finishes token tile nt
-                    f32x4_t v = lds_read_f4(red_base + ((0 * NT + wave) * WAVE + ln) * 16);
-#pragma unroll
-                    for (int w = 1; w < FFN_WAVES; ++w) v += lds_read_f4(red_base + ((w * NT + wave) * WAVE + ln) * 16);
+                    f32x4_t v = lds_sum4<NT * WAVE * 16>(red_base + (uint32_t)(wave * WAVE + ln) * 16);
                     const int row = row_base + wave * 16 + n;
                     // lane holds (g_a, g_b, u_a, u_b) of intermediate indices it*8 + 2*q, +1 for token row `row`
                     if constexpr (WB == 1) {
-                        const float g0 = q == 0 ? sc_g[0] : q == 1 ? sc_g[2] : q == 2 ? sc_g[4] : sc_g[6];
-                        const float g1 = q == 0 ? sc_g[1] : q == 1 ? sc_g[3] : q == 2 ? sc_g[5] : sc_g[7];
-                        const float u0 = q == 0 ? sc_u[0] : q == 1 ? sc_u[2] : q == 2 ? sc_u[4] : sc_u[6];
-                        const float u1 = q == 0 ? sc_u[1] : q == 1 ? sc_u[3] : q == 2 ? sc_u[5] : sc_u[7];
+                        // (the lane's group index is made opaque here so that the selections are not moved in front of the
+                        // stream, where their results would occupy registers the stream needs)
+                        const int qs = opaque(q);
+                        const float g0 = qs == 0 ? sc_g[0] : qs == 1 ? sc_g[2] : qs == 2 ? sc_g[4] : sc_g[6];
+                        const float g1 = qs == 0 ? sc_g[1] : qs == 1 ? sc_g[3] : qs == 2 ? sc_g[5] : sc_g[7];
+                        const float u0 = qs == 0 ? sc_u[0] : qs == 1 ? sc_u[2] : qs == 2 ? sc_u[4] : sc_u[6];
+                        const float u1 = qs == 0 ? sc_u[1] : qs == 1 ? sc_u[3] : qs == 2 ? sc_u[5] : sc_u[7];
                         v[0] *= g0; v[1] *= g1; v[2] *= u0; v[3] *= u1;
                     }
                     const float h0 = silu_f32(v[0]) * v[2];
@@ -628,22 +646,25 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                     else stream_item<SB, UB, RB, false, false, WB, KSM>(region, n, q, opr, acc, next_stage);
                 }
                 settle_accumulators(reinterpret_cast<f32x4_t(&)[RB * NT]>(acc));
-#pragma unroll
-                for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) lds_write_f4(redb_base + (((wave * RB + rb) * NT + nt) * WAVE + ln) * 16, acc[rb][nt]);
+                const uint32_t redb_mine = redb_base + (uint32_t)(wave * RB * NT * WAVE + ln) * 16;
+                static_assert(NT == 2 && (RB == 1 || RB == 2), "partial sums are written out one by one");
+                lds_write_f4_at<0>(redb_mine, acc[0][0]);
+                lds_write_f4_at<WAVE * 16>(redb_mine, acc[0][1]);
+                if constexpr (RB == 2) {
+                    lds_write_f4_at<2 * WAVE * 16>(redb_mine, acc[1][0]);
+                    lds_write_f4_at<3 * WAVE * 16>(redb_mine, acc[1][1]);
+                }
                 lds_barrier();
                 // (rb, nt) pairs are finished by wavefronts round-robin, partial sums added in wavefront order
                 for (int pair = wave; pair < RB * NT; pair += FFN_WAVES) {
                     const int rb = pair / NT, nt = pair % NT;
                     const int row = row_base + nt * 16 + n;
                     if (row < m) {
-                        f32x4_t v = lds_read_f4(redb_base + (((0 * RB + rb) * NT + nt) * WAVE + ln) * 16);
-#pragma unroll
-                        for (int w = 1; w < FFN_WAVES; ++w) v += lds_read_f4(redb_base + (((w * RB + rb) * NT + nt) * WAVE + ln) * 16);
+                        f32x4_t v = lds_sum4<RB * NT * WAVE * 16>(redb_base + (uint32_t)((rb * NT + nt) * WAVE + ln) * 16);
                         // lane holds output rows it*16*RB + rb*16 + 4*q + (0..3) of token row `row`
                         if constexpr (WB == 1) {
-                            v[0] *= pick4(sc_d, q, 0); v[1] *= pick4(sc_d, q, 1); v[2] *= pick4(sc_d, q, 2); v[3] *= pick4(sc_d, q, 3);
+                            const int qs = opaque(q);       // as in the gate/up epilogue
+                            v[0] *= pick4(sc_d, qs, 0); v[1] *= pick4(sc_d, qs, 1); v[2] *= pick4(sc_d, qs, 2); v[3] *= pick4(sc_d, qs, 3);
                         }
                         *reinterpret_cast<f32x4_t*>(out + (size_t)(r0 + row) * H + it * 16 * RB + rb * 16 + 4 * q) = v;
                     }
