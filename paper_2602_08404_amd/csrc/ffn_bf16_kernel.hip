@@ -10,7 +10,7 @@
 //                   all H columns; h = silu(g) * u is formed in the epilogue and stored as bf16;
 //   down items    : (active expert, 16*RB consecutive output rows of w_down), all I columns; fp32 out.
 // The grid is exactly the number of workgroups the device holds at once.  Workgroup b owns the b-th of G
-// equal contiguous shares of the gate/up item list and then the b-th share of the down item list (lists in
+// contiguous shares (equal up to one item) of the gate/up item list and then the b-th share of the down item list (lists in
 // expert-major order, computed on the device from n_active, so experts without tokens cost nothing and the
 // host never reads device data).  Consecutive items of a share belong to the same expert, so the token
 // operand stays in registers; and because both lists are cut at the same fractions, the down items of a
@@ -389,8 +389,14 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         }
     }
     const long long total_a = (long long)n_act * TILES_A, total_b = (long long)n_act * TILES_B;
-    const int a_begin = (int)(total_a * blockIdx.x / G), a_end = (int)(total_a * (blockIdx.x + 1) / G);
-    const int b_begin = (int)(total_b * blockIdx.x / G), b_end = (int)(total_b * (blockIdx.x + 1) / G);
+    // Contiguous shares of floor(total / G) items; the remainder goes, one item each, to the lowest-numbered workgroups.  Those are
+    // placed first, one per compute unit, and run ahead of the second workgroup of their unit by about one item over a launch
+    // (measured), so the extra item is absorbed instead of extending the phase (with shares that alternate between n and n + 1
+    // items every unit ends up with a straggler).
+    const int bx = (int)blockIdx.x;
+    const int base_a = (int)(total_a / G), rem_a = (int)(total_a % G), base_b = (int)(total_b / G), rem_b = (int)(total_b % G);
+    const int a_begin = bx * base_a + min(bx, rem_a), a_end = a_begin + base_a + (bx < rem_a ? 1 : 0);
+    const int b_begin = bx * base_b + min(bx, rem_b), b_end = b_begin + base_b + (bx < rem_b ? 1 : 0);
     const int n_a = a_end - a_begin, n_mine = n_a + (b_end - b_begin);
     __syncthreads();
 

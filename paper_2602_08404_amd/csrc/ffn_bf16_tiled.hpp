@@ -128,7 +128,9 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
         const int tiles = phase == 0 ? tiles_a : tiles_b;
         const int nks = (phase == 0 ? H : I) / KC;                 // stages per (item, pass)
         const long long total = (long long)n_act * tiles;
-        const int li_begin = (int)(total * blockIdx.x / G), li_end = (int)(total * (blockIdx.x + 1) / G);
+        // contiguous shares; the remainder goes to the lowest-numbered workgroups (see the register-operand body)
+        const int share = (int)(total / G), extra = (int)(total % G), bx = (int)blockIdx.x;
+        const int li_begin = bx * share + min(bx, extra), li_end = li_begin + share + (bx < extra ? 1 : 0);
 
         auto load_item = [&](Seg& s) {                              // fills a, it, e, r0, m of item s.li; skips items without rows
             s.valid = false;
