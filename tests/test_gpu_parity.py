@@ -538,3 +538,46 @@ def test_w8_rejects_unsupported_configurations(cfg1_case, cfg2_w8):
         with pytest.raises(tm.TeamMoeError) as e:
             call(bad)
         assert e.value.status == -2
+
+
+# ----------------------------------------------------------------------------- captured into a HIP graph
+def test_layer_calls_replay_from_a_hip_graph(cfg2_case, cfg2_w8):
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no synchronisation, no memset nodes), so a
+    caller may capture them.  Three layer variants are captured into one graph; every replay, with eager calls on other inputs
+    in between, must give the bits of the eager calls."""
+    c, s = cfg2_case, gen.CFG2
+    mask = torch.from_numpy(c12_mask(c, 32)).to(hz.DEV)
+    cls = torch.from_numpy(gen.token_classes(s.T, 4, seed=3)).to(hz.DEV)
+    ws = torch.empty(tm.team_moe_workspace_size(c.cfg), dtype=torch.uint8, device=hz.DEV)
+    w, q, sc = c.d_w, cfg2_w8.q, cfg2_w8.scale
+    ys = [torch.zeros((s.T, s.H), dtype=torch.bfloat16, device=hz.DEV) for _ in range(3)]
+    e_a = torch.zeros((s.E,), dtype=torch.uint8, device=hz.DEV)
+    n_a = torch.zeros((1,), dtype=torch.int32, device=hz.DEV)
+
+    def calls():
+        tm.team_moe_layer_forward(c.cfg, c.d_x, s.T, w["router"], w["gate"], w["up"], w["down"], mask, ys[0], ws)
+        tm.team_moe_layer_forward_two_round(c.cfg, c.d_x, s.T, w["router"], w["gate"], w["up"], w["down"], cls, e_a, n_a, ys[1], ws)
+        tm.team_moe_layer_forward_w8(c.cfg, c.d_x, s.T, w["router"], q["gate"], q["up"], q["down"], sc["gate"], sc["up"], sc["down"],
+                                     mask, ys[2], ws)
+
+    calls()
+    torch.cuda.synchronize()
+    want = [y.clone() for y in ys]
+    want_n = int(n_a.item())
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            calls()
+    torch.cuda.synchronize()
+    other = c.with_x(s, gen.make_x(s, seed=11))
+    for i in range(4):
+        for y in ys:
+            y.zero_()
+        n_a.zero_()
+        hz.gpu_layer(other, None, ws)                       # eager work on the same workspace between the replays
+        graph.replay()
+        torch.cuda.synchronize()
+        for y, ref in zip(ys, want):
+            assert torch.equal(y, ref), i
+        assert int(n_a.item()) == want_n
