@@ -107,6 +107,26 @@ def test_bad_call_arguments_are_rejected_before_any_launch():
     assert lib.team_moe_layer_forward_rows(C.byref(cfg), fake, fake, 0, fake, *rows_args, None, None, None, None, fake, 1 << 30, st) == -1
     assert lib.team_moe_layer_forward_rows(C.byref(cfg), fake, fake, 32, fake, *rows_args, fake, fake, None, None, fake, 1 << 30, st) == -1
     assert lib.team_moe_layer_forward_rows(C.byref(cfg), fake, fake, 32, fake, *rows_args, None, None, None, None, None, 0, st) == -3
+    # repeated rows: same validation as the plain layer (the optional outputs may be NULL)
+    assert lib.team_moe_layer_forward_unique_rows(C.byref(cfg), None, 8, fake, fake, fake, fake, None, fake, None, None, fake, 1 << 30, st) == -1
+    assert lib.team_moe_layer_forward_unique_rows(C.byref(cfg), fake, 8, fake, fake, fake, fake, None, fake, None, None, fake, 1024, st) == -3
+    # 8-bit weights: scale tables required and 4-byte aligned; bf16 configuration with hidden 1024/2048 and inter % 256 == 0
+    w8_tail = (fake, fake, 1 << 30, st)
+    assert lib.team_moe_layer_forward_w8(C.byref(cfg), fake, 8, fake, fake, fake, fake, fake, None, fake, None, *w8_tail) == -1
+    assert lib.team_moe_layer_forward_w8(C.byref(cfg), fake, 8, fake, fake, fake, fake, fake, C.c_void_p(0x1002), fake, None, *w8_tail) == -1
+    assert lib.team_moe_layer_forward_w8(C.byref(cfg), fake, 8, fake, fake, fake, fake, fake, fake, fake, None, fake, None, 0, st) == -3
+    for bad_cfg in (tm.make_config(2048, 640, 128, 8, "bf16", 1, 32), tm.make_config(512, 768, 128, 8, "bf16", 1, 32),
+                    tm.make_config(2048, 768, 128, 8, "f32", 1, 32)):
+        assert lib.team_moe_layer_forward_w8(C.byref(bad_cfg), fake, 8, fake, fake, fake, fake, fake, fake, fake, None, *w8_tail) == -2
+        assert lib.team_moe_expert_ffn_w8(C.byref(bad_cfg), fake, 8, fake, fake, fake, fake, fake, fake, fake, fake, fake, fake, fake,
+                                          fake, 1 << 30, st) == -2
+    assert lib.team_moe_expert_ffn_w8(C.byref(cfg), fake, 8, fake, fake, fake, fake, fake, fake, fake, fake, fake, None, fake,
+                                      fake, 1 << 30, st) == -1
+    i64 = C.c_int64
+    assert lib.team_moe_dequantize_w8(None, fake, i64(4), i64(64), fake, st) == -1
+    assert lib.team_moe_dequantize_w8(fake, fake, i64(4), i64(40), fake, st) == -1          # columns not a multiple of 16
+    assert lib.team_moe_dequantize_w8(fake, fake, i64(0), i64(64), fake, st) == -1
+    assert lib.team_moe_dequantize_w8(odd, fake, i64(4), i64(64), fake, st) == -1
     # NULL cfg / NULL size pointer
     assert lib.team_moe_workspace_size(None, C.byref(C.c_size_t())) == -1
     assert lib.team_moe_workspace_size(C.byref(cfg), None) == -1
