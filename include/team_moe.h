@@ -245,6 +245,43 @@ int team_moe_layer_forward_w8(const team_moe_config* cfg, const void* x, int32_t
                               void* stream);
 int team_moe_dequantize_w8(const uint8_t* codes, const float* scale, int64_t rows, int64_t cols, float* out, void* stream);
 
+/*
+ * One denoising step's MoE layer with the variants above combined, as the decoding loop of the paper uses them together
+ * (Sections "Delayed Caching for Decoded Tokens", "Limited Activation for Cold Tokens (LAC)" / Algorithm 1, and "Speculative
+ * Exploration for Hot Tokens (SEH)"): live rows of the block's tensors, the activated set from a mask or from the tokens'
+ * classes on the device, bf16 or 8-bit expert weights, repeated rows computed once.  All pointers are device pointers unless
+ * stated; every field that a variant does not use must be NULL / 0.
+ */
+typedef struct {
+    const void* x;                  /* [T,H], or [n_rows,H] when row_index is given */
+    void* y;                        /* same shape as x; only the rows of the call are written */
+    int32_t T;                      /* tokens of the call */
+    int32_t n_rows;                 /* rows of x and y when row_index is given, else 0 */
+    const int32_t* row_index;       /* [T] rows of x / y that the call computes, or NULL: rows 0..T-1 (team_moe_layer_forward_rows) */
+    const void* w_router;           /* [E,H] in cfg->dtype */
+    const void* w_gate;             /* [E,I,H] in cfg->dtype, or E4M3 codes when the scales are given */
+    const void* w_up;               /* [E,I,H] */
+    const void* w_down;             /* [E,H,I] */
+    const float* scale_gate;        /* [E,I]; all three scale tables or none (team_moe_layer_forward_w8) */
+    const float* scale_up;          /* [E,I] */
+    const float* scale_down;        /* [E,H] */
+    const uint8_t* expert_mask;     /* [E] or NULL; must be NULL when token_class is given */
+    const uint8_t* token_class;     /* [T] or NULL: two-round routing (team_moe_layer_forward_two_round) */
+    uint8_t* activated_mask_out;    /* [E] or NULL; written in the two-round mode */
+    int32_t* n_activated_out;       /* [1] or NULL; written in the two-round mode */
+    int32_t unique_rows;            /* 1: compute repeated rows once (team_moe_layer_forward_unique_rows); needs row_index == NULL
+                                       and token_class == NULL */
+    int32_t reserved;               /* must be 0 */
+    int32_t* row_rep_out;           /* [T] or NULL; written when unique_rows */
+    int32_t* n_unique_out;          /* [1] or NULL; written when unique_rows */
+    void* workspace;                /* team_moe_workspace_size(cfg) bytes, 256-byte aligned */
+    size_t ws_bytes;
+    void* stream;                   /* hipStream_t */
+} team_moe_layer_args;
+
+/* `args` is a host pointer and is not retained.  Returns a team_status; unsupported combinations: TEAM_ERR_INVALID_ARG. */
+int team_moe_layer_forward_ex(const team_moe_config* cfg, const team_moe_layer_args* args);
+
 /* Static, NUL-terminated description of a team_status value. */
 const char* team_moe_status_string(int status);
 

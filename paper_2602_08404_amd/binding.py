@@ -20,7 +20,19 @@ STATUS_OK = 0
 EXPORTS = ["team_moe_workspace_size", "team_moe_route", "team_moe_build_dispatch", "team_moe_expert_ffn",
            "team_moe_combine", "team_moe_layer_forward", "team_moe_route_two_round", "team_moe_layer_forward_two_round",
            "team_moe_classify_tokens", "team_moe_layer_forward_rows", "team_moe_layer_forward_unique_rows",
-           "team_moe_expert_ffn_w8", "team_moe_layer_forward_w8", "team_moe_dequantize_w8", "team_moe_status_string"]
+           "team_moe_expert_ffn_w8", "team_moe_layer_forward_w8", "team_moe_dequantize_w8", "team_moe_layer_forward_ex",
+           "team_moe_status_string"]
+
+
+class LayerArgs(C.Structure):
+    """team_moe_layer_args of include/team_moe.h."""
+    _fields_ = [("x", C.c_void_p), ("y", C.c_void_p), ("T", C.c_int32), ("n_rows", C.c_int32), ("row_index", C.c_void_p),
+                ("w_router", C.c_void_p), ("w_gate", C.c_void_p), ("w_up", C.c_void_p), ("w_down", C.c_void_p),
+                ("scale_gate", C.c_void_p), ("scale_up", C.c_void_p), ("scale_down", C.c_void_p),
+                ("expert_mask", C.c_void_p), ("token_class", C.c_void_p), ("activated_mask_out", C.c_void_p),
+                ("n_activated_out", C.c_void_p), ("unique_rows", C.c_int32), ("reserved", C.c_int32),
+                ("row_rep_out", C.c_void_p), ("n_unique_out", C.c_void_p), ("workspace", C.c_void_p), ("ws_bytes", C.c_size_t),
+                ("stream", C.c_void_p)]
 
 
 class TeamMoeError(RuntimeError):
@@ -65,6 +77,7 @@ def lib() -> C.CDLL:
         L.team_moe_expert_ffn_w8.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_layer_forward_w8.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_dequantize_w8.argtypes = [vp, vp, C.c_int64, C.c_int64, vp, vp]
+        L.team_moe_layer_forward_ex.argtypes = [cfgp, C.POINTER(LayerArgs)]
         L.team_moe_status_string.argtypes = [C.c_int]
         L.team_moe_status_string.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -195,3 +208,15 @@ def team_moe_layer_forward_w8(cfg: Config, x, T: int, w_router, w_gate_q, w_up_q
 def team_moe_dequantize_w8(codes, scale, rows: int, cols: int, out, stream=None) -> None:
     _check(lib().team_moe_dequantize_w8(_ptr(codes), _ptr(scale), rows, cols, _ptr(out), stream if stream is not None else _stream()),
            "team_moe_dequantize_w8")
+
+
+def team_moe_layer_forward_ex(cfg: Config, x, y, T: int, w_router, w_gate, w_up, w_down, workspace, *, row_index=None, n_rows: int = 0,
+                              scales=None, expert_mask=None, token_class=None, activated_mask_out=None, n_activated_out=None,
+                              unique_rows: bool = False, row_rep_out=None, n_unique_out=None, stream=None) -> None:
+    """Keyword arguments select the variants; `scales` = (scale_gate, scale_up, scale_down) tensors for 8-bit weights."""
+    sg, su, sd = scales if scales is not None else (None, None, None)
+    a = LayerArgs(_ptr(x), _ptr(y), T, n_rows, _ptr(row_index), _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(sg), _ptr(su),
+                  _ptr(sd), _ptr(expert_mask), _ptr(token_class), _ptr(activated_mask_out), _ptr(n_activated_out), 1 if unique_rows else 0, 0,
+                  _ptr(row_rep_out), _ptr(n_unique_out), _ptr(workspace),
+                  0 if workspace is None else workspace.numel() * workspace.element_size(), stream if stream is not None else _stream())
+    _check(lib().team_moe_layer_forward_ex(C.byref(cfg), C.byref(a)), "team_moe_layer_forward_ex")

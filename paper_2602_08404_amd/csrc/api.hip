@@ -357,6 +357,22 @@ int team_moe_layer_forward_w8(const team_moe_config* cfg, const void* x, int32_t
                          stream, nullptr, 0, false, nullptr, nullptr, &w8);
 }
 
+int team_moe_layer_forward_ex(const team_moe_config* cfg, const team_moe_layer_args* a) {
+    if (!a || a->reserved != 0) return TEAM_ERR_INVALID_ARG;
+    const bool rows = a->row_index != nullptr;
+    if (rows ? a->n_rows < 1 : a->n_rows != 0) return TEAM_ERR_INVALID_ARG;
+    if (a->expert_mask && a->token_class) return TEAM_ERR_INVALID_ARG;                // one routing mode per call
+    if (a->unique_rows != 0 && a->unique_rows != 1) return TEAM_ERR_INVALID_ARG;
+    if (a->unique_rows && (rows || a->token_class)) return TEAM_ERR_INVALID_ARG;      // the search reads dense x and single-round tables
+    if (!a->unique_rows && (a->row_rep_out || a->n_unique_out)) return TEAM_ERR_INVALID_ARG;
+    if (!a->token_class && (a->activated_mask_out || a->n_activated_out)) return TEAM_ERR_INVALID_ARG;
+    const bool any_scale = a->scale_gate || a->scale_up || a->scale_down;
+    const team::W8Scales w8{a->scale_gate, a->scale_up, a->scale_down};
+    return layer_forward(cfg, a->x, a->T, a->w_router, a->w_gate, a->w_up, a->w_down, a->expert_mask, a->token_class,
+                         a->activated_mask_out, a->n_activated_out, a->y, a->workspace, a->ws_bytes, a->stream, a->row_index, a->n_rows,
+                         a->unique_rows != 0, a->row_rep_out, a->n_unique_out, any_scale ? &w8 : nullptr);
+}
+
 const char* team_moe_status_string(int status) {
     switch (status) {
         case TEAM_OK: return "ok";

@@ -127,6 +127,25 @@ def test_bad_call_arguments_are_rejected_before_any_launch():
     assert lib.team_moe_dequantize_w8(fake, fake, i64(4), i64(40), fake, st) == -1          # columns not a multiple of 16
     assert lib.team_moe_dequantize_w8(fake, fake, i64(0), i64(64), fake, st) == -1
     assert lib.team_moe_dequantize_w8(odd, fake, i64(4), i64(64), fake, st) == -1
+    # the combined call: combinations that are not supported, stray outputs, bad row counts
+    def ex(**kw):
+        base = dict(x=0x1000, y=0x1000, T=8, n_rows=0, row_index=None, w_router=0x1000, w_gate=0x1000, w_up=0x1000, w_down=0x1000,
+                    workspace=0x1000, ws_bytes=1 << 30, stream=None)
+        base.update(kw)
+        return lib.team_moe_layer_forward_ex(C.byref(cfg), C.byref(binding.LayerArgs(**base)))
+    assert lib.team_moe_layer_forward_ex(C.byref(cfg), None) == -1
+    assert ex(expert_mask=0x1000, token_class=0x1000) == -1
+    assert ex(unique_rows=1, token_class=0x1000) == -1
+    assert ex(unique_rows=1, row_index=0x1000, n_rows=16) == -1
+    assert ex(unique_rows=2) == -1
+    assert ex(row_rep_out=0x1000) == -1
+    assert ex(n_activated_out=0x1000) == -1
+    assert ex(row_index=0x1000, n_rows=0) == -1
+    assert ex(n_rows=16) == -1
+    assert ex(reserved=1) == -1
+    assert ex(scale_gate=0x1000) == -1                       # all three scale tables or none
+    assert ex(workspace=None, ws_bytes=0) == -3
+    assert ex(x=None) == -1
     # NULL cfg / NULL size pointer
     assert lib.team_moe_workspace_size(None, C.byref(C.c_size_t())) == -1
     assert lib.team_moe_workspace_size(C.byref(cfg), None) == -1

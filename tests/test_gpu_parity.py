@@ -581,3 +581,68 @@ def test_layer_calls_replay_from_a_hip_graph(cfg2_case, cfg2_w8):
         for y, ref in zip(ys, want):
             assert torch.equal(y, ref), i
         assert int(n_a.item()) == want_n
+
+
+# ----------------------------------------------------------------------------- the variants combined in one call
+def test_combined_call_live_rows_two_round_8bit_weights(cfg2_case, cfg2_w8):
+    """Live rows of a block + activated set decided on the device + 8-bit weights in one call, against the same pieces
+    called one by one: same E_A as the two-round router on the gathered rows, same bits as the 8-bit layer on the gathered
+    rows under that E_A (whose numerics are then checked against the oracle), other rows untouched."""
+    s = gen.CFG2
+    n_rows, T = 64, 23
+    x_rows = gen.make_x(gen.scaled(s, T=n_rows), seed=12)
+    rows = np.sort(gen.token_permutation(n_rows, seed=12)[:T]).astype(np.int32)
+    cls = gen.token_classes(T, 5, seed=12)
+    sT = gen.scaled(s, T=T)
+    cfg = tm.make_config(s.H, s.I, s.E, s.k, "bf16", 1, T)
+    ws = torch.empty(tm.team_moe_workspace_size(cfg), dtype=torch.uint8, device=hz.DEV)
+    w, q, sc = cfg2_case.d_w, cfg2_w8.q, cfg2_w8.scale
+    y_rows = torch.full((n_rows, s.H), 7.0, dtype=torch.bfloat16, device=hz.DEV)
+    e_a = torch.full((s.E,), 9, dtype=torch.uint8, device=hz.DEV)
+    n_a = torch.full((1,), -7, dtype=torch.int32, device=hz.DEV)
+    tm.team_moe_layer_forward_ex(cfg, hz.to_dev(x_rows), y_rows, T, w["router"], q["gate"], q["up"], q["down"], ws,
+                                 row_index=torch.from_numpy(rows).to(hz.DEV), n_rows=n_rows, scales=(sc["gate"], sc["up"], sc["down"]),
+                                 token_class=torch.from_numpy(cls).to(hz.DEV), activated_mask_out=e_a, n_activated_out=n_a)
+    torch.cuda.synchronize()
+    mask = e_a.cpu().numpy()
+    gathered = cfg2_w8.with_x(sT, np.ascontiguousarray(x_rows[rows]))
+    _, _, g_mask, g_n, _ = hz.gpu_route_two_round(gathered.case, cls)
+    assert np.array_equal(mask, g_mask) and int(n_a.item()) == g_n == int(mask.sum())
+    _, y_dense = hz.gpu_layer_w8(gathered, mask)
+    live = torch.from_numpy(rows).long().to(hz.DEV)
+    assert torch.equal(y_rows[live], y_dense)
+    other = torch.ones(n_rows, dtype=torch.bool, device=hz.DEV)
+    other[live] = False
+    assert (y_rows[other] == 7.0).all()
+    say("combined call", hz.w8_parity(gathered, mask))
+
+
+def test_combined_call_plain_and_repeated_rows_with_8bit_weights(cfg2_case, cfg2_w8):
+    s = gen.CFG2
+    c = cfg2_case
+    mask = torch.from_numpy(c12_mask(c, 32)).to(hz.DEV)
+    ws = torch.empty(tm.team_moe_workspace_size(c.cfg), dtype=torch.uint8, device=hz.DEV)
+    w, q, sc = c.d_w, cfg2_w8.q, cfg2_w8.scale
+    # no variant selected: the bits of team_moe_layer_forward
+    y = torch.empty((s.T, s.H), dtype=torch.bfloat16, device=hz.DEV)
+    tm.team_moe_layer_forward_ex(c.cfg, c.d_x, y, s.T, w["router"], w["gate"], w["up"], w["down"], ws, expert_mask=mask)
+    torch.cuda.synchronize()
+    assert torch.equal(y, hz.gpu_layer(c, mask.cpu().numpy())[1])
+    # repeated rows + 8-bit weights: every row equals the 8-bit layer's row of its first occurrence
+    x = np.ascontiguousarray(c.x[[0, 1, 0, 2, 1, 3, 3, 0, 4, 5, 4, 6]])
+    rep_case = cfg2_w8.with_x(gen.scaled(s, T=12), x)
+    y2 = torch.empty((12, s.H), dtype=torch.bfloat16, device=hz.DEV)
+    rep = torch.full((12,), -7, dtype=torch.int32, device=hz.DEV)
+    n_u = torch.full((1,), -7, dtype=torch.int32, device=hz.DEV)
+    tm.team_moe_layer_forward_ex(rep_case.case.cfg, rep_case.case.d_x, y2, 12, w["router"], q["gate"], q["up"], q["down"], ws,
+                                 scales=(sc["gate"], sc["up"], sc["down"]), expert_mask=mask, unique_rows=True, row_rep_out=rep,
+                                 n_unique_out=n_u)
+    torch.cuda.synchronize()
+    want_rep = orc.row_representatives(x)
+    assert np.array_equal(rep.cpu().numpy(), want_rep) and int(n_u.item()) == 7
+    first = np.nonzero(want_rep == np.arange(12))[0]
+    uniq = cfg2_w8.with_x(gen.scaled(s, T=len(first)), np.ascontiguousarray(x[first]))
+    _, y_uniq = hz.gpu_layer_w8(uniq, mask.cpu().numpy())
+    pos = {int(t): i for i, t in enumerate(first)}
+    idx = torch.tensor([pos[int(r)] for r in want_rep], device=hz.DEV)
+    assert torch.equal(y2, y_uniq[idx])
