@@ -15,7 +15,9 @@ workload on this machine's host cores.
 
 Other workloads (--workload): cfg3 = 4 speculative candidates x 32 tokens sharing one set of 32 experts;
 cfg5 = 256 tokens over 256 fine-grained experts (sets 256/96/48); cfg4 = a stack of 48 such layers run for 16
-denoising steps with an activated set of 24 per (layer, step), a step being one pass over the whole stack.
+denoising steps with an activated set of 24 per (layer, step), a step being one pass over the whole stack;
+block = the decoding of one 32-token block through that stack the way the paper's method runs it (live rows only, token
+classes and the activated set decided on the device), next to the same block with every row and free routing.
 """
 from __future__ import annotations
 
@@ -42,17 +44,114 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def run_block(args) -> int:
+    """One diffusion block of 32 tokens decoded in 16 steps through a stack of MoE layers (MoE FFN only), two ways:
+    (a) every step computes all 32 rows with free top-8 routing (no caching, no limited activation);
+    (b) the paper's path: a step computes only the masked rows and the rows accepted in the previous step (Section "Delayed
+        Caching for Decoded Tokens"), classes them on the device (Eq. 4, tau_h = 0.7, L_h = 3) and routes in two rounds
+        (Algorithm 1), through team_moe_classify_tokens + team_moe_layer_forward_ex per layer.
+    The acceptance schedule is synthetic and fixed (the two most confident masked positions per step, confidences drawn with a
+    bias towards the left of the block: near-autoregressive decoding); it is input preparation, not part of the timed path."""
+    import torch
+
+    import paper_2602_08404_amd as tm
+    from paper_2602_08404_amd import inputs as gen
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    shape = gen.CFG4
+    L, H, E, k, I = shape.T, shape.H, shape.E, shape.k, shape.I
+    n_layers = args.copies if args.copies > 0 else 48
+    n_steps, tau_h, l_h = 16, 0.7, 3
+    cfg = tm.make_config(H, I, E, k, "bf16", 1, L)
+
+    def dev_t(a):
+        return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    t0 = time.time()
+    layers = []
+    for c in range(n_layers):
+        w = gen.make_weights(shape, seed=0, layer=c)
+        layers.append(({n: dev_t(a) for n, a in w.items()},
+                       [dev_t(gen.make_x(shape, seed=0, layer=c, step=st, kind=args.block_x, noise_std=0.40 if args.block_x == "structured" else 0.0552))
+                        for st in range(n_steps)]))
+        del w
+    log(f"[bench] block: generated {n_layers} layers in {time.time() - t0:.1f}s")
+    # ---- the schedule: state 0 masked, 2 accepted in the previous step (still computed), 1 decoded earlier (cached)
+    state = np.zeros(L, np.uint8)
+    sched = []
+    for st in range(n_steps):
+        conf = gen.confidences(L, seed=100 + st) ** (0.25 + 3.0 * np.arange(L) / L).astype(np.float32)
+        live = np.nonzero(state != 1)[0].astype(np.int32)
+        sched.append((torch.from_numpy(conf.astype(np.float32)).to(dev), torch.from_numpy(state.copy()).to(dev), torch.from_numpy(live).to(dev),
+                      int(live.size)))
+        state[state == 2] = 1
+        masked = np.nonzero(state == 0)[0]
+        take = masked[np.argsort(-conf[masked], kind="stable")[:2]]
+        state[take] = 2
+    ws = torch.empty(tm.team_moe_workspace_size(cfg), dtype=torch.uint8, device=dev)
+    y = torch.empty((L, H), dtype=torch.bfloat16, device=dev)
+    cls = torch.zeros((L,), dtype=torch.uint8, device=dev)
+    e_a = torch.zeros((E,), dtype=torch.uint8, device=dev)
+    n_a = torch.zeros((n_steps * n_layers,), dtype=torch.int32, device=dev)
+
+    def block_all_rows():
+        for st in range(n_steps):
+            for d_w, xs in layers:
+                tm.team_moe_layer_forward(cfg, xs[st], L, d_w["router"], d_w["gate"], d_w["up"], d_w["down"], None, y, ws)
+
+    def block_team():
+        for st in range(n_steps):
+            conf, state_d, live, n_live = sched[st]
+            tm.team_moe_classify_tokens(conf, state_d, L, L, live, n_live, tau_h, l_h, cls)
+            for li, (d_w, xs) in enumerate(layers):
+                tm.team_moe_layer_forward_ex(cfg, xs[st], y, n_live, d_w["router"], d_w["gate"], d_w["up"], d_w["down"], ws, row_index=live,
+                                             n_rows=L, token_class=cls, activated_mask_out=e_a,
+                                             n_activated_out=n_a[st * n_layers + li: st * n_layers + li + 1])
+
+    def timed(fn, n):
+        fn()
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t_begin) / n
+
+    reps = max(1, args.steps // 100)
+    s_all, s_team = timed(block_all_rows, reps), timed(block_team, reps)
+    apf = n_a.cpu().numpy().reshape(n_steps, n_layers)
+    live_counts = [c[3] for c in sched]
+    log(f"[bench] block of {L} tokens, {n_steps} steps, {n_layers} layers: all rows + free routing {s_all * 1e3:.2f} ms; "
+        f"live rows + two-round routing {s_team * 1e3:.2f} ms ({s_all / s_team:.2f}x); activated experts per layer call {apf.mean():.1f}")
+    out = {"metric": "moe_layer_tokens_per_s", "value": L / s_team, "unit": "tokens/s", "n_gpus": 1, "steps": reps, "warmup": 1,
+           "ms_per_step": s_team * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"block: one {L}-token block decoded in {n_steps} steps through {n_layers} cfg2-shaped MoE layers; a step of "
+                                  "this line is the whole block (classification + two-round routing over the live rows, every layer, every step)",
+                      "tokens": L, "layers": n_layers, "denoising_steps": n_steps, "tau_h": tau_h, "L_h": l_h, "hidden_states": args.block_x},
+           "roofline": None, "cpu_baseline": None,
+           "block": {"ms_all_rows_free_routing": s_all * 1e3, "ms_live_rows_two_round": s_team * 1e3, "speedup": s_all / s_team,
+                     "live_rows_per_step": live_counts, "activated_per_layer_call_mean": float(apf.mean()),
+                     "activated_per_step_mean": [float(v) for v in apf.mean(axis=1)],
+                     "us_per_layer_call_all_rows": s_all * 1e6 / (n_steps * n_layers),
+                     "us_per_layer_call_team": s_team * 1e6 / (n_steps * n_layers)}}
+    print(json.dumps(out), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg5"], default="cfg2")
+    ap.add_argument("--workload", choices=["cfg2", "cfg3", "cfg4", "cfg5", "block"], default="cfg2")
     ap.add_argument("--copies", type=int, default=0, help="distinct weight sets rotated over (default 4; cfg4: layers of the stack, default 48)")
     ap.add_argument("--masks", type=str, default="",
                     help="activated-set sizes of the sweep (the headline size is always measured); e.g. --masks 32 for a profile of the headline only")
     ap.add_argument("--w8", action="store_true",
                     help="time the layer on 8-bit expert weights (E4M3 codes + row scales) instead of bf16 weights (not the headline)")
+    ap.add_argument("--block-x", choices=["structured", "drift"], default="structured",
+                    help="block workload: hidden states with a component shared by the rows of the block (default), or independent rows")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     args = ap.parse_args()
@@ -67,6 +166,8 @@ def main() -> int:
     from paper_2602_08404_amd import inputs as gen
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload == "block":
+        return run_block(args)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = args.workload

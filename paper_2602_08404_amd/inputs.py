@@ -194,6 +194,9 @@ def make_x(shape: MoEShape, seed: int = 0, layer: int = 0, step: int = 0, kind: 
     kind="candidates": T = C*32 rows; a shared 32-row base ~N(0,1) plus per-candidate noise of std
                        ``noise_std`` (speculative branches whose hidden states are highly similar;
                        Section "Speculative Exploration for Hot Tokens").
+    kind="structured": every row = one vector shared by the block (per layer) + per-row, per-step noise of std ``noise_std``:
+                       masked positions of a block have highly similar hidden states (Section "Spatial Consistency"; two
+                       rows have cosine similarity 1 / (1 + noise_std^2), 0.86 at 0.40).
     kind="drift":      base ~N(0,1) for the layer plus per-step noise of std ``noise_std`` (hidden states of
                        the same block at successive denoising steps; Section "Temporal Consistency").
     kind="branches":   T = 4*32 rows: a 32-row base branch and the three extra branches of Section "Aligned Token
@@ -222,6 +225,9 @@ def make_x(shape: MoEShape, seed: int = 0, layer: int = 0, step: int = 0, kind: 
         b2[p2] = new_rows[1]
         b3[p1], b3[p2] = new_rows[0], new_rows[1]
         x = np.concatenate([base, b1, b2, b3], axis=0)
+    elif kind == "structured":
+        shared = normal(seed, TAG_X_BASE, layer, 0, H).reshape(1, H)
+        x = shared + normal(seed, TAG_X_NOISE, layer, step, T * H, noise_std).reshape(T, H)
     elif kind == "drift":
         base = normal(seed, TAG_X_BASE, layer, 0, T * H).reshape(T, H)
         x = base + normal(seed, TAG_X_NOISE, layer, step, T * H, noise_std).reshape(T, H)
