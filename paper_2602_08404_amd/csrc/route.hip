@@ -13,11 +13,15 @@
 //            earlier token with the same row (hash match, then a byte-wise comparison); such a token gets an empty
 //            routing table and later the result of the earlier one (candidate branches of Section "Speculative
 //            Exploration for Hot Tokens (SEH)" repeat most rows of the base branch).
-//   two-round select : Algorithm 1 in one launch.  Workgroups are ordered first-round tokens (newly accepted and
-//            hot) before cold tokens.  A first-round workgroup selects over all experts, ORs its picks into a
-//            device-wide bit set E_A and counts itself done; a cold workgroup waits until every first-round
-//            workgroup is counted, then selects inside E_A.  Workgroups start in index order and first-round ones
-//            never wait, so a waiting workgroup can only wait for workgroups that already run.
+//   two-round select : Algorithm 1 in one launch.
+//            Calls of at most 64 tokens (one block): no workgroup depends on another.  Every workgroup rebuilds E_A itself:
+//            a wavefront finds the k picks of a first-round token with k rounds of a cross-lane maximum over the same
+//            (logit, id) keys the selection uses, four tokens at a time, which is cheaper than one exchange through memory.
+//            Larger calls: workgroups are ordered first-round tokens (newly accepted and hot) before cold tokens.  A
+//            first-round workgroup selects over all experts, ORs its picks into a device-wide bit set E_A and counts
+//            itself done; a cold workgroup waits until every first-round workgroup is counted, then selects inside E_A.
+//            Workgroups start in index order and first-round ones never wait, so a waiting workgroup can only wait for
+//            workgroups that already run.
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -168,15 +172,18 @@ struct SelectLds {
 };
 
 // Thread e ranks expert e among the candidates; on return (after a workgroup barrier) LDS holds the k selected experts in
-// slot order and the number of candidates.  Returns whether expert e is one of the selected.
+// slot order and the number of candidates.  Returns whether expert e is one of the selected.  Threads e >= SELECT_THREADS of a
+// larger workgroup only take part in the barriers (ok must be false for them).
 __device__ __forceinline__ bool select_rank(SelectLds& sm, float v, bool ok, int e, int E, int k) {
     const int lane = e & (WAVE - 1);
     const unsigned long long my_key = ok ? select_key(v, e) : 0ull;
     if (e < 16) { sm.sel_idx[e] = -1; sm.sel_logit[e] = 0.f; }
-    sm.all[e] = e < E ? v : -INFINITY;
-    sm.key[e] = my_key;
-    const unsigned long long ok_lanes = __ballot(ok);
-    if (lane == 0) sm.count[e / WAVE] = __popcll(ok_lanes);
+    if (e < SELECT_THREADS) {
+        sm.all[e] = e < E ? v : -INFINITY;
+        sm.key[e] = my_key;
+        const unsigned long long ok_lanes = __ballot(ok);
+        if (lane == 0) sm.count[e / WAVE] = __popcll(ok_lanes);
+    }
     __syncthreads();
     bool selected = false;
     if (ok) {                                                         // rank = number of candidates that beat this one
@@ -391,6 +398,82 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_two_round_kernel(
     if (e < WAVE) write_gates(sm, t, e, E, k, renormalize, topk_idx, topk_gate);
 }
 
+// ---- two-round routing for calls of at most LOCAL_2R_MAX_TOKENS tokens: E_A is rebuilt by every workgroup -------------------
+constexpr int LOCAL_2R_MAX_TOKENS = 64;
+constexpr int LOCAL_2R_THREADS = 1024;                 // 16 wavefronts share the first-round tokens; the first 4 then select
+
+__global__ __launch_bounds__(LOCAL_2R_THREADS) void route_select_two_round_local_kernel(const float* __restrict__ logits,
+                                                                                        const uint8_t* __restrict__ token_class,
+                                                                                        uint8_t* __restrict__ mask_out,
+                                                                                        int32_t* __restrict__ n_activated_out,
+                                                                                        int32_t* __restrict__ topk_idx,
+                                                                                        float* __restrict__ topk_gate, int T, int E, int k,
+                                                                                        int renormalize, CtrlZero ctrl) {
+    __shared__ SelectLds sm;
+    __shared__ uint32_t s_bits[TWO_ROUND_MASK_WORDS];
+    const int t = blockIdx.x;
+    const int e = threadIdx.x;
+    const int lane = e & (WAVE - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(e / WAVE);
+    if (ctrl.words && t == 0 && e < SELECT_THREADS) clear_ffn_ctrl(ctrl, e, E);
+    if (e < TWO_ROUND_MASK_WORDS) s_bits[e] = 0u;
+    // one memory round trip: the token classes (every wavefront builds the bit set of first-round tokens for itself) and
+    // this token's own logits
+    const bool lane_first = lane < T && token_class[lane] != 0;
+    float v = 0.f;
+    if (e < E) v = logits[(size_t)t * E + e] + 0.f;
+    const unsigned long long first_set = __ballot(lane_first);
+    const int n_first = __popcll(first_set);
+    const bool is_first = (first_set >> t) & 1ull;
+    __syncthreads();                                   // s_bits is cleared
+    // ---- E_A = union of the picks of the first-round tokens.  Needed by cold tokens, and by workgroup 0 for the outputs.
+    // Wavefront w takes the w-th, (w+16)-th, ... first-round token: k rounds of a cross-lane maximum over the selection keys.
+    if (!is_first || t == 0) {
+        unsigned long long rest = first_set;
+        for (int i = 0; i < wave; ++i) rest &= rest - 1ull;                       // drop the tokens of lower wavefronts
+        for (int j = wave; j < n_first; j += LOCAL_2R_THREADS / WAVE) {
+            const int tok = __builtin_ctzll(rest);
+            for (int i = 0; i < LOCAL_2R_THREADS / WAVE; ++i) rest &= rest - 1ull;
+            const float* row = logits + (size_t)tok * E;
+            unsigned long long key[MAX_E / WAVE];        // expert lane + 64 i
+#pragma unroll
+            for (int i = 0; i < MAX_E / WAVE; ++i) {
+                const int ex = lane + WAVE * i;
+                const float lv = ex < E ? row[ex] + 0.f : 0.f;
+                key[i] = (ex < E && lv == lv) ? select_key(lv, ex) : 0ull;
+            }
+            for (int r = 0; r < k; ++r) {
+                unsigned long long mine = key[0];
+#pragma unroll
+                for (int i = 1; i < MAX_E / WAVE; ++i) mine = key[i] > mine ? key[i] : mine;
+                const unsigned long long best = wave_max_u64(mine);
+                if (best == 0ull) break;                 // fewer than k experts with a usable logit
+                if (mine == best) {                      // keys are distinct: exactly one lane, one of its slots
+                    const int ex = (int)(0xffffffffu - (uint32_t)best);
+                    atomicOr(&s_bits[ex >> 5], 1u << (ex & 31));
+#pragma unroll
+                    for (int i = 0; i < MAX_E / WAVE; ++i)
+                        if (key[i] == best) key[i] = 0ull;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    if (t == 0) {
+        if (mask_out && e < E) mask_out[e] = (uint8_t)((s_bits[e >> 5] >> (e & 31)) & 1u);
+        if (n_activated_out && e == 0) {
+            int n = 0;
+#pragma unroll
+            for (int w = 0; w < TWO_ROUND_MASK_WORDS; ++w) n += __popc(s_bits[w]);
+            *n_activated_out = n;
+        }
+    }
+    // ---- this token's own selection: over all experts (first round) or inside E_A (cold)
+    const bool ok = e < E && v == v && (is_first || ((s_bits[e >> 5] >> (e & 31)) & 1u));
+    select_rank(sm, v, ok, e, E, k);
+    if (e < WAVE) write_gates(sm, t, e, E, k, renormalize, topk_idx, topk_gate);
+}
+
 static hipError_t launch_logits(const Dims& d, const void* x, const void* w_router, float* logits, uint32_t* zero_words, int n_zero,
                                 hipStream_t s, unsigned long long* row_hash = nullptr) {
     dim3 grid((d.E + LOGIT_GROUP - 1) / LOGIT_GROUP, d.T), block(LOGIT_THREADS);
@@ -419,6 +502,13 @@ hipError_t launch_route_two_round(const Dims& d, const void* x, const void* w_ro
                                   CtrlZero ctrl, hipStream_t s) {
     if (d.T > MAX_TOKENS_2R || d.E > 32 * TWO_ROUND_MASK_WORDS) return hipErrorInvalidValue;
     uint32_t* words = (uint32_t*)state;                 // [0..7] bit set E_A, [16] arrivals, [32] error flag
+    if (d.T <= LOCAL_2R_MAX_TOKENS) {                   // one block: every workgroup rebuilds E_A itself, nothing is exchanged
+        hipError_t err = launch_logits(d, x, w_router, logits, nullptr, 0, s);
+        if (err != hipSuccess) return err;
+        hipLaunchKernelGGL(route_select_two_round_local_kernel, dim3(d.T), dim3(LOCAL_2R_THREADS), 0, s, logits, token_class, mask_out,
+                           n_activated_out, topk_idx, topk_gate, d.T, d.E, d.k, d.renormalize, ctrl);
+        return hipGetLastError();
+    }
     hipError_t err = launch_logits(d, x, w_router, logits, words, TWO_ROUND_STATE_WORDS, s);
     if (err != hipSuccess) return err;
     TwoRound tr;
