@@ -383,7 +383,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         __syncthreads();
         const int total_rows = s_off[E];
         if (n_act > 0 && (long long)total_rows >= (long long)tiled_min_avg_rows * n_act) {
-            tiled::ffn_tiled_body<tiled::RING_STAGES>(s_mem, s_slot_e, s_off, n_act, x, sorted_token, (const uint16_t*)wg, (const uint16_t*)wu,
+            tiled::ffn_tiled_body<tiled::RING_STAGES, tiled::X_AHEAD>(s_mem, s_slot_e, s_off, lds_tokens ? s_sorted : nullptr, n_act, x, sorted_token, (const uint16_t*)wg, (const uint16_t*)wu,
                                                       (const uint16_t*)wd, h, out, ctrl, T, E, H, I, spin_limit);
             return;
         }

@@ -3,28 +3,36 @@
 // ffn_bf16_kernel.hip; the persistent kernel switches to this body when the call averages many rows per expert.
 //
 // Same work decomposition, same per-expert h hand-over and same deterministic results as ffn_bf16_kernel.hip,
-// but both operands stream through LDS in a software pipeline instead of keeping the token operand in
-// registers: with more than 32 rows per expert the register-resident operand has to be re-gathered for every
-// item, and that gather (16 bytes per lane, rows 4 KB apart) costs more than the weights it is used with.
+// but the token operand is not kept in registers across items: with more than 32 rows per expert it would have to
+// be re-gathered for every item, with the weight stream standing still meanwhile.  Here both operands are
+// software-pipelined:
 //
 //   item     gate/up: (expert, 16 intermediate indices) = 16 rows of w_gate + 16 rows of w_up, all H columns
 //            down   : (expert, 32 output rows of w_down), all I columns
+//   segment  up to TILES consecutive items of a workgroup's share that belong to one expert, worked on together: the token
+//            rows are fetched once per segment, not once per item (that traffic, from L2, is otherwise twice the weights')
 //   pass     64 token rows of the expert (4 token tiles, one per wavefront); experts with more rows take
 //            several passes over the same weight rows (served by the caches after the first pass)
-//   stage    64 reduction columns: 32 weight rows x 128 B (4 KB) + 64 token rows x 128 B (8 KB)
-// A ring of D stages lives in LDS.  Every wavefront issues three 1 KB direct-to-LDS loads per stage (8 weight
-// rows, and the two halves of its own token tile), D-1 stages ahead of the stage being multiplied, so weight
-// bytes are in flight all the time, also across item boundaries.  A wavefront owns a token tile and
-// multiplies it with both 16-row weight tiles: no reduction across wavefronts, sums in a fixed order.
+//   stage    64 reduction columns of a segment: 32 weight rows x 128 B = 4 KB per item
+// Weights: a ring of RING_STAGES stages in LDS; every wavefront issues one 1 KB direct-to-LDS load per item and stage (8
+// weight rows), RING_STAGES-1 stages (up to 48 KB per workgroup) ahead of the stage being multiplied, also across segment
+// boundaries.  Tokens: a
+// wavefront owns a token tile and loads its own MFMA operand of a stage (16 bytes per lane and K-step, straight from the
+// L2-resident x or h rows) into registers, X_AHEAD stages ahead.  It multiplies the tile with both 16-row weight tiles of
+// every item of the segment: no reduction across wavefronts, sums in a fixed order.
 //
 // LDS stage layout: rows of 128 B (8 chunks of 16 B); chunk c of row r is stored at chunk c ^ ((r >> 1) & 7),
 // which spreads the 16 rows of an MFMA operand read over all 16 bank groups.  The swizzle is applied to the
 // global address a lane fetches, because a direct-to-LDS load writes the lanes of a wavefront contiguously.
 //
-// The loop counts its own outstanding loads (s_waitcnt vmcnt(N) with a constant N per wavefront) and reads LDS
-// with explicit instructions: the compiler's automatic waits treat every direct-to-LDS load as aliasing every
-// LDS read and would drain the pipeline at each stage.
+// The loop issues all of its loads as explicit instructions, counts them, and waits with s_waitcnt vmcnt(N), N = the
+// loads issued after the ones a stage needs (loads complete in issue order); it reads LDS with explicit instructions too.
+// The compiler cannot do this: it turns every wait for an ordinary load into a wait for all loads while a direct-to-LDS
+// load it knows of is in flight, treats such loads as aliasing every LDS read, and gives up counting across a loop's back edge.
 #pragma once
+#include <type_traits>
+#include <utility>
+
 #include "ffn_bf16.hpp"
 
 namespace team {
@@ -36,9 +44,8 @@ constexpr int MT = 64;                 // token rows per pass
 constexpr int W_ROWS = 32;             // weight rows per item
 constexpr int ROW_BYTES = KC * 2;      // 128
 constexpr int W_BYTES = W_ROWS * ROW_BYTES;
-constexpr int X_BYTES = MT * ROW_BYTES;
-constexpr int STAGE_BYTES = W_BYTES + X_BYTES;
-constexpr int LOADS_PER_STAGE = 3;     // per wavefront
+constexpr int TILES = 4;               // items of a segment (measured: 2 and 3 are slower, 6 is no faster)
+constexpr int STAGE_BYTES = TILES * W_BYTES;   // only the weights pass through LDS
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -46,6 +53,32 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 template <int AUX>
 __device__ __forceinline__ void slab_load(const void* gsrc, char* lds_base_uniform) {
     __builtin_amdgcn_global_load_lds((gptr_t)gsrc, (lptr_t)lds_base_uniform, 16, 0, AUX);
+}
+// Streaming (non-temporal) direct-to-LDS load: M0 holds the LDS address; one idle cycle between writing M0 and the load that
+// reads it; M0 is restored, as the compiler does not expect it to change.
+__device__ __forceinline__ void slab_load_stream_explicit(const void* gsrc, uint32_t lds_addr_uniform) {
+    uint32_t saved_m0;
+    lds_addr_uniform = __builtin_amdgcn_readfirstlane(lds_addr_uniform);   // (a scalar register also where the compiler cannot prove uniformity)
+    asm volatile(
+        "s_mov_b32 %0, m0\n\t"
+        "s_mov_b32 m0, %2\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %1, off nt\n\t"
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0"
+        : "=&s"(saved_m0)
+        : "v"(gsrc), "s"(lds_addr_uniform)
+        : "memory");
+}
+// 16 bytes per lane into registers, asynchronously: `dst` is only valid after a wait for at most N outstanding loads with N = the
+// loads issued since.  Until then the compiler believes the value is there already, so nothing may touch it: its only use is as an operand
+// of the matrix instructions, which depend on the LDS reads that follow that wait (explicit statements keep their order).  A
+// copy of such a register in the generated code would read it too early; tests/test_generated_code.py looks for that.
+// DEVICE: device-scope load (h written by other workgroups of this launch).
+template <bool DEVICE, int BYTE_OFFSET>
+__device__ __forceinline__ void request_tokens(bf16x8_t& dst, const uint16_t* p) {
+    if constexpr (DEVICE) asm volatile("global_load_dwordx4 %0, %1, off offset:%2 sc1" : "=v"(dst) : "v"(p), "n"(BYTE_OFFSET) : "memory");
+    else asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(dst) : "v"(p), "n"(BYTE_OFFSET) : "memory");
 }
 constexpr int AUX_NONE = 0;
 constexpr int AUX_STREAM = 2;          // nt: read once, do not displace the small reused data (tokens, h, out) from L2
@@ -58,47 +91,81 @@ __device__ __forceinline__ void wait_outstanding() {
 __device__ __forceinline__ void wg_barrier() {
     asm volatile("s_barrier" ::: "memory");
 }
-// Three 16-byte LDS reads (two weight tiles, one token tile) at byte addresses a0, a1, a2.
-__device__ __forceinline__ void lds_read3(uint32_t a0, uint32_t a1, uint32_t a2, bf16x8_t& w0, bf16x8_t& w1, bf16x8_t& xt) {
-    asm volatile(
-        "ds_read_b128 %0, %3\n\t"
-        "ds_read_b128 %1, %4\n\t"
-        "ds_read_b128 %2, %5\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "=&v"(w0), "=&v"(w1), "=&v"(xt)
-        : "v"(a0), "v"(a1), "v"(a2)
-        : "memory");
-}
 __device__ __forceinline__ void store_coherent(uint32_t* p, uint32_t v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
     return (uint32_t)(uintptr_t)(lptr_t)p;
 }
-// One 32-bit LDS read at byte address a (explicit for the same reason as lds_read3).
+__device__ __forceinline__ int lds_read_u16(uint32_t a) {
+    int v;
+    asm volatile("ds_read_u16 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
+    return v;
+}
+// One 32-bit LDS read at byte address a.
 __device__ __forceinline__ int lds_read_i32(uint32_t a) {
     int v;
     asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(a) : "memory");
     return v;
 }
 
-struct Seg {                   // one (item, pass) of a workgroup's share
-    int li;                    // item index in the expert-major list of the phase
+// f(integral_constant<int, 0>), f(<1>), ... in turn, until one returns false.
+template <class F, int... U>
+__device__ __forceinline__ void for_each_slot(F&& f, std::integer_sequence<int, U...>) {
+    (void)(f(std::integral_constant<int, U>{}) && ...);
+}
+
+struct Seg {                   // one (segment, pass) of a workgroup's share
+    int li;                    // first item of the segment in the expert-major list of the phase
+    int nw;                    // items in the segment (1..TILES)
     int a, it, e, r0, m, pass;
     bool valid;
 };
 
-constexpr int RING_STAGES = 6;
+constexpr int RING_STAGES = 4;
 constexpr int RING_BYTES = RING_STAGES * STAGE_BYTES;
+constexpr int X_AHEAD = 4;
+constexpr int MAX_COUNTED = 24;        // largest wait count used: (RING_STAGES - 1) stages of TILES + 2 loads, rounded up
+
+// Waits until at most n vector-memory operations of this wavefront are outstanding (n uniform; above MAX_COUNTED: until none).
+__device__ __forceinline__ void wait_outstanding_rt(int n) {
+#define TEAM_WAIT_CASE(N) \
+    case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
+    switch (n) {
+        TEAM_WAIT_CASE(1) TEAM_WAIT_CASE(2) TEAM_WAIT_CASE(3) TEAM_WAIT_CASE(4) TEAM_WAIT_CASE(5) TEAM_WAIT_CASE(6)
+        TEAM_WAIT_CASE(7) TEAM_WAIT_CASE(8) TEAM_WAIT_CASE(9) TEAM_WAIT_CASE(10) TEAM_WAIT_CASE(11) TEAM_WAIT_CASE(12)
+        TEAM_WAIT_CASE(13) TEAM_WAIT_CASE(14) TEAM_WAIT_CASE(15) TEAM_WAIT_CASE(16) TEAM_WAIT_CASE(17) TEAM_WAIT_CASE(18)
+        TEAM_WAIT_CASE(19) TEAM_WAIT_CASE(20) TEAM_WAIT_CASE(21) TEAM_WAIT_CASE(22) TEAM_WAIT_CASE(23) TEAM_WAIT_CASE(24)
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    }
+#undef TEAM_WAIT_CASE
+}
+// The four weight operands of an item's stage (two 16-row tiles x two K-steps) at byte addresses a0..a3.
+__device__ __forceinline__ void lds_read4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3, bf16x8_t& w0, bf16x8_t& w1, bf16x8_t& w2,
+                                          bf16x8_t& w3) {
+    asm volatile(
+        "ds_read_b128 %0, %4\n\t"
+        "ds_read_b128 %1, %5\n\t"
+        "ds_read_b128 %2, %6\n\t"
+        "ds_read_b128 %3, %7\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(w0), "=&v"(w1), "=&v"(w2), "=&v"(w3)
+        : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+        : "memory");
+}
 
 // Body of the streaming variant; runs inside the persistent FFN kernel (all workgroups take it or none does).
-// s_ring: RING_BYTES of LDS, 1 KB aligned; s_slot_e / s_off: the kernel's tables (active list, clipped offsets).
-template <int D>
-__device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_slot_e, const int32_t* s_off, int n_act,
+// s_ring: RING_BYTES of LDS, 1 KB aligned; s_slot_e / s_off: the kernel's tables (active list, clipped offsets); s_sorted: its
+// LDS copy of the grouped token list (0xffff: no token), or null when the list did not fit.
+template <int DW, int DX>
+__device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_slot_e, const int32_t* s_off, const uint16_t* s_sorted, int n_act,
                                                const uint16_t* __restrict__ x, const int32_t* __restrict__ sorted_token,
                                                const uint16_t* __restrict__ wg, const uint16_t* __restrict__ wu,
                                                const uint16_t* __restrict__ wd, uint16_t* __restrict__ h, float* __restrict__ out,
                                                FfnCtrl* __restrict__ ctrl, int T, int E, int H, int I, int spin_limit) {
+    // The tokens of a stage are requested before its weights (DX >= DW), so "everything up to the weights of the stage" is
+    // what a stage waits for.
+    static_assert(DX >= DW && (DW - 1) * (TILES + 2) <= MAX_COUNTED, "token requests lead the weight requests; wait counts fit");
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -107,36 +174,35 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
     const int tiles_a = I / 16, tiles_b = H / W_ROWS;
 
     // ---- lane constants
-    // loads: lane fetches row (l / 8) of an 8-row slab, stored chunk (l % 8)
+    // weight loads: lane fetches row (l / 8) of an 8-row slab, stored chunk (l % 8)
     const int ld_row = lane >> 3, ld_cs = lane & 7;
-    // reads: MFMA operand row n, chunk 4*ks + q, un-swizzled on the fly
+    // weight reads: MFMA operand row n of tile rt, chunk 4*ks + q, un-swizzled on the fly
     const uint32_t ring0 = lds_addr(s_ring);
     const uint32_t tab_e = lds_addr(s_slot_e), tab_off = lds_addr(s_off);
-    uint32_t rd_w[2][2], rd_x[2];
+    uint32_t rd_w[2][2];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt) {
             const int r = 16 * rt + n;
             rd_w[rt][ks] = r * ROW_BYTES + (((4 * ks + q) ^ ((r >> 1) & 7)) << 4);
         }
-        const int r = 16 * wave + n;
-        rd_x[ks] = W_BYTES + r * ROW_BYTES + (((4 * ks + q) ^ ((r >> 1) & 7)) << 4);
-    }
 
     for (int phase = 0; phase < 2; ++phase) {
         const int tiles = phase == 0 ? tiles_a : tiles_b;
-        const int nks = (phase == 0 ? H : I) / KC;                 // stages per (item, pass)
+        const int nks = (phase == 0 ? H : I) / KC;                 // stages per (segment, pass)
         const long long total = (long long)n_act * tiles;
         // contiguous shares; the remainder goes to the lowest-numbered workgroups (see the register-operand body)
         const int share = (int)(total / G), extra = (int)(total % G), bx = (int)blockIdx.x;
         const int li_begin = bx * share + min(bx, extra), li_end = li_begin + share + (bx < extra ? 1 : 0);
+        const size_t tile_stride = phase == 0 ? (size_t)16 * H : (size_t)W_ROWS * I;   // elements between the weight rows of adjacent items
 
-        auto load_item = [&](Seg& s) {                              // fills a, it, e, r0, m of item s.li; skips items without rows
+        auto load_seg = [&](Seg& s) {                               // segment that starts at item s.li; skips experts without rows
             s.valid = false;
             while (s.li < li_end) {
                 s.a = s.li / tiles;
                 s.it = s.li - s.a * tiles;
+                s.nw = min(min(TILES, li_end - s.li), tiles - s.it);
                 s.e = __builtin_amdgcn_readfirstlane(lds_read_i32(tab_e + 4 * s.a));
                 const bool ok = s.e >= 0 && s.e < E;
                 s.r0 = ok ? __builtin_amdgcn_readfirstlane(lds_read_i32(tab_off + 4 * s.e)) : 0;
@@ -146,46 +212,68 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                     s.valid = true;
                     return;
                 }
-                ++s.li;
+                s.li += s.nw;
             }
         };
         auto next_seg = [&](Seg& s) {
             if ((s.pass + 1) * MT < s.m) {
                 ++s.pass;
             } else {
-                ++s.li;
-                load_item(s);
+                s.li += s.nw;
+                load_seg(s);
             }
         };
 
-        // ---------------------------------------------------------------- producer: per-lane source pointers of the three slabs
-        Seg ps;
-        ps.li = li_begin;
-        load_item(ps);
-        int p_ks = 0;
-        int p_issued = 0;                 // stages issued so far in this phase
-        const uint16_t* src_w = nullptr;  // weight slab: rows 8*wave .. 8*wave+7 of the item
-        const uint16_t* src_x0 = nullptr; // token slabs: rows 16*wave .. +7 and +8 .. +15 of the pass
-        const uint16_t* src_x1 = nullptr;
-        int p_key = -1;                   // (slot, pass) the token pointers were built for
-        int ready_slot = -1;              // down phase: slot whose h is known to be complete
+        int issued = 0;                   // vector-memory loads this wavefront has issued in this phase
 
-        auto producer_enter = [&]() {     // new (item, pass): rebuild the source pointers (uniform control flow)
+        // ---------------------------------------------------------------- weight producer: one 1 KB slab per item and stage
+        Seg pw;
+        pw.li = li_begin;
+        load_seg(pw);
+        int pw_ks = 0, w_issued = 0;
+        const uint16_t* src_w = nullptr;  // rows 8*wave .. 8*wave+7 of the segment's first item
+        int mark_w[DW];                   // `issued` right after the weight requests of the stage in that ring slot
+        auto pw_enter = [&]() {
             const int r = 8 * wave + ld_row;                       // weight row of the item this lane fetches
             const int c = ld_cs ^ ((r >> 1) & 7);                  // global chunk that belongs at the stored chunk
             if (phase == 0) {
                 const int i = r & 15;
-                const int iidx = ps.it * 16 + (r >> 4) * 8 + 2 * (i >> 2) + (i & 1);   // rows 4q+{0,1}: gate, 4q+{2,3}: up
+                const int iidx = pw.it * 16 + (r >> 4) * 8 + 2 * (i >> 2) + (i & 1);   // rows 4q+{0,1}: gate, 4q+{2,3}: up
                 const uint16_t* mat = (i & 2) ? wu : wg;
-                src_w = mat + ((size_t)ps.e * I + iidx) * H + c * 8;
+                src_w = mat + ((size_t)pw.e * I + iidx) * H + c * 8;
             } else {
-                src_w = wd + ((size_t)ps.e * H + (size_t)ps.it * W_ROWS + r) * I + c * 8;
+                src_w = wd + ((size_t)pw.e * H + (size_t)pw.it * W_ROWS + r) * I + c * 8;
             }
-            const int key = ps.a * 64 + ps.pass;
-            if (phase == 1 && ps.a != ready_slot) {                // wait until every gate/up item of this expert has published h
+        };
+        auto produce_w = [&](int& slot_mark) {                      // (only while pw.valid)
+            const uint32_t dst = ring0 + (w_issued % DW) * STAGE_BYTES + wave * 8 * ROW_BYTES;
+            const uint16_t* p = src_w + pw_ks * KC;
+#pragma unroll
+            for (int t = 0; t < TILES; ++t)
+                if (t < pw.nw) slab_load_stream_explicit(p + t * tile_stride, dst + t * W_BYTES);
+            issued += pw.nw;
+            slot_mark = issued;
+            ++w_issued;
+            if (++pw_ks == nks) {
+                pw_ks = 0;
+                next_seg(pw);
+                if (pw.valid) pw_enter();
+            }
+        };
+
+        // ---------------------------------------------------------------- token producer: this lane's operand of a stage, in registers
+        Seg px;
+        px.li = li_begin;
+        load_seg(px);
+        int px_ks = 0;
+        const uint16_t* src_x = nullptr;  // row 16*wave + n of the pass, columns 8*q ..
+        int px_key = -1;                  // (slot, pass) src_x was built for
+        int ready_slot = -1;              // down phase: slot whose h is known to be complete
+        auto px_enter = [&]() {           // new (segment, pass): uniform control flow
+            if (phase == 1 && px.a != ready_slot) {                // wait until every gate/up item of this expert has published h
                 if (tid == 0) {
                     int spins = 0;
-                    while (__hip_atomic_load(&ctrl->done[ps.a][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < tiles_a) {
+                    while (__hip_atomic_load(&ctrl->done[px.a][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < tiles_a) {
                         __builtin_amdgcn_s_sleep(8);
                         if (++spins > spin_limit) {                  // cannot happen with a control block zeroed before the launch
                             ctrl->error = 1;
@@ -194,119 +282,146 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                     }
                 }
                 wg_barrier();
-                ready_slot = ps.a;
+                ready_slot = px.a;
             }
-            if (key != p_key) {
-                p_key = key;
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int tr = 16 * wave + 8 * j + ld_row;     // token row of the pass
-                    const int cx = ld_cs ^ ((tr >> 1) & 7);
-                    int row = ps.pass * MT + tr;
-                    if (row >= ps.m) row = ps.pass * MT;           // rows beyond the expert's last: fetch a valid row, result unused
-                    const uint16_t* p;
-                    if (phase == 0) {
-                        int tok = sorted_token[ps.r0 + row];
-                        tok = min(max(tok, 0), T - 1);
-                        p = x + (size_t)tok * H + cx * 8;
-                    } else {
-                        p = h + (size_t)(ps.r0 + row) * I + cx * 8;
-                    }
-                    if (j == 0) src_x0 = p; else src_x1 = p;
+            const int key = px.a * 64 + px.pass;
+            if (key != px_key) {
+                px_key = key;
+                int row = px.pass * MT + 16 * wave + n;
+                if (row >= px.m) row = px.pass * MT;               // rows beyond the expert's last: a valid row, result unused
+                if (phase == 0) {
+                    // (from the kernel's LDS copy when there is one; a load from global memory waits for every load in flight)
+                    int tok = s_sorted ? lds_read_u16(lds_addr(s_sorted) + 2 * (px.r0 + row)) : sorted_token[px.r0 + row];
+                    tok = min(max(tok, 0), T - 1);
+                    src_x = x + (size_t)tok * H + q * 8;
+                } else {
+                    src_x = h + (size_t)(px.r0 + row) * I + q * 8;
                 }
             }
         };
-        auto produce_stage = [&]() {      // issue the three loads of the producer's current stage, then advance it
-            char* slot = s_ring + (p_issued % D) * STAGE_BYTES;
-            const int koff = p_ks * KC;
-            slab_load<AUX_STREAM>(src_w + koff, slot + wave * 8 * ROW_BYTES);
+        bf16x8_t xq[DX][2];               // token operands of the next DX stages
+        auto produce_x = [&](bf16x8_t (&dst)[2]) {                  // (only while px.valid)
+            const uint16_t* p = src_x + px_ks * KC;
             if (phase == 0) {
-                slab_load<AUX_NONE>(src_x0 + koff, slot + W_BYTES + (16 * wave) * ROW_BYTES);
-                slab_load<AUX_NONE>(src_x1 + koff, slot + W_BYTES + (16 * wave + 8) * ROW_BYTES);
+                request_tokens<false, 0>(dst[0], p);
+                request_tokens<false, 64>(dst[1], p);
             } else {
-                slab_load<AUX_DEVICE_SCOPE>(src_x0 + koff, slot + W_BYTES + (16 * wave) * ROW_BYTES);
-                slab_load<AUX_DEVICE_SCOPE>(src_x1 + koff, slot + W_BYTES + (16 * wave + 8) * ROW_BYTES);
+                request_tokens<true, 0>(dst[0], p);
+                request_tokens<true, 64>(dst[1], p);
             }
-            ++p_issued;
-            if (++p_ks == nks) {
-                p_ks = 0;
-                next_seg(ps);
-                if (ps.valid) producer_enter();
+            issued += 2;
+            if (++px_ks == nks) {
+                px_ks = 0;
+                next_seg(px);
+                if (px.valid) px_enter();
             }
         };
 
         // ---------------------------------------------------------------- consumer
         Seg cs;
         cs.li = li_begin;
-        load_item(cs);
+        load_seg(cs);
         int c_ks = 0, c_done = 0;         // stage inside the segment; stages consumed so far in this phase
         int pend = 0;                     // finished gate/up items of the current run (one slot) not yet published
-        int pub_slot = -1, pub_cnt = 0, pub_at = 0;   // run whose publication waits for its h stores to be acknowledged
-        f32x4_t acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        int pub_slot = -1, pub_cnt = 0, pub_mark = 0;   // run whose publication waits for its h stores to be acknowledged
+        f32x4_t acc[TILES][2];
+#pragma unroll
+        for (int t = 0; t < TILES; ++t) acc[t][0] = acc[t][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-        if (ps.valid) producer_enter();
-        for (int i = 0; i < D - 1 && ps.valid; ++i) produce_stage();
+        // Requests in front of the loop: the weights of the first DW - 1 stages (they do not depend on other workgroups), then
+        // the tokens of the first DX stages (in the down phase: once the expert's h is complete).  These first stages wait for
+        // all of it; inside the loop the tokens of a stage are always requested before its weights.
+        if (pw.valid) pw_enter();
+#pragma unroll
+        for (int i = 0; i < DW; ++i) mark_w[i] = 0;
+#pragma unroll
+        for (int i = 0; i < DW - 1; ++i)
+            if (pw.valid) produce_w(mark_w[i]);
+        if (px.valid) px_enter();
+#pragma unroll
+        for (int u = 0; u < DX; ++u)
+            if (px.valid) produce_x(xq[u]);
+#pragma unroll
+        for (int i = 0; i < DW - 1; ++i) mark_w[i] = issued;
 
         while (cs.valid) {
-            // (1) this stage's loads have landed: all but the loads of the D-2 stages issued after it
-            if (p_issued - c_done - 1 == D - 2) wait_outstanding<LOADS_PER_STAGE*(D - 2)>(); else wait_outstanding<0>();
-            wg_barrier();
-            // (2) a run of gate/up items whose h stores are D-1 stages old is complete in every wavefront: publish it
-            if (pub_slot >= 0 && c_done >= pub_at) {
-                if (tid == 0) __hip_atomic_fetch_add(&ctrl->done[pub_slot][0], pub_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                pub_slot = -1;
-            }
-            // (3) refill the slot that the previous iteration has finished reading
-            if (ps.valid) produce_stage();
-            // (4) multiply
-            const uint32_t slot = ring0 + (c_done % D) * STAGE_BYTES;
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                bf16x8_t w0, w1, xt;
-                lds_read3(slot + rd_w[0][ks], slot + rd_w[1][ks], slot + rd_x[ks], w0, w1, xt);
-                acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, xt, acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, xt, acc[1], 0, 0, 0);
-            }
-            ++c_done;
-            if (++c_ks < nks) continue;
-            // (5) last stage of the (item, pass): epilogue for this wavefront's token tile
-            c_ks = 0;
-            const int row = cs.pass * MT + 16 * wave + n;
-            if (row < cs.m) {
-                if (phase == 0) {
-#pragma unroll
-                    for (int rt = 0; rt < 2; ++rt) {
-                        // lane holds (g_a, g_b, u_a, u_b) of intermediate indices it*16 + rt*8 + 2*q, +1 for token row `row`
-                        const float h0 = silu_f32(acc[rt][0]) * acc[rt][2];
-                        const float h1 = silu_f32(acc[rt][1]) * acc[rt][3];
-                        const uint32_t packed = f32_to_bf16_bits(h0) | (f32_to_bf16_bits(h1) << 16);
-                        store_coherent(reinterpret_cast<uint32_t*>(h + (size_t)(cs.r0 + row) * I + cs.it * 16 + rt * 8 + 2 * q), packed);
-                    }
-                } else {
-#pragma unroll
-                    for (int rt = 0; rt < 2; ++rt)   // lane holds output rows it*32 + rt*16 + 4*q + (0..3) of token row `row`
-                        *reinterpret_cast<f32x4_t*>(out + (size_t)(cs.r0 + row) * H + cs.it * W_ROWS + rt * 16 + 4 * q) = acc[rt];
+            for_each_slot([&](auto slot_index) -> bool {
+                constexpr int u = decltype(slot_index)::value;      // token registers of this stage; its ring slot is u % DW
+                static_assert(DX % DW == 0, "the ring slot of a stage follows from its token registers");
+                if (!cs.valid) return false;
+                // (1) this stage's tokens and weights have landed: everything up to the weight requests of this stage
+                wait_outstanding_rt(issued - mark_w[u % DW]);
+                wg_barrier();
+                // (2) a run of gate/up items whose h stores are older than loads that have completed is complete in every
+                //     wavefront (operations complete in issue order): publish it
+                if (pub_slot >= 0 && mark_w[u % DW] > pub_mark) {
+                    if (tid == 0) __hip_atomic_fetch_add(&ctrl->done[pub_slot][0], pub_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    pub_slot = -1;
                 }
-            }
-            acc[0] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            acc[1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            const int prev_a = cs.a, prev_li = cs.li;
-            next_seg(cs);
-            if (phase == 0 && (!cs.valid || cs.li != prev_li)) {   // the item is finished (all passes)
-                ++pend;
-                if (!cs.valid || cs.a != prev_a) {                  // and so is the run of items of this slot
-                    if (pub_slot >= 0) {                            // an older run is still waiting (only with very few stages per
-                        wait_outstanding<0>();                      // item): acknowledge everything now and publish it at once
-                        wg_barrier();
-                        if (tid == 0)
-                            __hip_atomic_fetch_add(&ctrl->done[pub_slot][0], pub_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // (3) refill the ring slot that the previous iteration has finished reading
+                if (pw.valid) produce_w(mark_w[(u + DW - 1) % DW]);
+                // (4) multiply
+                const uint32_t slot = ring0 + (u % DW) * STAGE_BYTES;
+#pragma unroll
+                for (int t = 0; t < TILES; ++t) {
+                    if (t < cs.nw) {
+                        const uint32_t wt = slot + t * W_BYTES;
+                        bf16x8_t w00, w10, w01, w11;
+                        lds_read4(wt + rd_w[0][0], wt + rd_w[1][0], wt + rd_w[0][1], wt + rd_w[1][1], w00, w10, w01, w11);
+                        acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w00, xq[u][0], acc[t][0], 0, 0, 0);
+                        acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w10, xq[u][0], acc[t][1], 0, 0, 0);
+                        acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w01, xq[u][1], acc[t][0], 0, 0, 0);
+                        acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w11, xq[u][1], acc[t][1], 0, 0, 0);
                     }
-                    pub_slot = prev_a;
-                    pub_cnt = pend;
-                    pub_at = c_done + D - 1;
-                    pend = 0;
                 }
-            }
+                ++c_done;
+                // (5) request this lane's tokens of the stage DX ahead into the registers just used
+                if (px.valid) produce_x(xq[u]);
+                if (++c_ks < nks) return true;
+                // (6) last stage of the (segment, pass): epilogue for this wavefront's token tile
+                c_ks = 0;
+                const int row = cs.pass * MT + 16 * wave + n;
+#pragma unroll
+                for (int t = 0; t < TILES; ++t) {
+                    if (t < cs.nw && row < cs.m) {
+                        const int it = cs.it + t;
+                        if (phase == 0) {
+#pragma unroll
+                            for (int rt = 0; rt < 2; ++rt) {
+                                // lane holds (g_a, g_b, u_a, u_b) of intermediate indices it*16 + rt*8 + 2*q, +1 for token row `row`
+                                const float h0 = silu_f32(acc[t][rt][0]) * acc[t][rt][2];
+                                const float h1 = silu_f32(acc[t][rt][1]) * acc[t][rt][3];
+                                const uint32_t packed = f32_to_bf16_bits(h0) | (f32_to_bf16_bits(h1) << 16);
+                                store_coherent(reinterpret_cast<uint32_t*>(h + (size_t)(cs.r0 + row) * I + it * 16 + rt * 8 + 2 * q), packed);
+                            }
+                        } else {
+#pragma unroll
+                            for (int rt = 0; rt < 2; ++rt)   // lane holds output rows it*32 + rt*16 + 4*q + (0..3) of token row `row`
+                                *reinterpret_cast<f32x4_t*>(out + (size_t)(cs.r0 + row) * H + it * W_ROWS + rt * 16 + 4 * q) = acc[t][rt];
+                        }
+                    }
+                    acc[t][0] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    acc[t][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                }
+                const int prev_a = cs.a, prev_li = cs.li, prev_nw = cs.nw;
+                next_seg(cs);
+                if (phase == 0 && (!cs.valid || cs.li != prev_li)) {   // the segment is finished (all passes)
+                    pend += prev_nw;
+                    if (!cs.valid || cs.a != prev_a) {                  // and so is the run of items of this slot
+                        if (pub_slot >= 0) {                            // an older run is still waiting (only with very few stages per
+                            wait_outstanding<0>();                      // item): acknowledge everything now and publish it at once
+                            wg_barrier();
+                            if (tid == 0)
+                                __hip_atomic_fetch_add(&ctrl->done[pub_slot][0], pub_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+                        pub_slot = prev_a;
+                        pub_cnt = pend;
+                        pub_mark = issued;
+                        pend = 0;
+                    }
+                }
+                return true;
+            }, std::make_integer_sequence<int, DX>{});
         }
         // ---- end of phase: everything this workgroup stored is acknowledged, then the last run is published
         wait_outstanding<0>();

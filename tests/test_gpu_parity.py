@@ -204,14 +204,18 @@ def test_bf16_other_shapes(H, I, E, k, T):
     say("shape", (H, I, E, k, T), hz.full_parity(case, gen.random_mask(E, max(k, E // 2), seed=2)))
 
 
+@pytest.mark.parametrize("body", ["streaming", "register operand"])
 @pytest.mark.parametrize("H,I", [(2048, 128), (2048, 256), (2048, 384), (2048, 896), (2048, 1024), (1024, 256), (512, 640), (256, 384)])
-def test_bf16_more_than_1024_routed_rows(H, I):
+def test_bf16_more_than_1024_routed_rows(H, I, body, monkeypatch):
     """T*k = 1152 routed rows: the FFN kernel then reads the grouped token list from global memory instead of
-    its LDS copy (56 activated experts keep the average below the row count at which the kernel switches to its
-    other variant).  One case per number of 128-wide blocks of I that the other tests do not reach on that path."""
+    its LDS copy, in both of its bodies.  56 activated experts give 20.6 rows per expert: the kernel picks its streaming
+    body; TEAM_MOE_FFN_TILED_ROWS (the average number of rows per expert from which it does) keeps it in the body with the
+    register-resident token operand.  One case per number of 128-wide blocks of I that the other tests do not reach."""
+    if body == "register operand":
+        monkeypatch.setenv("TEAM_MOE_FFN_TILED_ROWS", "100000")
     s = gen.MoEShape("rows1152", T=144, H=H, E=64, k=8, I=I, dtype="bf16")
     case = hz.Case.make(s, gen.make_x(s, seed=5), gen.make_weights(s, seed=5))
-    say("1152 rows", (H, I), hz.full_parity(case, gen.random_mask(64, 56, seed=5)))
+    say("1152 rows", (H, I), body, hz.full_parity(case, gen.random_mask(64, 56, seed=5)))
 
 
 def test_max_tokens_and_max_experts():
