@@ -328,21 +328,29 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
 #pragma unroll
         for (int t = 0; t < TILES; ++t) acc[t][0] = acc[t][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-        // Requests in front of the loop: the weights of the first DW - 1 stages (they do not depend on other workgroups), then
-        // the tokens of the first DX stages (in the down phase: once the expert's h is complete).  These first stages wait for
-        // all of it; inside the loop the tokens of a stage are always requested before its weights.
+        // Requests in front of the loop: the tokens of the first DX stages and the weights of the first DW - 1.  Gate/up phase:
+        // tokens first, as inside the loop.  Down phase: the weights first, because the tokens (h) have to wait for other
+        // workgroups and the weights do not; its first DW - 1 stages then wait for all of these requests.
+        if (phase == 0) {
+            if (px.valid) px_enter();
+#pragma unroll
+            for (int u = 0; u < DX; ++u)
+                if (px.valid) produce_x(xq[u]);
+        }
         if (pw.valid) pw_enter();
 #pragma unroll
         for (int i = 0; i < DW; ++i) mark_w[i] = 0;
 #pragma unroll
         for (int i = 0; i < DW - 1; ++i)
             if (pw.valid) produce_w(mark_w[i]);
-        if (px.valid) px_enter();
+        if (phase == 1) {
+            if (px.valid) px_enter();
 #pragma unroll
-        for (int u = 0; u < DX; ++u)
-            if (px.valid) produce_x(xq[u]);
+            for (int u = 0; u < DX; ++u)
+                if (px.valid) produce_x(xq[u]);
 #pragma unroll
-        for (int i = 0; i < DW - 1; ++i) mark_w[i] = issued;
+            for (int i = 0; i < DW - 1; ++i) mark_w[i] = issued;
+        }
 
         while (cs.valid) {
             for_each_slot([&](auto slot_index) -> bool {
