@@ -9,7 +9,7 @@ namespace team {
 constexpr int FFN_THREADS = 256;
 constexpr int FFN_WAVES = 4;
 constexpr int FFN_MAX_E = 256;
-constexpr int FFN_LAYER_MAX_TOKENS = 64;     // up to this many tokens (and FFN_LAYER_MAX_ROWS pairs) the kernel can group the routing table itself
+constexpr int FFN_LAYER_MAX_TOKENS = 128;    // up to this many tokens (and FFN_LAYER_MAX_ROWS pairs) the kernel can group the routing table itself
 constexpr int FFN_LAYER_MAX_ROWS = 1024;
 static_assert(FFN_THREADS == FFN_MAX_E && FFN_LAYER_MAX_ROWS % FFN_THREADS == 0, "the in-kernel grouping maps one thread to one expert");
 constexpr int FFN_DONE_STRIDE = 64;      // one counter per 256 bytes: polled counters sit in different memory channels

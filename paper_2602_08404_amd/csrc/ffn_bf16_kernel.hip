@@ -34,7 +34,7 @@
 // operands of two MFMA K-steps, which are widened to bf16 in registers (exactly), the token operand is laid out to match,
 // and the row scales multiply the fp32 sums in the epilogues.
 //
-// Two more things happen in this kernel.  (1) For small calls (at most 64 tokens) started by
+// Two more things happen in this kernel.  (1) For small calls (at most 128 tokens and 1024 routed rows) started by
 // team_moe_layer_forward, every workgroup groups the routing table itself in LDS during its prologue (the same
 // bitset / popcount / prefix-sum method as the dispatch kernel, which is then not launched).  (2) When a call
 // averages many rows per expert, all workgroups switch to the streaming body in ffn_bf16_tiled.hpp.
@@ -311,12 +311,14 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                 s_sorted[i] = (t >= 0 && t < T) ? (uint16_t)t : (uint16_t)0xffffu;
             }
     } else {
-        // ---- small calls (T <= 64, at most FFN_LAYER_MAX_ROWS pairs): every workgroup groups the routing table itself,
+        // ---- small calls (T <= FFN_LAYER_MAX_TOKENS, at most FFN_LAYER_MAX_ROWS pairs): every workgroup groups the routing table itself,
         // in LDS, instead of waiting for a separate grouping kernel.  Same method and same result as that kernel: a token
         // bitset per expert, popcount histogram, prefix sum, and the row of a pair = offset + number of lower tokens.
-        uint32_t* bits = reinterpret_cast<uint32_t*>(s_mem);                              // [E][2]
-        unsigned long long(*scan)[FFN_MAX_E] = reinterpret_cast<unsigned long long(*)[FFN_MAX_E]>(s_mem + 2 * FFN_MAX_E * 4);
-        for (int i = tid; i < 2 * E; i += FFN_THREADS) bits[i] = 0u;
+        constexpr int BW = FFN_LAYER_MAX_TOKENS / 32;                                     // words of a token bitset
+        static_assert(BW * FFN_MAX_E * 4 + 2 * FFN_MAX_E * 8 <= LDS_BYTES, "prologue tables fit the weight area");
+        uint32_t* bits = reinterpret_cast<uint32_t*>(s_mem);                              // [E][BW]
+        unsigned long long(*scan)[FFN_MAX_E] = reinterpret_cast<unsigned long long(*)[FFN_MAX_E]>(s_mem + BW * FFN_MAX_E * 4);
+        for (int i = tid; i < BW * E; i += FFN_THREADS) bits[i] = 0u;
         __syncthreads();
         int my_e[FFN_LAYER_MAX_ROWS / FFN_THREADS];
 #pragma unroll
@@ -327,14 +329,16 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
             my_e[j] = e;
             if (e >= 0) {
                 const int t = r / k;
-                atomicOr(&bits[2 * e + (t >> 5)], 1u << (t & 31));
+                atomicOr(&bits[BW * e + (t >> 5)], 1u << (t & 31));
             }
         }
         __syncthreads();
         {
             unsigned long long c = 0;
             if (tid < E) {
-                const unsigned cnt = __popc(bits[2 * tid]) + __popc(bits[2 * tid + 1]);
+                unsigned cnt = 0;
+#pragma unroll
+                for (int w = 0; w < BW; ++w) cnt += __popc(bits[BW * tid + w]);
                 c = (unsigned long long)cnt | ((unsigned long long)(cnt > 0) << 32);     // low: rows, high: 1 if the expert has rows
             }
             scan[0][tid] = c;
@@ -367,8 +371,12 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
             int pos = -1;
             if (e >= 0) {
                 const int t = r / k;
-                const uint32_t b0 = bits[2 * e], b1 = bits[2 * e + 1];
-                const int rank = t < 32 ? __popc(b0 & ((1u << t) - 1u)) : __popc(b0) + __popc(b1 & ((1u << (t - 32)) - 1u));
+                int rank = 0;                                       // tokens of this expert below t
+#pragma unroll
+                for (int w = 0; w < BW; ++w) {
+                    const uint32_t b = bits[BW * e + w];
+                    rank += w < (t >> 5) ? __popc(b) : (w == (t >> 5) ? __popc(b & ((1u << (t & 31)) - 1u)) : 0);
+                }
                 pos = s_off[e] + rank;
                 s_sorted[pos] = (uint16_t)t;
             }
