@@ -321,7 +321,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
         Seg cs;
         cs.li = li_begin;
         load_seg(cs);
-        int c_ks = 0, c_done = 0;         // stage inside the segment; stages consumed so far in this phase
+        int c_ks = 0;                     // stage inside the segment
         int pend = 0;                     // finished gate/up items of the current run (one slot) not yet published
         int pub_slot = -1, pub_cnt = 0, pub_mark = 0;   // run whose publication waits for its h stores to be acknowledged
         f32x4_t acc[TILES][2];
@@ -382,7 +382,6 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                         acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w11, xq[u][1], acc[t][1], 0, 0, 0);
                     }
                 }
-                ++c_done;
                 // (5) request this lane's tokens of the stage DX ahead into the registers just used
                 if (px.valid) produce_x(xq[u]);
                 if (++c_ks < nks) return true;
