@@ -218,6 +218,17 @@ def test_bf16_more_than_1024_routed_rows(H, I, body, monkeypatch):
     say("1152 rows", (H, I), body, hz.full_parity(case, gen.random_mask(64, 56, seed=5)))
 
 
+@pytest.mark.parametrize("H,I,E,k,T,M", [(512, 256, 16, 4, 128, 3), (2048, 768, 32, 8, 96, 9), (256, 128, 8, 2, 200, 1), (1024, 512, 64, 6, 160, 40)])
+def test_bf16_streaming_body_many_rows_per_expert(H, I, E, k, T, M):
+    """Calls of more than 64 tokens that average 16 or more rows per expert run the kernel's streaming body.  Few allowed experts
+    give experts with more than 64 rows (several passes of 64 token rows over the same weights: 128 rows per expert in the
+    first case, 200 in the third) and few items per workgroup (segments of one item, workgroups without work); the last case
+    has 24 rows per expert and segments of up to four items."""
+    s = gen.MoEShape("streaming", T=T, H=H, E=E, k=k, I=I, dtype="bf16")
+    case = hz.Case.make(s, gen.make_x(s, seed=8), gen.make_weights(s, seed=8))
+    say("streaming body", (H, I, E, k, T, M), hz.full_parity(case, gen.random_mask(E, M, seed=8)))
+
+
 def test_max_tokens_and_max_experts():
     """T = 1024 tokens (the dispatch bitset's limit) over 256 experts, k = 2, small matrices."""
     s = gen.MoEShape("limits", T=1024, H=256, E=256, k=2, I=128, dtype="bf16")
