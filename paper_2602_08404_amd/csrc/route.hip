@@ -5,6 +5,8 @@
 //            in flight together (one memory round trip), fp32 FMA, cross-lane sums without LDS traffic.
 //            Splitting the experts of a token over several compute units keeps the router matrix traffic per
 //            compute unit small (the whole matrix through one compute unit costs more than the rest together).
+//            Calls of 64 tokens or more (bf16): 16 x 16 tiles on the matrix cores instead, so that a router row is read
+//            once per 16 tokens.
 //   select : one workgroup per token, one thread per expert.  The slot of an expert is its rank = the number of
 //            allowed experts that beat it (larger logit, or equal logit and lower id): every thread counts its
 //            own rank against the logits in LDS, so there is no serial arg-max loop; experts with rank < k write
@@ -22,6 +24,8 @@
 //            itself done; a cold workgroup waits until every first-round workgroup is counted, then selects inside E_A.
 //            Workgroups start in index order and first-round ones never wait, so a waiting workgroup can only wait for
 //            workgroups that already run.
+#include <stdlib.h>
+
 #include "device_utils.hpp"
 #include "kernels.hpp"
 
@@ -152,6 +156,85 @@ __global__ __launch_bounds__(LOGIT_THREADS) void route_logits_kernel(const ST* _
     if (row_hash && first_wave_of_token) {              // exclusive-or of the chunk hashes: any order gives the same value
         const uint32_t lo = wave_xor_u32((uint32_t)hash), hi = wave_xor_u32((uint32_t)(hash >> 32));
         if (lane == 0) row_hash[t] = ((unsigned long long)hi << 32) | lo;
+    }
+}
+
+// The same scores on the matrix cores (bf16 storage, calls of LOGIT_MFMA_MIN_TOKENS tokens or more): a workgroup computes a 16 x 16 tile (experts x tokens), its
+// four wavefronts each a quarter of the reduction, operands loaded straight from global memory in MFMA layout (lane (n, q) of
+// K-step s holds 8 consecutive columns 32 s + 8 q .. of row n), partial sums added in wavefront order through LDS.  A row of the
+// router matrix is then read once per 16 tokens instead of once per token (T = 256 tokens over 256 experts: 32 MB from L2
+// instead of 256 MB).  bf16 products are exact in fp32; only the order of the fp32 sums differs from the kernel above.
+constexpr int LOGIT_TILE = 16;
+constexpr int LOGIT_MFMA_MIN_TOKENS = 64;
+__global__ __launch_bounds__(LOGIT_THREADS) void route_logits_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_router,
+                                                                          float* __restrict__ logits, int T, int H, int E,
+                                                                          uint32_t* __restrict__ zero_words, int n_zero,
+                                                                          const int32_t* __restrict__ row_index, int n_rows,
+                                                                          uint16_t* __restrict__ x_dense,
+                                                                          unsigned long long* __restrict__ row_hash) {
+    if (zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < n_zero) zero_words[threadIdx.x] = 0u;
+    __shared__ f32x4_t s_part[LOGIT_WAVES][WAVE];
+    __shared__ unsigned long long s_hash[LOGIT_WAVES][LOGIT_TILE];
+    static_assert(LOGIT_WAVES == 4, "four partial sums and four partial hashes per tile");
+    const int lane = threadIdx.x & (WAVE - 1), wave = threadIdx.x / WAVE;
+    const int n = lane & 15, q = lane >> 4;
+    const int e0 = blockIdx.x * LOGIT_TILE, t0 = blockIdx.y * LOGIT_TILE;
+    const int kw = H / LOGIT_WAVES;                                  // columns per wavefront, a multiple of 32
+    // rows beyond the last expert / token repeat the last one; their results are not stored
+    const int t_mine = min(t0 + n, T - 1);
+    const int col0 = wave * kw + q * 8;
+    const uint16_t* wp = w_router + (size_t)min(e0 + n, E - 1) * H + col0;
+    const uint16_t* xp = x + (size_t)token_row(row_index, n_rows, t_mine) * H + col0;
+    // the workgroups of the first expert tile also leave the dense copy of the live rows and the row hashes, as the kernel
+    // above does (same chunk numbering; the exclusive-or of the chunk hashes does not depend on the order)
+    const bool side_work = blockIdx.x == 0 && t0 + n < T;
+    unsigned long long hash = 0ull;
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    constexpr int STEPS = 16;                                        // K-steps whose loads are in flight together (one round trip for H = 2048)
+    for (int k0 = 0; k0 < kw; k0 += 32 * STEPS) {
+        bf16x8_t a[STEPS], b[STEPS];
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            const int k = min(k0 + 32 * s, kw - 32);                 // (a short last group re-reads its last step and skips it below)
+            a[s] = *reinterpret_cast<const bf16x8_t*>(wp + k);
+            b[s] = *reinterpret_cast<const bf16x8_t*>(xp + k);
+        }
+#pragma unroll
+        for (int s = 0; s < STEPS; ++s) {
+            if (k0 + 32 * s >= kw) break;
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[s], b[s], acc, 0, 0, 0);
+            if (side_work) {
+                const int col = col0 + k0 + 32 * s;
+                if (x_dense) *reinterpret_cast<bf16x8_t*>(x_dense + (size_t)t_mine * H + col) = b[s];
+                if (row_hash) hash ^= chunk_hash(__builtin_bit_cast(uint4, b[s]), (uint32_t)(col / 8));
+            }
+        }
+    }
+    s_part[wave][lane] = acc;
+    if (row_hash && blockIdx.x == 0) {                               // a row's chunks sit in the four lanes n, n + 16, n + 32, n + 48
+        uint32_t lo = (uint32_t)hash, hi = (uint32_t)(hash >> 32);
+        lo ^= __shfl_xor(lo, 16); hi ^= __shfl_xor(hi, 16);
+        lo ^= __shfl_xor(lo, 32); hi ^= __shfl_xor(hi, 32);
+        if (q == 0) s_hash[wave][n] = ((unsigned long long)hi << 32) | lo;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        f32x4_t v = s_part[0][lane];
+#pragma unroll
+        for (int w = 1; w < LOGIT_WAVES; ++w) v += s_part[w][lane];
+        // lane holds experts e0 + 4 q + (0..3) of token t0 + n
+        const int t = t0 + n, e = e0 + 4 * q;
+        if (t < T) {
+            float* dst = logits + (size_t)t * E + e;
+            if (e + 3 < E && (E & 3) == 0) {
+                *reinterpret_cast<f32x4_t*>(dst) = v;
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (e + j < E) dst[j] = v[j];
+            }
+            if (row_hash && blockIdx.x == 0 && q == 0) row_hash[t] = s_hash[0][n] ^ s_hash[1][n] ^ s_hash[2][n] ^ s_hash[3][n];
+        }
     }
 }
 
@@ -476,6 +559,17 @@ __global__ __launch_bounds__(LOCAL_2R_THREADS) void route_select_two_round_local
 
 static hipError_t launch_logits(const Dims& d, const void* x, const void* w_router, float* logits, uint32_t* zero_words, int n_zero,
                                 hipStream_t s, unsigned long long* row_hash = nullptr) {
+    // bf16, a hidden size the four wavefronts can split into K-steps, and enough tokens to fill tiles: the matrix-core kernel
+    // (with one block of 32 tokens it has only 16 workgroups and is 0.5-1 us slower than the kernel above; with 128 tokens it
+    // is 1.3 us faster, with 256 tokens over 256 experts 14 us)
+    const char* force = getenv("TEAM_MOE_LOGITS_KERNEL");           // tuning aid: "plain" / "mfma" for every token count
+    const bool many_tokens = force ? force[0] == 'm' : d.T >= LOGIT_MFMA_MIN_TOKENS;
+    if (d.bf16 && d.H % (32 * LOGIT_WAVES) == 0 && many_tokens) {
+        dim3 tiles((d.E + LOGIT_TILE - 1) / LOGIT_TILE, (d.T + LOGIT_TILE - 1) / LOGIT_TILE);
+        hipLaunchKernelGGL(route_logits_mfma_kernel, tiles, dim3(LOGIT_THREADS), 0, s, (const uint16_t*)x, (const uint16_t*)w_router, logits,
+                           d.T, d.H, d.E, zero_words, n_zero, d.row_index, d.n_rows, (uint16_t*)d.x_dense, row_hash);
+        return hipGetLastError();
+    }
     dim3 grid((d.E + LOGIT_GROUP - 1) / LOGIT_GROUP, d.T), block(LOGIT_THREADS);
     if (d.bf16)
         hipLaunchKernelGGL(route_logits_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)x, (const uint16_t*)w_router, logits, d.H,

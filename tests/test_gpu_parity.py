@@ -229,6 +229,27 @@ def test_bf16_streaming_body_many_rows_per_expert(H, I, E, k, T, M):
     say("streaming body", (H, I, E, k, T, M), hz.full_parity(case, gen.random_mask(E, M, seed=8)))
 
 
+@pytest.mark.parametrize("kernel", ["mfma", "plain"])
+@pytest.mark.parametrize("H,I,E,k,T", [(512, 128, 24, 4, 40), (256, 128, 7, 3, 20), (2048, 256, 130, 8, 100), (1024, 128, 256, 2, 17)])
+def test_bf16_both_router_score_kernels(H, I, E, k, T, kernel, monkeypatch):
+    """The router scores come from a matrix-core kernel (16 x 16 tiles) for calls of 64 tokens or more and from the
+    one-workgroup-per-token kernel below that; TEAM_MOE_LOGITS_KERNEL forces either.  Ragged tiles in both directions, a
+    number of experts that is not a multiple of 4 (scalar stores), every entry point against the oracle, and the live-row
+    and repeated-row forms (dense copy and row hashes made by the scores kernel) agreeing with the plain call."""
+    monkeypatch.setenv("TEAM_MOE_LOGITS_KERNEL", kernel)
+    s = gen.MoEShape("scores", T=T, H=H, E=E, k=k, I=I, dtype="bf16")
+    case = hz.Case.make(s, gen.make_x(s, seed=21), gen.make_weights(s, seed=21))
+    mask = gen.random_mask(E, max(k, E // 2), seed=21)
+    say("scores kernel", kernel, (H, I, E, k, T), hz.full_parity(case, mask))
+    _, y = hz.gpu_layer(case, mask)
+    live = np.arange(T, dtype=np.int32)[::-1].copy()            # the same rows, listed backwards
+    dense = hz.Case.make(s, case.x[live], case.w, case.wf, case.d_w)
+    _, y_dense = hz.gpu_layer(dense, mask)
+    y_rows, _, _ = hz.gpu_layer_rows(dense, case.x, live, mask=mask)
+    assert torch.equal(y_rows[torch.from_numpy(live).long().to(hz.DEV)], y_dense)
+    assert torch.equal(hz.gpu_layer_unique_rows(case, mask, want_tables=False)[1], y)
+
+
 def test_max_tokens_and_max_experts():
     """T = 1024 tokens (the dispatch bitset's limit) over 256 experts, k = 2, small matrices."""
     s = gen.MoEShape("limits", T=1024, H=256, E=256, k=2, I=128, dtype="bf16")
