@@ -396,13 +396,14 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
             return;
         }
     }
-    const long long total_a = (long long)n_act * TILES_A, total_b = (long long)n_act * TILES_B;
+    const uint32_t total_a = (uint32_t)n_act * TILES_A, total_b = (uint32_t)n_act * TILES_B;   // (at most 256 experts x 128 items)
     // Contiguous shares of floor(total / G) items; the remainder goes, one item each, to the lowest-numbered workgroups.  Those are
     // placed first, one per compute unit, and run ahead of the second workgroup of their unit by about one item over a launch
     // (measured), so the extra item is absorbed instead of extending the phase (with shares that alternate between n and n + 1
     // items every unit ends up with a straggler).
     const int bx = (int)blockIdx.x;
-    const int base_a = (int)(total_a / G), rem_a = (int)(total_a % G), base_b = (int)(total_b / G), rem_b = (int)(total_b % G);
+    const uint32_t Gu = (uint32_t)G;
+    const int base_a = (int)(total_a / Gu), rem_a = (int)(total_a % Gu), base_b = (int)(total_b / Gu), rem_b = (int)(total_b % Gu);
     const int a_begin = bx * base_a + min(bx, rem_a), a_end = a_begin + base_a + (bx < rem_a ? 1 : 0);
     const int b_begin = bx * base_b + min(bx, rem_b), b_end = b_begin + base_b + (bx < rem_b ? 1 : 0);
     const int n_a = a_end - a_begin, n_mine = n_a + (b_end - b_begin);

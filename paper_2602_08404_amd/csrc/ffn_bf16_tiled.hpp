@@ -191,9 +191,9 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
     for (int phase = 0; phase < 2; ++phase) {
         const int tiles = phase == 0 ? tiles_a : tiles_b;
         const int nks = (phase == 0 ? H : I) / KC;                 // stages per (segment, pass)
-        const long long total = (long long)n_act * tiles;
+        const uint32_t total = (uint32_t)n_act * (uint32_t)tiles;   // (at most FFN_MAX_E experts x 128 items: 32-bit arithmetic)
         // contiguous shares; the remainder goes to the lowest-numbered workgroups (see the register-operand body)
-        const int share = (int)(total / G), extra = (int)(total % G), bx = (int)blockIdx.x;
+        const int share = (int)(total / (uint32_t)G), extra = (int)(total % (uint32_t)G), bx = (int)blockIdx.x;
         const int li_begin = bx * share + min(bx, extra), li_end = li_begin + share + (bx < extra ? 1 : 0);
         const size_t tile_stride = phase == 0 ? (size_t)16 * H : (size_t)W_ROWS * I;   // elements between the weight rows of adjacent items
 

@@ -50,6 +50,15 @@ def test_explicit_memory_instructions_do_not_read_a_fresh_scalar_base(assemblies
             assert not gc.stale_scalar_base_uses(lines), (name, fn)
 
 
+def test_no_kernel_uses_scratch_memory(assemblies):
+    """Scratch (private) memory traffic consists of vector-memory operations: it would join the queue whose length the
+    kernel's explicit waits count, and every compiler-inserted wait for it would drain the weight stream."""
+    import re
+    for name, text in assemblies.items():
+        sizes = [int(v) for v in re.findall(r"; ScratchSize: (\d+)", text)]
+        assert sizes and all(v == 0 for v in sizes), (name, sizes)
+
+
 def test_the_checks_catch_planted_mistakes():
     """A register copy between a request and its wait, and a memory instruction right behind v_readlane, in a minimal listing."""
     ok = """
