@@ -16,7 +16,7 @@
 //            routing table and later the result of the earlier one (candidate branches of Section "Speculative
 //            Exploration for Hot Tokens (SEH)" repeat most rows of the base branch).
 //   two-round select : Algorithm 1 in one launch.
-//            Calls of at most 64 tokens (one block): no workgroup depends on another.  Every workgroup rebuilds E_A itself:
+//            Calls of at most 256 tokens (a block, or a few): no workgroup depends on another.  Every workgroup rebuilds E_A itself:
 //            a wavefront finds the k picks of a first-round token with k rounds of a cross-lane maximum over the same
 //            (logit, id) keys the selection uses, four tokens at a time, which is cheaper than one exchange through memory.
 //            Larger calls: workgroups are ordered first-round tokens (newly accepted and hot) before cold tokens.  A
@@ -482,7 +482,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_two_round_kernel(
 }
 
 // ---- two-round routing for calls of at most LOCAL_2R_MAX_TOKENS tokens: E_A is rebuilt by every workgroup -------------------
-constexpr int LOCAL_2R_MAX_TOKENS = 64;
+constexpr int LOCAL_2R_MAX_TOKENS = 256;             // (beyond that the redundant first-round work per workgroup outgrows one exchange through memory)
 constexpr int LOCAL_2R_THREADS = 1024;                 // 16 wavefronts share the first-round tokens; the first 4 then select
 
 __global__ __launch_bounds__(LOCAL_2R_THREADS) void route_select_two_round_local_kernel(const float* __restrict__ logits,
@@ -502,21 +502,31 @@ __global__ __launch_bounds__(LOCAL_2R_THREADS) void route_select_two_round_local
     if (e < TWO_ROUND_MASK_WORDS) s_bits[e] = 0u;
     // one memory round trip: the token classes (every wavefront builds the bit set of first-round tokens for itself) and
     // this token's own logits
-    const bool lane_first = lane < T && token_class[lane] != 0;
+    constexpr int WORDS = LOCAL_2R_MAX_TOKENS / WAVE;
+    bool lane_first[WORDS];
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) lane_first[w] = lane + WAVE * w < T && token_class[lane + WAVE * w] != 0;
     float v = 0.f;
     if (e < E) v = logits[(size_t)t * E + e] + 0.f;
-    const unsigned long long first_set = __ballot(lane_first);
-    const int n_first = __popcll(first_set);
-    const bool is_first = (first_set >> t) & 1ull;
+    unsigned long long first_set[WORDS];
+    int n_first = 0;
+    bool is_first = false;
+#pragma unroll
+    for (int w = 0; w < WORDS; ++w) {
+        first_set[w] = __ballot(lane_first[w]);
+        n_first += __popcll(first_set[w]);
+        if ((t >> 6) == w) is_first = (first_set[w] >> (t & 63)) & 1ull;
+    }
     __syncthreads();                                   // s_bits is cleared
     // ---- E_A = union of the picks of the first-round tokens.  Needed by cold tokens, and by workgroup 0 for the outputs.
     // Wavefront w takes the w-th, (w+16)-th, ... first-round token: k rounds of a cross-lane maximum over the selection keys.
-    if (!is_first || t == 0) {
-        unsigned long long rest = first_set;
-        for (int i = 0; i < wave; ++i) rest &= rest - 1ull;                       // drop the tokens of lower wavefronts
-        for (int j = wave; j < n_first; j += LOCAL_2R_THREADS / WAVE) {
-            const int tok = __builtin_ctzll(rest);
-            for (int i = 0; i < LOCAL_2R_THREADS / WAVE; ++i) rest &= rest - 1ull;
+    if ((!is_first || t == 0) && n_first > 0) {
+        int ordinal = 0;                               // first-round tokens seen so far (every wavefront walks the whole set)
+#pragma unroll
+        for (int w = 0; w < WORDS; ++w)
+        for (unsigned long long rest = first_set[w]; rest != 0ull; rest &= rest - 1ull, ++ordinal) {
+            if (ordinal % (LOCAL_2R_THREADS / WAVE) != wave) continue;
+            const int tok = WAVE * w + __builtin_ctzll(rest);
             const float* row = logits + (size_t)tok * E;
             unsigned long long key[MAX_E / WAVE];        // expert lane + 64 i
 #pragma unroll
@@ -596,7 +606,7 @@ hipError_t launch_route_two_round(const Dims& d, const void* x, const void* w_ro
                                   CtrlZero ctrl, hipStream_t s) {
     if (d.T > MAX_TOKENS_2R || d.E > 32 * TWO_ROUND_MASK_WORDS) return hipErrorInvalidValue;
     uint32_t* words = (uint32_t*)state;                 // [0..7] bit set E_A, [16] arrivals, [32] error flag
-    if (d.T <= LOCAL_2R_MAX_TOKENS) {                   // one block: every workgroup rebuilds E_A itself, nothing is exchanged
+    if (d.T <= LOCAL_2R_MAX_TOKENS) {                   // every workgroup rebuilds E_A itself, nothing is exchanged
         hipError_t err = launch_logits(d, x, w_router, logits, nullptr, 0, s);
         if (err != hipSuccess) return err;
         hipLaunchKernelGGL(route_select_two_round_local_kernel, dim3(d.T), dim3(LOCAL_2R_THREADS), 0, s, logits, token_class, mask_out,

@@ -327,8 +327,10 @@ def test_two_round_limits_and_ragged_counts():
     s = gen.MoEShape("limits", T=1024, H=256, E=256, k=2, I=128, dtype="bf16")
     case = hz.Case.make(s, gen.make_x(s, seed=3), gen.make_weights(s, seed=3))
     say("two-round limits", hz.two_round_parity(case, gen.token_classes(1024, 37, seed=3)))
-    # up to 64 tokens every workgroup rebuilds E_A itself (up to four first-round tokens per wavefront); above, it is exchanged
-    for T, n_first in ((77, 5), (65, 64), (129, 1), (64, 64), (64, 63), (64, 17), (64, 0), (33, 33), (40, 9), (1, 1), (1, 0)):
+    # up to 256 tokens every workgroup rebuilds E_A itself (the first-round tokens dealt out to 16 wavefronts); above, it is
+    # exchanged through device memory
+    for T, n_first in ((257, 30), (256, 256), (256, 255), (256, 0), (200, 77), (77, 5), (65, 64), (129, 1), (64, 64), (64, 63), (64, 17),
+                       (64, 0), (33, 33), (40, 9), (1, 1), (1, 0)):
         sT = gen.scaled(s, T=T)
         caseT = hz.Case.make(sT, gen.make_x(sT, seed=4), case.w, case.wf, case.d_w)
         say("two-round ragged", T, hz.two_round_parity(caseT, gen.token_classes(T, n_first, seed=T)))
