@@ -47,15 +47,11 @@ constexpr int W_BYTES = W_ROWS * ROW_BYTES;
 constexpr int TILES = 4;               // items of a segment (measured: 2 and 3 are slower, 6 is no faster)
 constexpr int STAGE_BYTES = TILES * W_BYTES;   // only the weights pass through LDS
 
-typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-template <int AUX>
-__device__ __forceinline__ void slab_load(const void* gsrc, char* lds_base_uniform) {
-    __builtin_amdgcn_global_load_lds((gptr_t)gsrc, (lptr_t)lds_base_uniform, 16, 0, AUX);
-}
-// Streaming (non-temporal) direct-to-LDS load: M0 holds the LDS address; one idle cycle between writing M0 and the load that
-// reads it; M0 is restored, as the compiler does not expect it to change.
+// Streaming direct-to-LDS load (non-temporal: weights are read once and must not displace the small reused data from L2).
+// M0 holds the LDS address; one idle cycle between writing M0 and the load that reads it; M0 is restored, as the compiler
+// does not expect it to change.
 __device__ __forceinline__ void slab_load_stream_explicit(const void* gsrc, uint32_t lds_addr_uniform) {
     uint32_t saved_m0;
     lds_addr_uniform = __builtin_amdgcn_readfirstlane(lds_addr_uniform);   // (a scalar register also where the compiler cannot prove uniformity)
@@ -70,20 +66,17 @@ __device__ __forceinline__ void slab_load_stream_explicit(const void* gsrc, uint
         : "v"(gsrc), "s"(lds_addr_uniform)
         : "memory");
 }
-// 16 bytes per lane into registers, asynchronously: `dst` is only valid after a wait for at most N outstanding loads with N = the
-// loads issued since.  Until then the compiler believes the value is there already, so nothing may touch it: its only use is as an operand
-// of the matrix instructions, which depend on the LDS reads that follow that wait (explicit statements keep their order).  A
-// copy of such a register in the generated code would read it too early; tests/test_generated_code.py looks for that.
+// 16 bytes per lane into registers, asynchronously: `dst` is only valid after a wait for at most N outstanding loads with
+// N = the loads issued since.  Until then the compiler believes the value is there already, so nothing may touch it: its only
+// use is as an operand of the matrix instructions, which depend on the LDS reads that follow that wait (explicit statements
+// keep their order).  A copy of such a register in the generated code would read it too early;
+// tests/test_generated_code.py looks for that.
 // DEVICE: device-scope load (h written by other workgroups of this launch).
 template <bool DEVICE, int BYTE_OFFSET>
 __device__ __forceinline__ void request_tokens(bf16x8_t& dst, const uint16_t* p) {
     if constexpr (DEVICE) asm volatile("global_load_dwordx4 %0, %1, off offset:%2 sc1" : "=v"(dst) : "v"(p), "n"(BYTE_OFFSET) : "memory");
     else asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=v"(dst) : "v"(p), "n"(BYTE_OFFSET) : "memory");
 }
-constexpr int AUX_NONE = 0;
-constexpr int AUX_STREAM = 2;          // nt: read once, do not displace the small reused data (tokens, h, out) from L2
-constexpr int AUX_DEVICE_SCOPE = 16;   // sc1: the load does not use possibly stale lines of this XCD's L2
-
 template <int N>
 __device__ __forceinline__ void wait_outstanding() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
