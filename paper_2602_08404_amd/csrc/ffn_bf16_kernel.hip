@@ -281,7 +281,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     constexpr int KSM = cmax(KSA, KSB);
     constexpr int W_A = FFN_WAVES * SA::BYTES, W_B = FFN_WAVES * RB * SB::BYTES;
     constexpr int RED_A = FFN_WAVES * NT * WAVE * 16, RED_B = FFN_WAVES * RB * NT * WAVE * 16;
-    constexpr int LDS_BYTES = cmax(cmax(W_A + RED_A, W_B + RED_B), WB == 2 ? tiled::RING_BYTES : 0);   // the streaming variant reuses s_mem
+    constexpr int LDS_BYTES = cmax(cmax(W_A + RED_A, W_B + RED_B), tiled::RING_BYTES);   // the streaming variant reuses s_mem
     constexpr int TILES_A = I / 8, TILES_B = H / (16 * RB);
     __shared__ __attribute__((aligned(1024))) char s_mem[LDS_BYTES];
     __shared__ int32_t s_slot_e[FFN_MAX_E];
@@ -384,15 +384,15 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         }
         __syncthreads();                                        // s_mem is handed to the weight stream from here on
     }
-    if (WB == 2 && tiled_min_avg_rows > 0) {
+    if (tiled_min_avg_rows > 0) {
         // Many rows per expert on average: the register-resident token operand below would have to be re-gathered for
         // every item; stream both operands through LDS instead.  The decision depends on the tables only, so every
         // workgroup of the launch takes the same branch.
         __syncthreads();
         const int total_rows = s_off[E];
         if (n_act > 0 && (long long)total_rows >= (long long)tiled_min_avg_rows * n_act) {
-            tiled::ffn_tiled_body<tiled::RING_STAGES, tiled::X_AHEAD>(s_mem, s_slot_e, s_off, lds_tokens ? s_sorted : nullptr, n_act, x, sorted_token, (const uint16_t*)wg, (const uint16_t*)wu,
-                                                      (const uint16_t*)wd, h, out, ctrl, T, E, H, I, spin_limit);
+            tiled::ffn_tiled_body<tiled::RING_STAGES, tiled::X_AHEAD, WB>(s_mem, s_slot_e, s_off, lds_tokens ? s_sorted : nullptr, n_act, x,
+                                                                          sorted_token, wg, wu, wd, h, out, ctrl, T, E, H, I, spin_limit, sg, su, sd);
             return;
         }
     }
@@ -708,7 +708,7 @@ hipError_t launch_ffn_fused(const FfnArgs& p) {
     const int grid = p.grid_override > 0 && p.grid_override < resident ? p.grid_override : resident;
     hipLaunchKernelGGL((ffn_fused_kernel<KSA, KSB, RB, WB>), dim3(grid), dim3(FFN_THREADS), 0, p.stream, p.x, p.offsets, p.sorted_token,
                        p.active, p.n_active, (const unsigned char*)p.wg, (const unsigned char*)p.wu, (const unsigned char*)p.wd, p.h, p.out,
-                       p.ctrl, p.T, p.k, p.E, p.spin_limit, WB == 2 ? p.tiled_min_avg_rows : 0, p.topk_idx, p.inv_pos_out, p.sg, p.su,
+                       p.ctrl, p.T, p.k, p.E, p.spin_limit, p.tiled_min_avg_rows, p.topk_idx, p.inv_pos_out, p.sg, p.su,
                        p.sd);
     return hipGetLastError();
 }

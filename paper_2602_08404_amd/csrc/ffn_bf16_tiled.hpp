@@ -39,7 +39,7 @@ namespace team {
 
 namespace tiled {
 
-constexpr int KC = 64;                 // reduction columns per stage
+constexpr int KC = 64;                 // reduction columns per stage with bf16 weights (128 bytes of a weight row; 128 columns of E4M3 codes)
 constexpr int MT = 64;                 // token rows per pass
 constexpr int W_ROWS = 32;             // weight rows per item
 constexpr int ROW_BYTES = KC * 2;      // 128
@@ -108,6 +108,21 @@ __device__ __forceinline__ void for_each_slot(F&& f, std::integer_sequence<int, 
     (void)(f(std::integral_constant<int, U>{}) && ...);
 }
 
+// Row scales of 8-bit weights: 16 consecutive floats at a wave-uniform address, read through the scalar cache (the tables are
+// never written by the kernel).  That path has its own counter, so the loads neither join the queue the loop counts nor make the
+// compiler wait for the weight stream.
+typedef const __attribute__((address_space(4))) float* const_f32_ptr;
+__device__ __forceinline__ void load_scales(const float* base_uniform, float (&v)[16]) {
+    const_f32_ptr p = (const_f32_ptr)base_uniform;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = p[i];
+}
+// v[first + stride * q] for a lane-dependent q in 0..3
+__device__ __forceinline__ float pick_q(const float (&v)[16], int first, int stride, int q) {
+    const float lo = q == 0 ? v[first] : v[first + stride], hi = q == 2 ? v[first + 2 * stride] : v[first + 3 * stride];
+    return q < 2 ? lo : hi;
+}
+
 struct Seg {                   // one (segment, pass) of a workgroup's share
     int li;                    // first item of the segment in the expert-major list of the phase
     int nw;                    // items in the segment (1..TILES)
@@ -150,15 +165,22 @@ __device__ __forceinline__ void lds_read4(uint32_t a0, uint32_t a1, uint32_t a2,
 // Body of the streaming variant; runs inside the persistent FFN kernel (all workgroups take it or none does).
 // s_ring: RING_BYTES of LDS, 1 KB aligned; s_slot_e / s_off: the kernel's tables (active list, clipped offsets); s_sorted: its
 // LDS copy of the grouped token list (0xffff: no token), or null when the list did not fit.
-template <int DW, int DX>
+// WB = bytes per weight: 2 (bf16) or 1 (E4M3 codes with one float scale per matrix row: sg, su [E,I], sd [E,H]).  With codes a
+// stage holds 128 reduction columns (the same 128 bytes per weight row), a 16-byte LDS read carries the operands of two K-steps
+// (widened to bf16 in registers), a lane's token operand of a stage is 4 x 16 bytes, and the row scales multiply the sums in
+// the epilogues.
+template <int DW, int DX, int WB>
 __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_slot_e, const int32_t* s_off, const uint16_t* s_sorted, int n_act,
                                                const uint16_t* __restrict__ x, const int32_t* __restrict__ sorted_token,
-                                               const uint16_t* __restrict__ wg, const uint16_t* __restrict__ wu,
-                                               const uint16_t* __restrict__ wd, uint16_t* __restrict__ h, float* __restrict__ out,
-                                               FfnCtrl* __restrict__ ctrl, int T, int E, int H, int I, int spin_limit) {
+                                               const unsigned char* __restrict__ wg, const unsigned char* __restrict__ wu,
+                                               const unsigned char* __restrict__ wd, uint16_t* __restrict__ h, float* __restrict__ out,
+                                               FfnCtrl* __restrict__ ctrl, int T, int E, int H, int I, int spin_limit,
+                                               const float* __restrict__ sg, const float* __restrict__ su, const float* __restrict__ sd) {
+    constexpr int KCOL = ROW_BYTES / WB;          // reduction columns per stage
+    constexpr int XL = 2 * (2 / WB);              // 16-byte token loads per lane and stage = K-steps per stage
     // The tokens of a stage are requested before its weights (DX >= DW), so "everything up to the weights of the stage" is
     // what a stage waits for.
-    static_assert(DX >= DW && (DW - 1) * (TILES + 2) <= MAX_COUNTED, "token requests lead the weight requests; wait counts fit");
+    static_assert(DX >= DW && (DW - 1) * (TILES + XL) <= MAX_COUNTED, "token requests lead the weight requests; wait counts fit");
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -183,12 +205,12 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
 
     for (int phase = 0; phase < 2; ++phase) {
         const int tiles = phase == 0 ? tiles_a : tiles_b;
-        const int nks = (phase == 0 ? H : I) / KC;                 // stages per (segment, pass)
+        const int nks = (phase == 0 ? H : I) / KCOL;               // stages per (segment, pass)
         const uint32_t total = (uint32_t)n_act * (uint32_t)tiles;   // (at most FFN_MAX_E experts x 128 items: 32-bit arithmetic)
         // contiguous shares; the remainder goes to the lowest-numbered workgroups (see the register-operand body)
         const int share = (int)(total / (uint32_t)G), extra = (int)(total % (uint32_t)G), bx = (int)blockIdx.x;
         const int li_begin = bx * share + min(bx, extra), li_end = li_begin + share + (bx < extra ? 1 : 0);
-        const size_t tile_stride = phase == 0 ? (size_t)16 * H : (size_t)W_ROWS * I;   // elements between the weight rows of adjacent items
+        const size_t tile_stride = (phase == 0 ? (size_t)16 * H : (size_t)W_ROWS * I) * WB;   // bytes between the weight rows of adjacent items
 
         auto load_seg = [&](Seg& s) {                               // segment that starts at item s.li; skips experts without rows
             s.valid = false;
@@ -224,7 +246,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
         pw.li = li_begin;
         load_seg(pw);
         int pw_ks = 0, w_issued = 0;
-        const uint16_t* src_w = nullptr;  // rows 8*wave .. 8*wave+7 of the segment's first item
+        const unsigned char* src_w = nullptr;  // rows 8*wave .. 8*wave+7 of the segment's first item
         int mark_w[DW];                   // `issued` right after the weight requests of the stage in that ring slot
         auto pw_enter = [&]() {
             const int r = 8 * wave + ld_row;                       // weight row of the item this lane fetches
@@ -232,15 +254,15 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
             if (phase == 0) {
                 const int i = r & 15;
                 const int iidx = pw.it * 16 + (r >> 4) * 8 + 2 * (i >> 2) + (i & 1);   // rows 4q+{0,1}: gate, 4q+{2,3}: up
-                const uint16_t* mat = (i & 2) ? wu : wg;
-                src_w = mat + ((size_t)pw.e * I + iidx) * H + c * 8;
+                const unsigned char* mat = (i & 2) ? wu : wg;
+                src_w = mat + ((size_t)pw.e * I + iidx) * H * WB + c * 16;
             } else {
-                src_w = wd + ((size_t)pw.e * H + (size_t)pw.it * W_ROWS + r) * I + c * 8;
+                src_w = wd + ((size_t)pw.e * H + (size_t)pw.it * W_ROWS + r) * I * WB + c * 16;
             }
         };
         auto produce_w = [&](int& slot_mark) {                      // (only while pw.valid)
             const uint32_t dst = ring0 + (w_issued % DW) * STAGE_BYTES + wave * 8 * ROW_BYTES;
-            const uint16_t* p = src_w + pw_ks * KC;
+            const unsigned char* p = src_w + pw_ks * ROW_BYTES;
 #pragma unroll
             for (int t = 0; t < TILES; ++t)
                 if (t < pw.nw) slab_load_stream_explicit(p + t * tile_stride, dst + t * W_BYTES);
@@ -259,7 +281,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
         px.li = li_begin;
         load_seg(px);
         int px_ks = 0;
-        const uint16_t* src_x = nullptr;  // row 16*wave + n of the pass, columns 8*q ..
+        const uint16_t* src_x = nullptr;  // row 16*wave + n of the pass, columns 8*q .. (bf16 weights) or 16*q .. (codes)
         int px_key = -1;                  // (slot, pass) src_x was built for
         int ready_slot = -1;              // down phase: slot whose h is known to be complete
         auto px_enter = [&]() {           // new (segment, pass): uniform control flow
@@ -286,23 +308,40 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                     // (from the kernel's LDS copy when there is one; a load from global memory waits for every load in flight)
                     int tok = s_sorted ? lds_read_u16(lds_addr(s_sorted) + 2 * (px.r0 + row)) : sorted_token[px.r0 + row];
                     tok = min(max(tok, 0), T - 1);
-                    src_x = x + (size_t)tok * H + q * 8;
+                    src_x = x + (size_t)tok * H + q * (16 / WB);
                 } else {
-                    src_x = h + (size_t)(px.r0 + row) * I + q * 8;
+                    src_x = h + (size_t)(px.r0 + row) * I + q * (16 / WB);
                 }
             }
         };
-        bf16x8_t xq[DX][2];               // token operands of the next DX stages
-        auto produce_x = [&](bf16x8_t (&dst)[2]) {                  // (only while px.valid)
-            const uint16_t* p = src_x + px_ks * KC;
-            if (phase == 0) {
-                request_tokens<false, 0>(dst[0], p);
-                request_tokens<false, 64>(dst[1], p);
+        // Token operands of the next DX stages.  K-step s of a stage meets, in lane group q, the 8 columns 32 s + 8 q .. (bf16
+        // weights) or 64 (s / 2) + 16 q + 8 (s % 2) .. (codes: a lane's 16-byte LDS read holds 16 consecutive columns, used as two
+        // K-steps); any assignment of columns to K-steps is a valid order of the sum as long as both operands use it.
+        bf16x8_t xq[DX][XL];
+        auto produce_x = [&](bf16x8_t (&dst)[XL]) {                 // (only while px.valid)
+            const uint16_t* p = src_x + px_ks * KCOL;
+            if constexpr (WB == 2) {
+                if (phase == 0) {
+                    request_tokens<false, 0>(dst[0], p);
+                    request_tokens<false, 64>(dst[1], p);
+                } else {
+                    request_tokens<true, 0>(dst[0], p);
+                    request_tokens<true, 64>(dst[1], p);
+                }
             } else {
-                request_tokens<true, 0>(dst[0], p);
-                request_tokens<true, 64>(dst[1], p);
+                if (phase == 0) {
+                    request_tokens<false, 0>(dst[0], p);
+                    request_tokens<false, 16>(dst[1], p);
+                    request_tokens<false, 128>(dst[2], p);
+                    request_tokens<false, 144>(dst[3], p);
+                } else {
+                    request_tokens<true, 0>(dst[0], p);
+                    request_tokens<true, 16>(dst[1], p);
+                    request_tokens<true, 128>(dst[2], p);
+                    request_tokens<true, 144>(dst[3], p);
+                }
             }
-            issued += 2;
+            issued += XL;
             if (++px_ks == nks) {
                 px_ks = 0;
                 next_seg(px);
@@ -369,10 +408,26 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                         const uint32_t wt = slot + t * W_BYTES;
                         bf16x8_t w00, w10, w01, w11;
                         lds_read4(wt + rd_w[0][0], wt + rd_w[1][0], wt + rd_w[0][1], wt + rd_w[1][1], w00, w10, w01, w11);
-                        acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w00, xq[u][0], acc[t][0], 0, 0, 0);
-                        acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w10, xq[u][0], acc[t][1], 0, 0, 0);
-                        acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w01, xq[u][1], acc[t][0], 0, 0, 0);
-                        acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w11, xq[u][1], acc[t][1], 0, 0, 0);
+                        if constexpr (WB == 2) {
+                            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w00, xq[u][0], acc[t][0], 0, 0, 0);
+                            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w10, xq[u][0], acc[t][1], 0, 0, 0);
+                            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w01, xq[u][1], acc[t][0], 0, 0, 0);
+                            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w11, xq[u][1], acc[t][1], 0, 0, 0);
+                        } else {                                    // each read: the codes of two K-steps
+                            bf16x8_t a0, a1, b0, b1;
+                            widen_e4m3(w00, a0, a1);
+                            widen_e4m3(w10, b0, b1);
+                            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, xq[u][0], acc[t][0], 0, 0, 0);
+                            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0, xq[u][0], acc[t][1], 0, 0, 0);
+                            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, xq[u][1], acc[t][0], 0, 0, 0);
+                            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1, xq[u][1], acc[t][1], 0, 0, 0);
+                            widen_e4m3(w01, a0, a1);
+                            widen_e4m3(w11, b0, b1);
+                            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, xq[u][2], acc[t][0], 0, 0, 0);
+                            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0, xq[u][2], acc[t][1], 0, 0, 0);
+                            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, xq[u][3], acc[t][0], 0, 0, 0);
+                            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1, xq[u][3], acc[t][1], 0, 0, 0);
+                        }
                     }
                 }
                 // (5) request this lane's tokens of the stage DX ahead into the registers just used
@@ -385,6 +440,28 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                 for (int t = 0; t < TILES; ++t) {
                     if (t < cs.nw && row < cs.m) {
                         const int it = cs.it + t;
+                        if constexpr (WB == 1) {                    // row scales of the item (read through the scalar cache: see load_scales)
+                            if (phase == 0) {
+                                float g16[16], u16[16];             // scales of intermediate indices it*16 .. +15
+                                load_scales(sg + (size_t)cs.e * I + it * 16, g16);
+                                load_scales(su + (size_t)cs.e * I + it * 16, u16);
+#pragma unroll
+                                for (int rt = 0; rt < 2; ++rt) {
+                                    acc[t][rt][0] *= pick_q(g16, 8 * rt, 2, q);
+                                    acc[t][rt][1] *= pick_q(g16, 8 * rt + 1, 2, q);
+                                    acc[t][rt][2] *= pick_q(u16, 8 * rt, 2, q);
+                                    acc[t][rt][3] *= pick_q(u16, 8 * rt + 1, 2, q);
+                                }
+                            } else {
+#pragma unroll
+                                for (int rt = 0; rt < 2; ++rt) {
+                                    float d16[16];                  // scales of output rows it*32 + rt*16 .. +15
+                                    load_scales(sd + (size_t)cs.e * H + it * W_ROWS + rt * 16, d16);
+#pragma unroll
+                                    for (int j = 0; j < 4; ++j) acc[t][rt][j] *= pick_q(d16, j, 4, q);
+                                }
+                            }
+                        }
                         if (phase == 0) {
 #pragma unroll
                             for (int rt = 0; rt < 2; ++rt) {

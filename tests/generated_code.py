@@ -10,7 +10,7 @@ from __future__ import annotations
 import re
 from typing import Dict, List, Set, Tuple
 
-TOKEN_LOAD = re.compile(r"^global_load_dwordx4 v\[(\d+):(\d+)\], v\[\d+:\d+\], off offset:(0|64)( sc1)?$")
+TOKEN_LOAD = re.compile(r"^global_load_dwordx4 v\[(\d+):(\d+)\], v\[\d+:\d+\], off offset:(\d+)( sc1)?$")
 EXPLICIT_WAIT = re.compile(r"^s_waitcnt vmcnt\((\d+)\)$")
 VREG = re.compile(r"\bv(\d+)\b")
 VRANGE = re.compile(r"\bv\[(\d+):(\d+)\]")
