@@ -386,8 +386,8 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     }
     if (tiled_min_avg_rows > 0) {
         // Many rows per expert on average: the register-resident token operand below would have to be re-gathered for
-        // every item; stream both operands through LDS instead.  The decision depends on the tables only, so every
-        // workgroup of the launch takes the same branch.
+        // every item; pipeline both operands instead (weights through an LDS ring, tokens through registers, several items
+        // per token pass).  The decision depends on the tables only, so every workgroup of the launch takes the same branch.
         __syncthreads();
         const int total_rows = s_off[E];
         if (n_act > 0 && (long long)total_rows >= (long long)tiled_min_avg_rows * n_act) {
