@@ -250,6 +250,24 @@ def test_bf16_both_router_score_kernels(H, I, E, k, T, kernel, monkeypatch):
     assert torch.equal(hz.gpu_layer_unique_rows(case, mask, want_tables=False)[1], y)
 
 
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_bf16_seeded_shape_sweep(seed):
+    """Shapes drawn from a seeded generator over the supported ranges (hidden 256 to 2048, intermediate a multiple of 128 up
+    to 1024, up to 256 experts, top-1 to top-8, 1 to 300 tokens, activated sets from one expert to all): whatever combination
+    of kernel bodies, grouping paths and score kernels a shape selects, every entry point meets the bars against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    H = int(rng.choice([256, 512, 1024, 2048], p=[0.3, 0.3, 0.25, 0.15]))
+    I = 128 * int(rng.integers(1, 9 if H < 2048 else 5))
+    E = int(rng.choice([4, 8, 16, 24, 32, 64, 100, 128, 256]))
+    k = int(rng.integers(1, min(8, E) + 1))
+    T = int(rng.choice([1, 3, 16, 31, 32, 33, 64, 65, 100, 128, 129, 200, 300]))
+    M = int(rng.integers(1, E + 1))
+    s = gen.MoEShape("sweep", T=T, H=H, E=E, k=k, I=I, dtype="bf16")
+    case = hz.Case.make(s, gen.make_x(s, seed=seed), gen.make_weights(s, seed=seed))
+    mask = None if M == E else gen.random_mask(E, M, seed=seed)
+    say("sweep", seed, (H, I, E, k, T, M), hz.full_parity(case, mask))
+
+
 def test_max_tokens_and_max_experts():
     """T = 1024 tokens (the dispatch bitset's limit) over 256 experts, k = 2, small matrices."""
     s = gen.MoEShape("limits", T=1024, H=256, E=256, k=2, I=128, dtype="bf16")
