@@ -269,8 +269,12 @@ typedef struct {
     const uint8_t* token_class;     /* [T] or NULL: two-round routing (team_moe_layer_forward_two_round) */
     uint8_t* activated_mask_out;    /* [E] or NULL; written in the two-round mode */
     int32_t* n_activated_out;       /* [1] or NULL; written in the two-round mode */
-    int32_t unique_rows;            /* 1: compute repeated rows once (team_moe_layer_forward_unique_rows); needs row_index == NULL
-                                       and token_class == NULL */
+    int32_t unique_rows;            /* 1: compute repeated rows once (team_moe_layer_forward_unique_rows).  With row_index the rows
+                                       compared are the live rows, and row_rep_out holds positions in the call (0..T-1), not rows
+                                       of x.  With token_class every first-round token, repeated or not, contributes its picks to
+                                       the activated set, so each token's result is the one it gets without the search (a row's
+                                       first occurrence may be cold and a later one first-round: the picks of that row then lie
+                                       inside the set, and routing confined to the set equals free routing for it) */
     int32_t reserved;               /* must be 0 */
     int32_t* row_rep_out;           /* [T] or NULL; written when unique_rows */
     int32_t* n_unique_out;          /* [1] or NULL; written when unique_rows */

@@ -296,7 +296,7 @@ int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const vo
     const team::CtrlZero cz = cfg->dtype == TEAM_BF16 ? team::ffn_ctrl_zero(ws + L.ctrl) : none;
     if (token_class)
         st = hip_status(team::launch_route_two_round(d, x, w_router, token_class, activated_mask_out, n_activated_out, topk_idx,
-                                                     topk_gate, logits, ws + L.two_round, short_path ? cz : none, s));
+                                                     topk_gate, logits, ws + L.two_round, short_path ? cz : none, s, dedup));
     else
         st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, logits, short_path ? cz : none, s, dedup));
     if (st != TEAM_OK) return st;
@@ -363,7 +363,6 @@ int team_moe_layer_forward_ex(const team_moe_config* cfg, const team_moe_layer_a
     if (rows ? a->n_rows < 1 : a->n_rows != 0) return TEAM_ERR_INVALID_ARG;
     if (a->expert_mask && a->token_class) return TEAM_ERR_INVALID_ARG;                // one routing mode per call
     if (a->unique_rows != 0 && a->unique_rows != 1) return TEAM_ERR_INVALID_ARG;
-    if (a->unique_rows && (rows || a->token_class)) return TEAM_ERR_INVALID_ARG;      // the search reads dense x and single-round tables
     if (!a->unique_rows && (a->row_rep_out || a->n_unique_out)) return TEAM_ERR_INVALID_ARG;
     if (!a->token_class && (a->activated_mask_out || a->n_activated_out)) return TEAM_ERR_INVALID_ARG;
     const bool any_scale = a->scale_gate || a->scale_up || a->scale_down;

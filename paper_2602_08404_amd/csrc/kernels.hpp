@@ -25,6 +25,8 @@ struct Dims {
 // Search for repeated rows inside the router (hash == nullptr: off).  The logits kernel writes a 64-bit hash of every row and
 // clears *n_unique; the selection kernel of token t compares hashes with the tokens before it, confirms a match byte by byte,
 // writes rep[t], counts the tokens that are their own representative and leaves the routing table of the others empty.
+// With a live-row index the rows compared are those of the dense copy (Dims::x_dense).  Under two-round routing a repeated
+// first-round row still contributes its picks to E_A, so the result of every token is the one it would get without the search.
 struct RowDedup {
     unsigned long long* hash = nullptr;   // [T]
     int32_t* rep = nullptr;               // [T]
@@ -47,7 +49,7 @@ hipError_t launch_route(const Dims& d, const void* x, const void* w_router, cons
 // n_activated_out [1] may be null.  T <= 1024.
 hipError_t launch_route_two_round(const Dims& d, const void* x, const void* w_router, const uint8_t* token_class, uint8_t* mask_out,
                                   int32_t* n_activated_out, int32_t* topk_idx, float* topk_gate, float* logits, void* state,
-                                  CtrlZero ctrl, hipStream_t s);
+                                  CtrlZero ctrl, hipStream_t s, RowDedup dedup = RowDedup());
 // Hot/cold classification of live tokens (Algorithm 1 step 1, Eq. 4): token_class[t] = 1 first-round, 0 cold.
 hipError_t launch_classify_tokens(const float* conf, const uint8_t* state, int n_rows, int block_len, const int32_t* live_index, int T,
                                   float tau_h, int L_h, uint8_t* token_class, hipStream_t s);

@@ -88,16 +88,24 @@ __device__ __forceinline__ uint32_t wave_xor_u32(uint32_t v) {
            (uint32_t)__builtin_amdgcn_readlane((int)v, 32) ^ (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
 }
 
+__device__ __forceinline__ void clear_select_state(uint32_t* __restrict__ zero_words, int n_zero, uint32_t* __restrict__ zero_count) {
+    if (blockIdx.x != 0 || blockIdx.y != 0) return;
+    if (zero_words && (int)threadIdx.x < n_zero) zero_words[threadIdx.x] = 0u;
+    if (zero_count && threadIdx.x == 0) *zero_count = 0u;
+}
+
 template <typename ST>
 __global__ __launch_bounds__(LOGIT_THREADS) void route_logits_kernel(const ST* __restrict__ x, const ST* __restrict__ w_router,
                                                                      float* __restrict__ logits, int H, int E,
                                                                      uint32_t* __restrict__ zero_words, int n_zero,
+                                                                     uint32_t* __restrict__ zero_count,
                                                                      const int32_t* __restrict__ row_index, int n_rows,
                                                                      ST* __restrict__ x_dense,
                                                                      unsigned long long* __restrict__ row_hash) {
     constexpr int CN = Chunk<ST>::N;
-    // state the selection kernel that follows starts from (two-round routing: bit set and arrival counter)
-    if (zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < n_zero) zero_words[threadIdx.x] = 0u;
+    // state the selection kernel that follows starts from (two-round routing: bit set and arrival counter; repeated-row
+    // search: the count of distinct rows)
+    clear_select_state(zero_words, n_zero, zero_count);
     constexpr int XC = 4;          // chunks of the token row per lane per block of 256 chunks
     const int t = blockIdx.y;
     const int lane = threadIdx.x & (WAVE - 1);
@@ -169,10 +177,11 @@ constexpr int LOGIT_MFMA_MIN_TOKENS = 64;
 __global__ __launch_bounds__(LOGIT_THREADS) void route_logits_mfma_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_router,
                                                                           float* __restrict__ logits, int T, int H, int E,
                                                                           uint32_t* __restrict__ zero_words, int n_zero,
+                                                                          uint32_t* __restrict__ zero_count,
                                                                           const int32_t* __restrict__ row_index, int n_rows,
                                                                           uint16_t* __restrict__ x_dense,
                                                                           unsigned long long* __restrict__ row_hash) {
-    if (zero_words && blockIdx.x == 0 && blockIdx.y == 0 && (int)threadIdx.x < n_zero) zero_words[threadIdx.x] = 0u;
+    clear_select_state(zero_words, n_zero, zero_count);
     __shared__ f32x4_t s_part[LOGIT_WAVES][WAVE];
     __shared__ unsigned long long s_hash[LOGIT_WAVES][LOGIT_TILE];
     static_assert(LOGIT_WAVES == 4, "four partial sums and four partial hashes per tile");
@@ -320,6 +329,7 @@ __device__ __forceinline__ void clear_ffn_ctrl(const CtrlZero& ctrl, int tid, in
 // First token j < t whose row holds the same row_bytes bytes as token t's (t itself if there is none); all threads of the
 // workgroup take part and get the result.  Candidates are the tokens with the same (masked) hash, in ascending order; each is
 // confirmed by comparing the rows.
+template <int THREADS>
 __device__ __forceinline__ int first_equal_row(const RowDedup& dd, const unsigned char* __restrict__ x, int row_bytes, int t, int tid) {
     __shared__ int s_best;
     const unsigned long long my_hash = dd.hash[t] & dd.hash_mask;
@@ -328,20 +338,35 @@ __device__ __forceinline__ int first_equal_row(const RowDedup& dd, const unsigne
     while (true) {
         if (tid == 0) s_best = t;
         __syncthreads();
-        for (int j = after + 1 + tid; j < t; j += SELECT_THREADS)
+        for (int j = after + 1 + tid; j < t; j += THREADS)
             if ((dd.hash[j] & dd.hash_mask) == my_hash) { atomicMin(&s_best, j); break; }
         __syncthreads();
         const int cand = s_best;
         if (cand >= t) return t;
         const uint4* other = reinterpret_cast<const uint4*>(x + (size_t)cand * row_bytes);
         bool same = true;
-        for (int c = tid; c < row_bytes / 16; c += SELECT_THREADS) {
+        for (int c = tid; c < row_bytes / 16; c += THREADS) {
             const uint4 a = mine[c], b = other[c];
             same = same && a.x == b.x && a.y == b.y && a.z == b.z && a.w == b.w;
         }
         if (__syncthreads_and(same)) return cand;        // (also orders this round's reads of s_best before the next write)
         after = cand;
     }
+}
+
+// Repeated-row search for token t (all THREADS threads of the workgroup): writes rep[t], counts the tokens that are their own
+// representative, and for a token that is not leaves its row of the routing table empty (it takes no part in the expert FFN:
+// its result is its representative's).  Returns whether t is its own representative.
+template <int THREADS>
+__device__ __forceinline__ bool own_representative(const RowDedup& dd, const unsigned char* __restrict__ x, int row_bytes, int t, int tid,
+                                                   int k, int32_t* __restrict__ topk_idx, float* __restrict__ topk_gate) {
+    const int rep = first_equal_row<THREADS>(dd, x, row_bytes, t, tid);
+    if (tid == 0) {
+        dd.rep[t] = rep;
+        if (rep == t) atomicAdd(dd.n_unique, 1);
+    }
+    if (rep != t && tid < k) { topk_idx[(size_t)t * k + tid] = -1; topk_gate[(size_t)t * k + tid] = 0.f; }
+    return rep == t;
 }
 
 __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(const float* __restrict__ logits, const uint8_t* __restrict__ mask,
@@ -352,17 +377,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(const floa
     const int t = blockIdx.x;
     const int e = threadIdx.x;
     if (ctrl.words && t == 0) clear_ffn_ctrl(ctrl, e, E);   // control block of an expert FFN that follows without a dispatch kernel
-    if (dd.hash) {
-        const int rep = first_equal_row(dd, x, row_bytes, t, e);
-        if (e == 0) {
-            dd.rep[t] = rep;
-            if (rep == t) atomicAdd(dd.n_unique, 1);
-        }
-        if (rep != t) {                                  // computed once, for token rep: this token takes no part in the expert FFN
-            if (e < k) { topk_idx[(size_t)t * k + e] = -1; topk_gate[(size_t)t * k + e] = 0.f; }
-            return;
-        }
-    }
+    if (dd.hash && !own_representative<SELECT_THREADS>(dd, x, row_bytes, t, e, k, topk_idx, topk_gate)) return;
     float v = 0.f;
     bool ok = false;
     if (e < E) {
@@ -379,7 +394,8 @@ __device__ __forceinline__ uint32_t load_agent(const uint32_t* p) { return __hip
 __global__ __launch_bounds__(SELECT_THREADS) void route_select_two_round_kernel(const float* __restrict__ logits, TwoRound tr,
                                                                                 int32_t* __restrict__ topk_idx,
                                                                                 float* __restrict__ topk_gate, int T, int E, int k,
-                                                                                int renormalize, CtrlZero ctrl) {
+                                                                                int renormalize, CtrlZero ctrl, RowDedup dd,
+                                                                                const unsigned char* __restrict__ x, int row_bytes) {
     __shared__ SelectLds sm;
     __shared__ unsigned long long s_cls[MAX_TOKENS_2R / WAVE];   // bit t: token t is a first-round token
     __shared__ uint32_t s_bits[TWO_ROUND_MASK_WORDS];
@@ -426,6 +442,14 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_two_round_kernel(
         t = word * WAVE + (bits ? __builtin_ctzll(bits) : 0);
     }
     const bool is_first = b < n_first;
+    // A repeated row is routed and computed once, for its first occurrence.  As a first-round token it still adds its picks to
+    // E_A (its first occurrence may be a cold token; the picks then lie inside E_A, so that token's restricted routing is the
+    // free one and serves both); as a cold token it has nothing left to do.
+    bool keeps_row = true;
+    if (dd.hash) {
+        keeps_row = own_representative<SELECT_THREADS>(dd, x, row_bytes, t, e, k, topk_idx, topk_gate);
+        if (!keeps_row && !is_first) return;
+    }
 
     float v = 0.f;
     bool ok = false;
@@ -478,7 +502,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_two_round_kernel(
         if (tr.mask_out && e < E) tr.mask_out[e] = 0;
         if (tr.n_activated_out && e == 0) *tr.n_activated_out = 0;
     }
-    if (e < WAVE) write_gates(sm, t, e, E, k, renormalize, topk_idx, topk_gate);
+    if (keeps_row && e < WAVE) write_gates(sm, t, e, E, k, renormalize, topk_idx, topk_gate);
 }
 
 // ---- two-round routing for calls of at most LOCAL_2R_MAX_TOKENS tokens: E_A is rebuilt by every workgroup -------------------
@@ -491,7 +515,8 @@ __global__ __launch_bounds__(LOCAL_2R_THREADS) void route_select_two_round_local
                                                                                         int32_t* __restrict__ n_activated_out,
                                                                                         int32_t* __restrict__ topk_idx,
                                                                                         float* __restrict__ topk_gate, int T, int E, int k,
-                                                                                        int renormalize, CtrlZero ctrl) {
+                                                                                        int renormalize, CtrlZero ctrl, RowDedup dd,
+                                                                                        const unsigned char* __restrict__ x, int row_bytes) {
     __shared__ SelectLds sm;
     __shared__ uint32_t s_bits[TWO_ROUND_MASK_WORDS];
     const int t = blockIdx.x;
@@ -499,6 +524,10 @@ __global__ __launch_bounds__(LOCAL_2R_THREADS) void route_select_two_round_local
     const int lane = e & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(e / WAVE);
     if (ctrl.words && t == 0 && e < SELECT_THREADS) clear_ffn_ctrl(ctrl, e, E);
+    // A repeated row is routed once, for its first occurrence (token 0 is always one, so the outputs below are written).  E_A is
+    // built from every first-round token, repeated or not: a cold first occurrence of a first-round row finds that row's free
+    // picks inside E_A, and its restricted routing is the free one.
+    if (dd.hash && !own_representative<LOCAL_2R_THREADS>(dd, x, row_bytes, t, e, k, topk_idx, topk_gate)) return;
     if (e < TWO_ROUND_MASK_WORDS) s_bits[e] = 0u;
     // one memory round trip: the token classes (every wavefront builds the bit set of first-round tokens for itself) and
     // this token's own logits
@@ -568,7 +597,9 @@ __global__ __launch_bounds__(LOCAL_2R_THREADS) void route_select_two_round_local
 }
 
 static hipError_t launch_logits(const Dims& d, const void* x, const void* w_router, float* logits, uint32_t* zero_words, int n_zero,
-                                hipStream_t s, unsigned long long* row_hash = nullptr) {
+                                hipStream_t s, const RowDedup& dedup = RowDedup()) {
+    unsigned long long* row_hash = dedup.hash;
+    uint32_t* zero_count = dedup.hash ? (uint32_t*)dedup.n_unique : nullptr;
     // bf16, a hidden size the four wavefronts can split into K-steps, and enough tokens to fill tiles: the matrix-core kernel
     // (with one block of 32 tokens it has only 16 workgroups and is 0.5-1 us slower than the kernel above; with 128 tokens it
     // is 1.3 us faster, with 256 tokens over 256 experts 14 us)
@@ -577,49 +608,61 @@ static hipError_t launch_logits(const Dims& d, const void* x, const void* w_rout
     if (d.bf16 && d.H % (32 * LOGIT_WAVES) == 0 && many_tokens) {
         dim3 tiles((d.E + LOGIT_TILE - 1) / LOGIT_TILE, (d.T + LOGIT_TILE - 1) / LOGIT_TILE);
         hipLaunchKernelGGL(route_logits_mfma_kernel, tiles, dim3(LOGIT_THREADS), 0, s, (const uint16_t*)x, (const uint16_t*)w_router, logits,
-                           d.T, d.H, d.E, zero_words, n_zero, d.row_index, d.n_rows, (uint16_t*)d.x_dense, row_hash);
+                           d.T, d.H, d.E, zero_words, n_zero, zero_count, d.row_index, d.n_rows, (uint16_t*)d.x_dense, row_hash);
         return hipGetLastError();
     }
     dim3 grid((d.E + LOGIT_GROUP - 1) / LOGIT_GROUP, d.T), block(LOGIT_THREADS);
     if (d.bf16)
         hipLaunchKernelGGL(route_logits_kernel<uint16_t>, grid, block, 0, s, (const uint16_t*)x, (const uint16_t*)w_router, logits, d.H,
-                           d.E, zero_words, n_zero, d.row_index, d.n_rows, (uint16_t*)d.x_dense, row_hash);
+                           d.E, zero_words, n_zero, zero_count, d.row_index, d.n_rows, (uint16_t*)d.x_dense, row_hash);
     else
         hipLaunchKernelGGL(route_logits_kernel<float>, grid, block, 0, s, (const float*)x, (const float*)w_router, logits, d.H, d.E,
-                           zero_words, n_zero, d.row_index, d.n_rows, (float*)d.x_dense, row_hash);
+                           zero_words, n_zero, zero_count, d.row_index, d.n_rows, (float*)d.x_dense, row_hash);
     return hipGetLastError();
+}
+
+// The repeated-row search compares the rows of the call: the caller's dense x, or the dense copy of the live rows the logits
+// kernel has just written.
+static bool dedup_args_ok(const Dims& d, const RowDedup& dedup, int row_bytes) {
+    if (!dedup.hash) return true;
+    return row_bytes % 16 == 0 && dedup.rep && dedup.n_unique && (!d.row_index || d.x_dense);
+}
+static const unsigned char* searched_rows(const Dims& d, const void* x) {
+    return (const unsigned char*)(d.row_index ? d.x_dense : x);
 }
 
 hipError_t launch_route(const Dims& d, const void* x, const void* w_router, const uint8_t* mask, int32_t* topk_idx,
                         float* topk_gate, float* logits, CtrlZero ctrl, hipStream_t s, RowDedup dedup) {
     const int row_bytes = d.H * (d.bf16 ? 2 : 4);
-    if (dedup.hash && (d.row_index || row_bytes % 16 != 0 || !dedup.rep || !dedup.n_unique)) return hipErrorInvalidValue;
-    hipError_t err = launch_logits(d, x, w_router, logits, (uint32_t*)dedup.n_unique, dedup.hash ? 1 : 0, s, dedup.hash);
+    if (!dedup_args_ok(d, dedup, row_bytes)) return hipErrorInvalidValue;
+    hipError_t err = launch_logits(d, x, w_router, logits, nullptr, 0, s, dedup);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(route_select_kernel, dim3(d.T), dim3(SELECT_THREADS), 0, s, logits, mask, topk_idx, topk_gate, d.E, d.k,
-                       d.renormalize, ctrl, dedup, (const unsigned char*)x, row_bytes);
+                       d.renormalize, ctrl, dedup, searched_rows(d, x), row_bytes);
     return hipGetLastError();
 }
 
 hipError_t launch_route_two_round(const Dims& d, const void* x, const void* w_router, const uint8_t* token_class, uint8_t* mask_out,
                                   int32_t* n_activated_out, int32_t* topk_idx, float* topk_gate, float* logits, void* state,
-                                  CtrlZero ctrl, hipStream_t s) {
+                                  CtrlZero ctrl, hipStream_t s, RowDedup dedup) {
     if (d.T > MAX_TOKENS_2R || d.E > 32 * TWO_ROUND_MASK_WORDS) return hipErrorInvalidValue;
+    const int row_bytes = d.H * (d.bf16 ? 2 : 4);
+    if (!dedup_args_ok(d, dedup, row_bytes)) return hipErrorInvalidValue;
     uint32_t* words = (uint32_t*)state;                 // [0..7] bit set E_A, [16] arrivals, [32] error flag
     if (d.T <= LOCAL_2R_MAX_TOKENS) {                   // every workgroup rebuilds E_A itself, nothing is exchanged
-        hipError_t err = launch_logits(d, x, w_router, logits, nullptr, 0, s);
+        hipError_t err = launch_logits(d, x, w_router, logits, nullptr, 0, s, dedup);
         if (err != hipSuccess) return err;
         hipLaunchKernelGGL(route_select_two_round_local_kernel, dim3(d.T), dim3(LOCAL_2R_THREADS), 0, s, logits, token_class, mask_out,
-                           n_activated_out, topk_idx, topk_gate, d.T, d.E, d.k, d.renormalize, ctrl);
+                           n_activated_out, topk_idx, topk_gate, d.T, d.E, d.k, d.renormalize, ctrl, dedup, searched_rows(d, x), row_bytes);
         return hipGetLastError();
     }
-    hipError_t err = launch_logits(d, x, w_router, logits, words, TWO_ROUND_STATE_WORDS, s);
+    hipError_t err = launch_logits(d, x, w_router, logits, words, TWO_ROUND_STATE_WORDS, s, dedup);
     if (err != hipSuccess) return err;
     TwoRound tr;
     tr.token_class = token_class; tr.mask_bits = words; tr.arrived = words + 16; tr.error = words + 32;
     tr.mask_out = mask_out; tr.n_activated_out = n_activated_out; tr.spin_limit = 1 << 16;
     hipLaunchKernelGGL(route_select_two_round_kernel, dim3(d.T), dim3(SELECT_THREADS), 0, s, logits, tr, topk_idx, topk_gate, d.T, d.E,
-                       d.k, d.renormalize, ctrl);
+                       d.k, d.renormalize, ctrl, dedup, searched_rows(d, x), row_bytes);
     return hipGetLastError();
 }
 

@@ -460,3 +460,52 @@ def two_round_parity(case: Case, token_class: np.ndarray, threads=0):
     set_safe_m, _ = safe_tokens(o_logits, g_mask, s.k)
     layer_err, n_band = check_layer(case, g_mask, y_gpu, g_idx, g_gate, o_y, o_idx_m, set_safe_m)
     return {"n_first": int(len(first)), "n_activated": g_n, "first_safe": first_safe, "layer_err": layer_err, "band_tokens": n_band}
+
+
+def two_round_unique_rows_parity(case: Case, token_class: np.ndarray, scatter_seed: Optional[int] = None, threads=0):
+    """team_moe_layer_forward_ex with the two-round router and the repeated-row search together (and, with scatter_seed, the
+    tokens scattered over the rows of a larger tensor and reached through a row index).  The search changes no token's
+    result: the table of first equal rows is bit-exact against the oracle's byte-wise definition, E_A is the one the
+    two-round router finds without the search, y is compared row by row with the oracle's layer over all tokens under that
+    E_A, repeated rows carry the bits of their first occurrence and rows outside the call are not written."""
+    s = case.shape
+    T = s.T
+    if scatter_seed is None:
+        n_rows, rows, d_x = 0, None, case.d_x
+    else:
+        n_rows = T + 9
+        rows = gen.token_permutation(n_rows, seed=scatter_seed)[:T].astype(np.int32)       # not sorted: order of the call != order of the rows
+        x_rows = np.zeros((n_rows,) + case.x.shape[1:], case.x.dtype)
+        x_rows[rows] = case.x
+        d_x = to_dev(x_rows)
+    ws = torch.empty(tm.team_moe_workspace_size(case.cfg), dtype=torch.uint8, device=DEV)
+    y = torch.full((n_rows or T, s.H), 7.0, dtype=out_dtype(s), device=DEV)
+    e_a = torch.full((s.E,), 9, dtype=torch.uint8, device=DEV)
+    n_a = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+    rep = torch.full((T,), -7, dtype=torch.int32, device=DEV)
+    n_u = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+    w = case.d_w
+    tm.team_moe_layer_forward_ex(case.cfg, d_x, y, T, w["router"], w["gate"], w["up"], w["down"], ws,
+                                 row_index=None if rows is None else torch.from_numpy(rows).to(DEV), n_rows=n_rows,
+                                 token_class=torch.from_numpy(token_class).to(DEV), activated_mask_out=e_a, n_activated_out=n_a,
+                                 unique_rows=True, row_rep_out=rep, n_unique_out=n_u)
+    torch.cuda.synchronize()
+    o_rep = orc.row_representatives(case.x)
+    assert np.array_equal(rep.cpu().numpy(), o_rep)
+    n_unique = int((o_rep == np.arange(T)).sum())
+    assert int(n_u.item()) == n_unique
+    if rows is not None:
+        live = torch.from_numpy(rows).long().to(DEV)
+        other = torch.ones(n_rows, dtype=torch.bool, device=DEV)
+        other[live] = False
+        assert (y[other] == 7.0).all()
+        y = y[live]
+    assert torch.equal(y, y[torch.from_numpy(o_rep).long().to(DEV)])
+    g_idx, g_gate, g_mask, g_n, _ = gpu_route_two_round(case, token_class)
+    mask = e_a.cpu().numpy()
+    assert np.array_equal(mask, g_mask) and int(n_a.item()) == g_n
+    o_logits = oracle_logits(case)
+    o_y, o_idx_m, _ = oracle_layer(case, mask, threads)
+    set_safe_m, _ = safe_tokens(o_logits, mask, s.k)
+    layer_err, n_band = check_layer(case, mask, y_to_host(y), g_idx, g_gate, o_y, o_idx_m, set_safe_m)
+    return {"n_unique": n_unique, "n_activated": g_n, "layer_err": layer_err, "band_tokens": n_band}

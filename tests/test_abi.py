@@ -135,8 +135,6 @@ def test_bad_call_arguments_are_rejected_before_any_launch():
         return lib.team_moe_layer_forward_ex(C.byref(cfg), C.byref(binding.LayerArgs(**base)))
     assert lib.team_moe_layer_forward_ex(C.byref(cfg), None) == -1
     assert ex(expert_mask=0x1000, token_class=0x1000) == -1
-    assert ex(unique_rows=1, token_class=0x1000) == -1
-    assert ex(unique_rows=1, row_index=0x1000, n_rows=16) == -1
     assert ex(unique_rows=2) == -1
     assert ex(row_rep_out=0x1000) == -1
     assert ex(n_activated_out=0x1000) == -1

@@ -641,6 +641,52 @@ def test_layer_calls_replay_from_a_hip_graph(cfg2_case, cfg2_w8):
 
 
 # ----------------------------------------------------------------------------- the variants combined in one call
+def classes_across_repeats(case, n_first, seed):
+    """Token classes in which a repeated row is first-round in one occurrence and cold in another, both ways round: for two
+    rows the first occurrence is cold and a later one first-round, for a third the first occurrence is first-round and all
+    later ones cold."""
+    T = case.shape.T
+    rep = orc.row_representatives(case.x)
+    cls = gen.token_classes(T, n_first, seed=seed)
+    later = np.nonzero(rep != np.arange(T))[0]
+    r0, r1, r2 = np.unique(rep[later])[:3]
+    for r in (r0, r1):
+        cls[r] = 0
+        cls[later[rep[later] == r][0]] = 1
+    cls[r2] = 1
+    cls[later[rep[later] == r2]] = 0
+    return cls
+
+
+@pytest.mark.parametrize("scatter", [None, 5])
+def test_combined_call_two_round_with_repeated_rows_of_branches(cfg2_case, scatter):
+    """Four candidate branches (128 tokens, 34 distinct rows), activated set decided on the device, distinct rows computed
+    once; dense and through a row index."""
+    case = branch_case(cfg2_case, seed=2)
+    cls = classes_across_repeats(case, 6, seed=4)
+    r = hz.two_round_unique_rows_parity(case, cls, scatter_seed=scatter)
+    assert r["n_unique"] == 34
+    say("two-round + repeated rows", scatter, r)
+
+
+def test_combined_call_two_round_with_repeated_rows_many_tokens():
+    """More tokens than one workgroup rebuilds the activated set for (the first-round picks are exchanged through memory),
+    with repeated rows among first-round and cold tokens; and a small call in float storage."""
+    s = gen.MoEShape("rep2r", T=300, H=256, E=32, k=4, I=128, dtype="bf16")
+    base = gen.make_x(gen.scaled(s, T=40), seed=3)
+    x = np.ascontiguousarray(base[gen.token_permutation(300, seed=6) % 40])
+    case = hz.Case.make(s, x, gen.make_weights(s, seed=3))
+    cls = classes_across_repeats(case, 3, seed=7)
+    r = hz.two_round_unique_rows_parity(case, cls)
+    assert r["n_unique"] == 40
+    say("two-round + repeated rows, 300 tokens", r)
+    say("  through a row index", hz.two_round_unique_rows_parity(case, cls, scatter_seed=8))
+    s1 = gen.scaled(gen.CFG1, T=12)
+    x1 = np.ascontiguousarray(gen.make_x(gen.CFG1, seed=0)[[0, 1, 0, 2, 1, 3, 3, 0, 4, 5, 4, 6]])
+    case1 = hz.Case.make(s1, x1, gen.make_weights(gen.CFG1, seed=0))
+    say("  fp32", hz.two_round_unique_rows_parity(case1, classes_across_repeats(case1, 2, seed=1), scatter_seed=1))
+
+
 def test_combined_call_live_rows_two_round_8bit_weights(cfg2_case, cfg2_w8):
     """Live rows of a block + activated set decided on the device + 8-bit weights in one call, against the same pieces
     called one by one: same E_A as the two-round router on the gathered rows, same bits as the 8-bit layer on the gathered
