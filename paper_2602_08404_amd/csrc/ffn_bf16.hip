@@ -48,6 +48,8 @@ static hipError_t launch_common(const Dims& d, FfnArgs& p, hipStream_t s) {
     // With at most 64 tokens per call an expert has at most 64 rows and the register-resident token operand is reused
     // across its items; beyond that the kernel decides on the device from the average number of rows per expert.
     p.tiled_min_avg_rows = d.T > 64 ? env_int("TEAM_MOE_FFN_TILED_ROWS", 16) : 0;      // override is a tuning aid only
+    const char* shares = getenv("TEAM_MOE_FFN_SHARES");     // tuning aid: "contiguous" = never deal workgroups out to experts
+    p.expert_major = shares && shares[0] == 'c' ? 0 : (shares && shares[0] == 'a' ? 2 : 1);
     p.stream = s;
     if (p.sg) {                       // 8-bit weights
         if (!p.su || !p.sd || !ffn_w8_supported(d.H, d.I)) return hipErrorInvalidValue;

@@ -174,7 +174,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                                                const uint16_t* __restrict__ x, const int32_t* __restrict__ sorted_token,
                                                const unsigned char* __restrict__ wg, const unsigned char* __restrict__ wu,
                                                const unsigned char* __restrict__ wd, uint16_t* __restrict__ h, float* __restrict__ out,
-                                               FfnCtrl* __restrict__ ctrl, int T, int E, int H, int I, int spin_limit,
+                                               FfnCtrl* __restrict__ ctrl, int T, int E, int H, int I, int spin_limit, int expert_major_ok,
                                                const float* __restrict__ sg, const float* __restrict__ su, const float* __restrict__ sd) {
     constexpr int KCOL = ROW_BYTES / WB;          // reduction columns per stage
     constexpr int XL = 2 * (2 / WB);              // 16-byte token loads per lane and stage = K-steps per stage
@@ -203,13 +203,38 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
             rd_w[rt][ks] = r * ROW_BYTES + (((4 * ks + q) ^ ((r >> 1) & 7)) << 4);
         }
 
+    // (decided once for both phases, from the gate/up list, so that a workgroup's down items belong to the expert whose
+    // gate/up items it and its neighbours have just finished)
+    bool expert_major = false;
+    if (expert_major_ok && n_act > 0 && n_act <= G) {
+        const uint32_t total_a = (uint32_t)n_act * (uint32_t)tiles_a;
+        const int need = (int)((total_a + (uint32_t)G - 1u) / (uint32_t)G);
+        expert_major = need <= TILES && (tiles_a % need != 0 || total_a % (uint32_t)G != 0u);
+    }
+
     for (int phase = 0; phase < 2; ++phase) {
         const int tiles = phase == 0 ? tiles_a : tiles_b;
         const int nks = (phase == 0 ? H : I) / KCOL;               // stages per (segment, pass)
         const uint32_t total = (uint32_t)n_act * (uint32_t)tiles;   // (at most FFN_MAX_E experts x 128 items: 32-bit arithmetic)
         // contiguous shares; the remainder goes to the lowest-numbered workgroups (see the register-operand body)
         const int share = (int)(total / (uint32_t)G), extra = (int)(total % (uint32_t)G), bx = (int)blockIdx.x;
-        const int li_begin = bx * share + min(bx, extra), li_end = li_begin + share + (bx < extra ? 1 : 0);
+        int li_begin = bx * share + min(bx, extra), li_end = li_begin + share + (bx < extra ? 1 : 0);
+        // A share that crosses from one expert into the next costs its workgroup a second, short segment: as many stages again
+        // for a fraction of the bytes, and those stages are bound by latency, not by bytes (a segment of one item keeps 12 KB in
+        // flight).  That workgroup then finishes late, and with it both experts it has a part of.  Where a share is a single
+        // segment, the workgroups are therefore dealt out to the experts instead (G / n_act each, one more for the first
+        // G % n_act), and an expert's items are cut evenly among its workgroups: shares differ by one item, none crosses.
+        if (expert_major && (phase == 0 || expert_major_ok == 1)) {
+            const int q_wg = G / n_act, r_wg = G % n_act, big = r_wg * (q_wg + 1);
+            int a, j, wgs;
+            if (bx < big) {
+                a = bx / (q_wg + 1); j = bx - a * (q_wg + 1); wgs = q_wg + 1;
+            } else {
+                a = r_wg + (bx - big) / q_wg; j = (bx - big) - (a - r_wg) * q_wg; wgs = q_wg;
+            }
+            li_begin = a * tiles + j * tiles / wgs;
+            li_end = a * tiles + (j + 1) * tiles / wgs;
+        }
         const size_t tile_stride = (phase == 0 ? (size_t)16 * H : (size_t)W_ROWS * I) * WB;   // bytes between the weight rows of adjacent items
 
         auto load_seg = [&](Seg& s) {                               // segment that starts at item s.li; skips experts without rows
