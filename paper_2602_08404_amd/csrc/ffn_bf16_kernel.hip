@@ -315,11 +315,10 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         // in LDS, instead of waiting for a separate grouping kernel.  Same method and same result as that kernel: a token
         // bitset per expert, popcount histogram, prefix sum, and the row of a pair = offset + number of lower tokens.
         constexpr int BW = FFN_LAYER_MAX_TOKENS / 32;                                     // words of a token bitset
-        static_assert(BW * FFN_MAX_E * 4 + 2 * FFN_MAX_E * 8 <= LDS_BYTES, "prologue tables fit the weight area");
+        static_assert(BW * FFN_MAX_E * 4 + 16 <= LDS_BYTES, "prologue tables fit the weight area");
         uint32_t* bits = reinterpret_cast<uint32_t*>(s_mem);                              // [E][BW]
-        unsigned long long(*scan)[FFN_MAX_E] = reinterpret_cast<unsigned long long(*)[FFN_MAX_E]>(s_mem + BW * FFN_MAX_E * 4);
-        for (int i = tid; i < BW * E; i += FFN_THREADS) bits[i] = 0u;
-        __syncthreads();
+        uint32_t* wave_total = reinterpret_cast<uint32_t*>(s_mem + BW * FFN_MAX_E * 4);   // [4]
+        // the table is requested first; clearing the bitsets and the barrier pass while it is on its way
         int my_e[FFN_LAYER_MAX_ROWS / FFN_THREADS];
 #pragma unroll
         for (int j = 0; j < FFN_LAYER_MAX_ROWS / FFN_THREADS; ++j) {
@@ -327,38 +326,48 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
             int e = r < A ? topk_idx[r] : -1;
             if (e >= E) e = -1;
             my_e[j] = e;
-            if (e >= 0) {
-                const int t = r / k;
-                atomicOr(&bits[BW * e + (t >> 5)], 1u << (t & 31));
-            }
         }
+        for (int i = tid; i < BW * E; i += FFN_THREADS) bits[i] = 0u;
         __syncthreads();
-        {
-            unsigned long long c = 0;
-            if (tid < E) {
-                unsigned cnt = 0;
 #pragma unroll
-                for (int w = 0; w < BW; ++w) cnt += __popc(bits[BW * tid + w]);
-                c = (unsigned long long)cnt | ((unsigned long long)(cnt > 0) << 32);     // low: rows, high: 1 if the expert has rows
+        for (int j = 0; j < FFN_LAYER_MAX_ROWS / FFN_THREADS; ++j) {
+            const int r = tid + j * FFN_THREADS;
+            if (my_e[j] >= 0) {
+                const int t = r / k;
+                atomicOr(&bits[BW * my_e[j] + (t >> 5)], 1u << (t & 31));
             }
-            scan[0][tid] = c;
         }
         __syncthreads();
-        int cur = 0;
-        for (int step = 1; step < FFN_MAX_E; step <<= 1) {
-            unsigned long long v = scan[cur][tid];
-            if (tid >= step) v += scan[cur][tid - step];
-            scan[cur ^ 1][tid] = v;
-            cur ^= 1;
-            __syncthreads();
-        }
+        // Prefix sums over the experts (thread = expert) of (rows, 1 if the expert has rows), packed as rows | flag << 16 (at most
+        // FFN_LAYER_MAX_ROWS rows and FFN_MAX_E experts in total, so neither field overflows): inside each wavefront with
+        // cross-lane moves, then the totals of the lower wavefronts through LDS.  One barrier instead of one per doubling step.
+        static_assert(FFN_LAYER_MAX_ROWS < 65536 && FFN_MAX_E < 65536 && FFN_THREADS == FFN_MAX_E && FFN_THREADS == 4 * WAVE,
+                      "packed prefix sum: one thread per expert, four wavefronts");
+        uint32_t c = 0;
         if (tid < E) {
-            const unsigned long long incl = scan[cur][tid], excl = tid ? scan[cur][tid - 1] : 0ull;
-            s_off[tid] = (int)(excl & 0xffffffffull);
-            if ((incl >> 32) != (excl >> 32)) s_slot_e[(int)(excl >> 32)] = tid;
+            unsigned cnt = 0;
+#pragma unroll
+            for (int w = 0; w < BW; ++w) cnt += __popc(bits[BW * tid + w]);
+            c = cnt | ((cnt > 0 ? 1u : 0u) << 16);
+        }
+        uint32_t incl = c;
+#pragma unroll
+        for (int d = 1; d < WAVE; d <<= 1) {
+            const uint32_t below = __shfl_up(incl, d, WAVE);
+            if (lane >= d) incl += below;
+        }
+        if (lane == WAVE - 1) wave_total[wave] = incl;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < 3; ++w)
+            if (w < wave) incl += wave_total[w];
+        const uint32_t excl = incl - c;
+        if (tid < E) {
+            s_off[tid] = (int)(excl & 0xffffu);
+            if ((incl >> 16) != (excl >> 16)) s_slot_e[(int)(excl >> 16)] = tid;
             if (tid == E - 1) {
-                s_off[E] = (int)(incl & 0xffffffffull);
-                s_nact = (int)(incl >> 32);
+                s_off[E] = (int)(incl & 0xffffu);
+                s_nact = (int)(incl >> 16);
             }
         }
         __syncthreads();

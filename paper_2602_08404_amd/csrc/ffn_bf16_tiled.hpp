@@ -302,9 +302,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
         };
 
         // ---------------------------------------------------------------- token producer: this lane's operand of a stage, in registers
-        Seg px;
-        px.li = li_begin;
-        load_seg(px);
+        Seg px = pw;                      // (the three cursors start at the same segment: looked up once)
         int px_ks = 0;
         const uint16_t* src_x = nullptr;  // row 16*wave + n of the pass, columns 8*q .. (bf16 weights) or 16*q .. (codes)
         int px_key = -1;                  // (slot, pass) src_x was built for
@@ -375,9 +373,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
         };
 
         // ---------------------------------------------------------------- consumer
-        Seg cs;
-        cs.li = li_begin;
-        load_seg(cs);
+        Seg cs = pw;
         int c_ks = 0;                     // stage inside the segment
         int pend = 0;                     // finished gate/up items of the current run (one slot) not yet published
         int pub_slot = -1, pub_cnt = 0, pub_mark = 0;   // run whose publication waits for its h stores to be acknowledged
