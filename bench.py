@@ -37,7 +37,7 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per ffn_fused_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/), keyed by
 # (workload, activated-set size); counters cannot be read from inside this script.
-PMC_TRAFFIC_BYTES = {("cfg2", 32): 306609997 + 2900434, ("cfg3", 32): 319346000 + 11553000, ("cfg5", 96): 625790000 + 20990000}
+PMC_TRAFFIC_BYTES = {("cfg2", 32): 306609997 + 2900434, ("cfg3", 32): 319283000 + 11553000, ("cfg5", 96): 625746000 + 20990000}
 
 
 def log(*a):

@@ -136,17 +136,52 @@ constexpr int X_AHEAD = 4;
 constexpr int MAX_COUNTED = 24;        // largest wait count used: (RING_STAGES - 1) stages of TILES + 2 loads, rounded up
 
 // Waits until at most n vector-memory operations of this wavefront are outstanding (n uniform; above MAX_COUNTED: until none).
+// The count is an immediate of the wait instruction, so a run-time count selects one of MAX_COUNTED + 1 instructions: a jump into
+// a table of (wait, branch to the end) pairs of 8 bytes each.  (Written as a switch, the compiler emitted a chain of some 60
+// scalar instructions and taken branches per call, a fifth of the time of a stage.)
 __device__ __forceinline__ void wait_outstanding_rt(int n) {
-#define TEAM_WAIT_CASE(N) \
-    case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
-    switch (n) {
-        TEAM_WAIT_CASE(1) TEAM_WAIT_CASE(2) TEAM_WAIT_CASE(3) TEAM_WAIT_CASE(4) TEAM_WAIT_CASE(5) TEAM_WAIT_CASE(6)
-        TEAM_WAIT_CASE(7) TEAM_WAIT_CASE(8) TEAM_WAIT_CASE(9) TEAM_WAIT_CASE(10) TEAM_WAIT_CASE(11) TEAM_WAIT_CASE(12)
-        TEAM_WAIT_CASE(13) TEAM_WAIT_CASE(14) TEAM_WAIT_CASE(15) TEAM_WAIT_CASE(16) TEAM_WAIT_CASE(17) TEAM_WAIT_CASE(18)
-        TEAM_WAIT_CASE(19) TEAM_WAIT_CASE(20) TEAM_WAIT_CASE(21) TEAM_WAIT_CASE(22) TEAM_WAIT_CASE(23) TEAM_WAIT_CASE(24)
-        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-    }
-#undef TEAM_WAIT_CASE
+    static_assert(MAX_COUNTED == 24, "the table below has entries 0 .. 24");
+    n = __builtin_amdgcn_readfirstlane(n);
+    const int entry = (unsigned)n > (unsigned)MAX_COUNTED ? 0 : n;
+    int offset;
+    asm volatile(
+        "s_getpc_b64 vcc\n"
+        ".Lteam_wait_pc%=:\n\t"
+        "s_lshl_b32 %0, %1, 3\n\t"
+        "s_add_u32 %0, %0, .Lteam_wait_table%=-.Lteam_wait_pc%=\n\t"
+        "s_add_u32 vcc_lo, vcc_lo, %0\n\t"
+        "s_addc_u32 vcc_hi, vcc_hi, 0\n\t"
+        "s_setpc_b64 vcc\n"
+        ".Lteam_wait_table%=:\n\t"
+        "s_waitcnt vmcnt(0)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(1)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(2)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(3)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(4)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(5)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(6)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(7)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(8)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(9)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(10)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(11)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(12)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(13)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(14)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(15)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(16)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(17)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(18)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(19)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(20)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(21)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(22)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(23)\n\ts_branch .Lteam_wait_end%=\n\t"
+        "s_waitcnt vmcnt(24)\n"
+        ".Lteam_wait_end%=:"
+        : "=&s"(offset)
+        : "s"(entry)
+        : "vcc", "scc", "memory");
 }
 // The four weight operands of an item's stage (two 16-row tiles x two K-steps) at byte addresses a0..a3.
 __device__ __forceinline__ void lds_read4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3, bf16x8_t& w0, bf16x8_t& w1, bf16x8_t& w2,
