@@ -295,6 +295,8 @@ def main() -> int:
     st_nact = torch.empty((1,), dtype=torch.int32, device=dev)
     st_out = torch.empty((A, H), dtype=torch.float32, device=dev)
 
+    ffn_spread = {}          # (M, w8) -> (median, min) of the per-launch event times in ms
+
     def time_ffn(M, calls, warmup, w8=False):
         """Average duration of team_moe_expert_ffn (one launch of the weight-streaming kernel) from HIP events on the launch stream."""
         evs = []
@@ -317,7 +319,21 @@ def main() -> int:
             if i >= warmup:
                 evs.append((e0, e1))
         torch.cuda.synchronize()
-        return float(np.mean([a.elapsed_time(b) for a, b in evs])) * 1e-3
+        ms = np.array([a.elapsed_time(b) for a, b in evs])
+        ffn_spread[(M, w8)] = (float(np.median(ms)), float(ms.min()))
+        return float(ms.mean()) * 1e-3
+
+    def chunked_step_times(M, chunks=20, per_chunk=20):
+        """Median and minimum over `chunks` groups of `per_chunk` back-to-back steps (seconds per step), outside the timed region."""
+        times = []
+        for c in range(chunks):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(per_chunk):
+                bench_step(c * per_chunk + i, M)
+            torch.cuda.synchronize()
+            times.append((time.perf_counter() - t0) / per_chunk)
+        return float(np.median(times)), float(np.min(times))
 
     # ---- headline: exactly `steps` timed steps between synchronisations
     if args.w8:
@@ -336,7 +352,8 @@ def main() -> int:
         wbytes = touched[M] * bytes_per_expert
         flops = 2.0 * A * 3 * H * I
         sweep.append({"activated": M, "touched": touched[M], "ms_per_layer": s_layer * 1e3, "tokens_per_s": T / s_step,
-                      "ffn_ms": s_ffn * 1e3, "weight_GBps_ffn": wbytes / s_ffn / 1e9, "weight_GBps_layer": wbytes / s_layer / 1e9,
+                      "ffn_ms": s_ffn * 1e3, "ffn_ms_median": ffn_spread[(M, args.w8)][0], "ffn_ms_min": ffn_spread[(M, args.w8)][1],
+                      "weight_GBps_ffn": wbytes / s_ffn / 1e9, "weight_GBps_layer": wbytes / s_layer / 1e9,
                       "ffn_TFLOPs": flops / s_ffn / 1e12, "mfma_frac": flops / s_ffn / 1e12 / MFMA_BF16_PEAK_TFLOPS})
         log(f"[bench] {wl} M={M}: layer {s_layer * 1e6:.1f} us, ffn {s_ffn * 1e6:.1f} us, touched {touched[M]:.1f}, "
             f"ffn weight stream {wbytes / s_ffn / 1e9:.0f} GB/s, {flops / s_ffn / 1e12:.1f} TFLOP/s")
@@ -485,6 +502,9 @@ def main() -> int:
            "device_copy_GBps": copy_gbps}
     if wl == "cfg4":
         out["ms_per_block_16_steps"] = sec_per_step * 1e3 * 16
+    else:
+        med, mn = chunked_step_times(headline)
+        out["ms_per_step_median"], out["ms_per_step_min"] = med * 1e3, mn * 1e3
     print(json.dumps(out), flush=True)
     return 0
 
