@@ -44,6 +44,7 @@ struct FfnArgs {
     int grid_override;          // > 0: use a smaller grid than the resident maximum (tuning aid)
     int spin_limit;
     int tiled_min_avg_rows;     // > 0: switch to the streaming variant when the call averages at least this many rows per expert
+    int wide_min_avg_rows;      // streaming variant: above this many rows per expert on average, two token tiles per wavefront
     int expert_major;           // 1: shares that would cross expert boundaries are replaced by whole workgroups per expert (see the kernel)
     hipStream_t stream;
 };

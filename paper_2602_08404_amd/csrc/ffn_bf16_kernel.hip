@@ -268,7 +268,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                                                                    const unsigned char* __restrict__ wg, const unsigned char* __restrict__ wu,
                                                                    const unsigned char* __restrict__ wd, uint16_t* __restrict__ h,
                                                                    float* __restrict__ out, FfnCtrl* __restrict__ ctrl, int T, int k, int E,
-                                                                   int spin_limit, int tiled_min_avg_rows, int expert_major_ok,
+                                                                   int spin_limit, int tiled_min_avg_rows, int expert_major_ok, int wide_min_avg_rows,
                                                                    const int32_t* __restrict__ topk_idx, int32_t* __restrict__ inv_pos_out,
                                                                    const float* __restrict__ sg, const float* __restrict__ su,
                                                                    const float* __restrict__ sd) {
@@ -400,8 +400,21 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         __syncthreads();
         const int total_rows = s_off[E];
         if (n_act > 0 && (long long)total_rows >= (long long)tiled_min_avg_rows * n_act) {
-            tiled::ffn_tiled_body<tiled::RING_STAGES, tiled::X_AHEAD, WB>(s_mem, s_slot_e, s_off, lds_tokens ? s_sorted : nullptr, n_act, x,
-                                                                          sorted_token, wg, wu, wd, h, out, ctrl, T, E, H, I, spin_limit, expert_major_ok, sg, su, sd);
+            // More than wide_min_avg_rows rows per expert on average: two token tiles per wavefront (128 rows per pass), so that
+            // most experts take one pass over their weights instead of two (bf16 weights; uniform over the launch).
+            bool wide = false;
+            if constexpr (WB == 2) wide = wide_min_avg_rows > 0 && (long long)total_rows > (long long)wide_min_avg_rows * n_act;
+            if constexpr (WB == 2) {
+                if (wide) {
+                    tiled::ffn_tiled_body<tiled::RING_STAGES, tiled::X_AHEAD, WB, 2>(s_mem, s_slot_e, s_off, lds_tokens ? s_sorted : nullptr, n_act, x,
+                                                                                     sorted_token, wg, wu, wd, h, out, ctrl, T, E, H, I, spin_limit,
+                                                                                     expert_major_ok, sg, su, sd);
+                    return;
+                }
+            }
+            tiled::ffn_tiled_body<tiled::RING_STAGES, tiled::X_AHEAD, WB, 1>(s_mem, s_slot_e, s_off, lds_tokens ? s_sorted : nullptr, n_act, x,
+                                                                             sorted_token, wg, wu, wd, h, out, ctrl, T, E, H, I, spin_limit,
+                                                                             expert_major_ok, sg, su, sd);
             return;
         }
     }
@@ -717,7 +730,7 @@ hipError_t launch_ffn_fused(const FfnArgs& p) {
     const int grid = p.grid_override > 0 && p.grid_override < resident ? p.grid_override : resident;
     hipLaunchKernelGGL((ffn_fused_kernel<KSA, KSB, RB, WB>), dim3(grid), dim3(FFN_THREADS), 0, p.stream, p.x, p.offsets, p.sorted_token,
                        p.active, p.n_active, (const unsigned char*)p.wg, (const unsigned char*)p.wu, (const unsigned char*)p.wd, p.h, p.out,
-                       p.ctrl, p.T, p.k, p.E, p.spin_limit, p.tiled_min_avg_rows, p.expert_major, p.topk_idx, p.inv_pos_out, p.sg, p.su,
+                       p.ctrl, p.T, p.k, p.E, p.spin_limit, p.tiled_min_avg_rows, p.expert_major, p.wide_min_avg_rows, p.topk_idx, p.inv_pos_out, p.sg, p.su,
                        p.sd);
     return hipGetLastError();
 }

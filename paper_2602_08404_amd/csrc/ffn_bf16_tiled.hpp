@@ -204,18 +204,23 @@ __device__ __forceinline__ void lds_read4(uint32_t a0, uint32_t a1, uint32_t a2,
 // stage holds 128 reduction columns (the same 128 bytes per weight row), a 16-byte LDS read carries the operands of two K-steps
 // (widened to bf16 in registers), a lane's token operand of a stage is 4 x 16 bytes, and the row scales multiply the sums in
 // the epilogues.
-template <int DW, int DX, int WB>
+template <int DW, int DX, int WB, int NT>
 __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_slot_e, const int32_t* s_off, const uint16_t* s_sorted, int n_act,
                                                const uint16_t* __restrict__ x, const int32_t* __restrict__ sorted_token,
                                                const unsigned char* __restrict__ wg, const unsigned char* __restrict__ wu,
                                                const unsigned char* __restrict__ wd, uint16_t* __restrict__ h, float* __restrict__ out,
                                                FfnCtrl* __restrict__ ctrl, int T, int E, int H, int I, int spin_limit, int expert_major_ok,
                                                const float* __restrict__ sg, const float* __restrict__ su, const float* __restrict__ sd) {
+    asm volatile("; team_tiled_body_begin" ::: "memory");   // (marks for the checks of the generated code: a kernel holds two instances)
     constexpr int KCOL = ROW_BYTES / WB;          // reduction columns per stage
+    // NT token tiles per wavefront: a pass covers MTT = NT x 64 rows of the expert (tile j of wavefront w: rows 64 j + 16 w ..).
+    // With two tiles an expert of 65 to 128 rows takes one pass instead of two, at about 1.3 times the cost of a stage.
+    constexpr int MTT = MT * NT;
+    static_assert(NT == 1 || (NT == 2 && WB == 2), "two token tiles per wavefront: bf16 weights only (registers)");
     constexpr int XL = 2 * (2 / WB);              // 16-byte token loads per lane and stage = K-steps per stage
     // The tokens of a stage are requested before its weights (DX >= DW), so "everything up to the weights of the stage" is
     // what a stage waits for.
-    static_assert(DX >= DW && (DW - 1) * (TILES + XL) <= MAX_COUNTED, "token requests lead the weight requests; wait counts fit");
+    static_assert(DX >= DW && (DW - 1) * (TILES + NT * XL) <= MAX_COUNTED, "token requests lead the weight requests; wait counts fit");
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -291,7 +296,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
             }
         };
         auto next_seg = [&](Seg& s) {
-            if ((s.pass + 1) * MT < s.m) {
+            if ((s.pass + 1) * MTT < s.m) {
                 ++s.pass;
             } else {
                 s.li += s.nw;
@@ -339,7 +344,9 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
         // ---------------------------------------------------------------- token producer: this lane's operand of a stage, in registers
         Seg px = pw;                      // (the three cursors start at the same segment: looked up once)
         int px_ks = 0;
-        const uint16_t* src_x = nullptr;  // row 16*wave + n of the pass, columns 8*q .. (bf16 weights) or 16*q .. (codes)
+        const uint16_t* src_x[NT];        // per token tile: row 64*j + 16*wave + n of the pass, columns 8*q .. (bf16 weights) or 16*q .. (codes)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) src_x[j] = nullptr;
         int px_key = -1;                  // (slot, pass) src_x was built for
         int ready_slot = -1;              // down phase: slot whose h is known to be complete
         auto px_enter = [&]() {           // new (segment, pass): uniform control flow
@@ -360,46 +367,52 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
             const int key = px.a * 64 + px.pass;
             if (key != px_key) {
                 px_key = key;
-                int row = px.pass * MT + 16 * wave + n;
-                if (row >= px.m) row = px.pass * MT;               // rows beyond the expert's last: a valid row, result unused
-                if (phase == 0) {
-                    // (from the kernel's LDS copy when there is one; a load from global memory waits for every load in flight)
-                    int tok = s_sorted ? lds_read_u16(lds_addr(s_sorted) + 2 * (px.r0 + row)) : sorted_token[px.r0 + row];
-                    tok = min(max(tok, 0), T - 1);
-                    src_x = x + (size_t)tok * H + q * (16 / WB);
-                } else {
-                    src_x = h + (size_t)(px.r0 + row) * I + q * (16 / WB);
+#pragma unroll
+                for (int j = 0; j < NT; ++j) {
+                    int row = px.pass * MTT + j * MT + 16 * wave + n;
+                    if (row >= px.m) row = px.pass * MTT;              // rows beyond the expert's last: a valid row, result unused
+                    if (phase == 0) {
+                        // (from the kernel's LDS copy when there is one; a load from global memory waits for every load in flight)
+                        int tok = s_sorted ? lds_read_u16(lds_addr(s_sorted) + 2 * (px.r0 + row)) : sorted_token[px.r0 + row];
+                        tok = min(max(tok, 0), T - 1);
+                        src_x[j] = x + (size_t)tok * H + q * (16 / WB);
+                    } else {
+                        src_x[j] = h + (size_t)(px.r0 + row) * I + q * (16 / WB);
+                    }
                 }
             }
         };
         // Token operands of the next DX stages.  K-step s of a stage meets, in lane group q, the 8 columns 32 s + 8 q .. (bf16
         // weights) or 64 (s / 2) + 16 q + 8 (s % 2) .. (codes: a lane's 16-byte LDS read holds 16 consecutive columns, used as two
         // K-steps); any assignment of columns to K-steps is a valid order of the sum as long as both operands use it.
-        bf16x8_t xq[DX][XL];
-        auto produce_x = [&](bf16x8_t (&dst)[XL]) {                 // (only while px.valid)
-            const uint16_t* p = src_x + px_ks * KCOL;
-            if constexpr (WB == 2) {
-                if (phase == 0) {
-                    request_tokens<false, 0>(dst[0], p);
-                    request_tokens<false, 64>(dst[1], p);
+        bf16x8_t xq[DX][NT][XL];
+        auto produce_x = [&](bf16x8_t (&dst)[NT][XL]) {             // (only while px.valid)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                const uint16_t* p = src_x[j] + px_ks * KCOL;
+                if constexpr (WB == 2) {
+                    if (phase == 0) {
+                        request_tokens<false, 0>(dst[j][0], p);
+                        request_tokens<false, 64>(dst[j][1], p);
+                    } else {
+                        request_tokens<true, 0>(dst[j][0], p);
+                        request_tokens<true, 64>(dst[j][1], p);
+                    }
                 } else {
-                    request_tokens<true, 0>(dst[0], p);
-                    request_tokens<true, 64>(dst[1], p);
-                }
-            } else {
-                if (phase == 0) {
-                    request_tokens<false, 0>(dst[0], p);
-                    request_tokens<false, 16>(dst[1], p);
-                    request_tokens<false, 128>(dst[2], p);
-                    request_tokens<false, 144>(dst[3], p);
-                } else {
-                    request_tokens<true, 0>(dst[0], p);
-                    request_tokens<true, 16>(dst[1], p);
-                    request_tokens<true, 128>(dst[2], p);
-                    request_tokens<true, 144>(dst[3], p);
+                    if (phase == 0) {
+                        request_tokens<false, 0>(dst[j][0], p);
+                        request_tokens<false, 16>(dst[j][1], p);
+                        request_tokens<false, 128>(dst[j][2], p);
+                        request_tokens<false, 144>(dst[j][3], p);
+                    } else {
+                        request_tokens<true, 0>(dst[j][0], p);
+                        request_tokens<true, 16>(dst[j][1], p);
+                        request_tokens<true, 128>(dst[j][2], p);
+                        request_tokens<true, 144>(dst[j][3], p);
+                    }
                 }
             }
-            issued += XL;
+            issued += NT * XL;
             if (++px_ks == nks) {
                 px_ks = 0;
                 next_seg(px);
@@ -412,9 +425,11 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
         int c_ks = 0;                     // stage inside the segment
         int pend = 0;                     // finished gate/up items of the current run (one slot) not yet published
         int pub_slot = -1, pub_cnt = 0, pub_mark = 0;   // run whose publication waits for its h stores to be acknowledged
-        f32x4_t acc[TILES][2];
+        f32x4_t acc[TILES][NT][2];
 #pragma unroll
-        for (int t = 0; t < TILES; ++t) acc[t][0] = acc[t][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < TILES; ++t)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) acc[t][j][0] = acc[t][j][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
         // Requests in front of the loop: the tokens of the first DX stages and the weights of the first DW - 1.  Gate/up phase:
         // tokens first, as inside the loop.  Down phase: the weights first, because the tokens (h) have to wait for other
@@ -465,24 +480,30 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                         bf16x8_t w00, w10, w01, w11;
                         lds_read4(wt + rd_w[0][0], wt + rd_w[1][0], wt + rd_w[0][1], wt + rd_w[1][1], w00, w10, w01, w11);
                         if constexpr (WB == 2) {
-                            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w00, xq[u][0], acc[t][0], 0, 0, 0);
-                            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w10, xq[u][0], acc[t][1], 0, 0, 0);
-                            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w01, xq[u][1], acc[t][0], 0, 0, 0);
-                            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w11, xq[u][1], acc[t][1], 0, 0, 0);
+#pragma unroll
+                            for (int j = 0; j < NT; ++j) {
+                                acc[t][j][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w00, xq[u][j][0], acc[t][j][0], 0, 0, 0);
+                                acc[t][j][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w10, xq[u][j][0], acc[t][j][1], 0, 0, 0);
+                            }
+#pragma unroll
+                            for (int j = 0; j < NT; ++j) {
+                                acc[t][j][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w01, xq[u][j][1], acc[t][j][0], 0, 0, 0);
+                                acc[t][j][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w11, xq[u][j][1], acc[t][j][1], 0, 0, 0);
+                            }
                         } else {                                    // each read: the codes of two K-steps
                             bf16x8_t a0, a1, b0, b1;
                             widen_e4m3(w00, a0, a1);
                             widen_e4m3(w10, b0, b1);
-                            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, xq[u][0], acc[t][0], 0, 0, 0);
-                            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0, xq[u][0], acc[t][1], 0, 0, 0);
-                            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, xq[u][1], acc[t][0], 0, 0, 0);
-                            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1, xq[u][1], acc[t][1], 0, 0, 0);
+                            acc[t][0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, xq[u][0][0], acc[t][0][0], 0, 0, 0);
+                            acc[t][0][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0, xq[u][0][0], acc[t][0][1], 0, 0, 0);
+                            acc[t][0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, xq[u][0][1], acc[t][0][0], 0, 0, 0);
+                            acc[t][0][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1, xq[u][0][1], acc[t][0][1], 0, 0, 0);
                             widen_e4m3(w01, a0, a1);
                             widen_e4m3(w11, b0, b1);
-                            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, xq[u][2], acc[t][0], 0, 0, 0);
-                            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0, xq[u][2], acc[t][1], 0, 0, 0);
-                            acc[t][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, xq[u][3], acc[t][0], 0, 0, 0);
-                            acc[t][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1, xq[u][3], acc[t][1], 0, 0, 0);
+                            acc[t][0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, xq[u][0][2], acc[t][0][0], 0, 0, 0);
+                            acc[t][0][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0, xq[u][0][2], acc[t][0][1], 0, 0, 0);
+                            acc[t][0][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, xq[u][0][3], acc[t][0][0], 0, 0, 0);
+                            acc[t][0][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1, xq[u][0][3], acc[t][0][1], 0, 0, 0);
                         }
                     }
                 }
@@ -491,9 +512,12 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                 if (++c_ks < nks) return true;
                 // (6) last stage of the (segment, pass): epilogue for this wavefront's token tile
                 c_ks = 0;
-                const int row = cs.pass * MT + 16 * wave + n;
 #pragma unroll
                 for (int t = 0; t < TILES; ++t) {
+#pragma unroll
+                  for (int j = 0; j < NT; ++j) {
+                    const int row = cs.pass * MTT + j * MT + 16 * wave + n;
+                    f32x4_t (&ac)[2] = acc[t][j];
                     if (t < cs.nw && row < cs.m) {
                         const int it = cs.it + t;
                         if constexpr (WB == 1) {                    // row scales of the item (read through the scalar cache: see load_scales)
@@ -503,10 +527,10 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                                 load_scales(su + (size_t)cs.e * I + it * 16, u16);
 #pragma unroll
                                 for (int rt = 0; rt < 2; ++rt) {
-                                    acc[t][rt][0] *= pick_q(g16, 8 * rt, 2, q);
-                                    acc[t][rt][1] *= pick_q(g16, 8 * rt + 1, 2, q);
-                                    acc[t][rt][2] *= pick_q(u16, 8 * rt, 2, q);
-                                    acc[t][rt][3] *= pick_q(u16, 8 * rt + 1, 2, q);
+                                    ac[rt][0] *= pick_q(g16, 8 * rt, 2, q);
+                                    ac[rt][1] *= pick_q(g16, 8 * rt + 1, 2, q);
+                                    ac[rt][2] *= pick_q(u16, 8 * rt, 2, q);
+                                    ac[rt][3] *= pick_q(u16, 8 * rt + 1, 2, q);
                                 }
                             } else {
 #pragma unroll
@@ -514,7 +538,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                                     float d16[16];                  // scales of output rows it*32 + rt*16 .. +15
                                     load_scales(sd + (size_t)cs.e * H + it * W_ROWS + rt * 16, d16);
 #pragma unroll
-                                    for (int j = 0; j < 4; ++j) acc[t][rt][j] *= pick_q(d16, j, 4, q);
+                                    for (int c = 0; c < 4; ++c) ac[rt][c] *= pick_q(d16, c, 4, q);
                                 }
                             }
                         }
@@ -522,19 +546,20 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
 #pragma unroll
                             for (int rt = 0; rt < 2; ++rt) {
                                 // lane holds (g_a, g_b, u_a, u_b) of intermediate indices it*16 + rt*8 + 2*q, +1 for token row `row`
-                                const float h0 = silu_f32(acc[t][rt][0]) * acc[t][rt][2];
-                                const float h1 = silu_f32(acc[t][rt][1]) * acc[t][rt][3];
+                                const float h0 = silu_f32(ac[rt][0]) * ac[rt][2];
+                                const float h1 = silu_f32(ac[rt][1]) * ac[rt][3];
                                 const uint32_t packed = f32_to_bf16_bits(h0) | (f32_to_bf16_bits(h1) << 16);
                                 store_coherent(reinterpret_cast<uint32_t*>(h + (size_t)(cs.r0 + row) * I + it * 16 + rt * 8 + 2 * q), packed);
                             }
                         } else {
 #pragma unroll
                             for (int rt = 0; rt < 2; ++rt)   // lane holds output rows it*32 + rt*16 + 4*q + (0..3) of token row `row`
-                                *reinterpret_cast<f32x4_t*>(out + (size_t)(cs.r0 + row) * H + it * W_ROWS + rt * 16 + 4 * q) = acc[t][rt];
+                                *reinterpret_cast<f32x4_t*>(out + (size_t)(cs.r0 + row) * H + it * W_ROWS + rt * 16 + 4 * q) = ac[rt];
                         }
                     }
-                    acc[t][0] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                    acc[t][1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    ac[0] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    ac[1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                  }
                 }
                 const int prev_a = cs.a, prev_li = cs.li, prev_nw = cs.nw;
                 next_seg(cs);
@@ -561,6 +586,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
         wg_barrier();
         if (pub_slot >= 0 && tid == 0) __hip_atomic_fetch_add(&ctrl->done[pub_slot][0], pub_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    asm volatile("; team_tiled_body_end" ::: "memory");
 }
 
 }  // namespace tiled

@@ -32,13 +32,42 @@ def registers(line: str) -> Set[int]:
     return regs
 
 
+BODY_BEGIN, BODY_END = "; team_tiled_body_begin", "; team_tiled_body_end"
+
+
+def streaming_bodies(lines: List[str]) -> List[List[str]]:
+    """The instances of the streaming body inside a kernel function (the source marks where each begins and ends; they use
+    different registers for their requests, so each is checked on its own); the whole function if it carries no marks."""
+    bodies, cur = [], None
+    for l in lines:
+        if l == BODY_BEGIN:
+            cur = []
+        elif l == BODY_END and cur is not None:
+            bodies.append(cur)
+            cur = None
+        elif cur is not None:
+            cur.append(l)
+    return bodies if bodies else [lines]
+
+
 def in_flight_register_uses(lines: List[str]) -> Tuple[int, List[str]]:
+    """Sum over the instances of the streaming body in a kernel function; see in_flight_register_uses_of_body."""
+    total, found = 0, []
+    for body in streaming_bodies(lines):
+        n, v = in_flight_register_uses_of_body(body)
+        total += n
+        found += v
+    return total, found
+
+
+def in_flight_register_uses_of_body(lines: List[str]) -> Tuple[int, List[str]]:
     """(number of pipelined token-load groups found, violations).
 
     A group = the consecutive explicit token loads of one stage (both halves, both load flavours) with the last explicit
     counted wait (N > 0) in front of them; its window = from that wait to the loads.  From the first request in front of the
     loop to the last one inside it, a group's destination registers may be touched by compiler-generated instructions only inside its
-    window, and there only by matrix instructions."""
+    window: there the data has arrived (the matrix instructions read it, and once they have, the compiler may reuse the registers,
+    e.g. for the address of the next request); anywhere else a request into them is still in flight."""
     in_asm = False
     events = []          # (index, kind, payload): 'load' (regs), 'wait' (N), 'ins' (text)
     for i, l in enumerate(lines):
@@ -99,7 +128,7 @@ def in_flight_register_uses(lines: List[str]) -> Tuple[int, List[str]]:
             if not touched:
                 continue
             inside = wait_pos < pos < first
-            if not inside or not payload.startswith("v_mfma_"):
+            if not inside:
                 violations.append(f"line {idx}: {payload}  (registers {sorted(touched)[:4]}.. of the loads at line {events[first][0]})")
     return len(pipelined), violations
 
