@@ -47,7 +47,7 @@ static hipError_t launch_common(const Dims& d, FfnArgs& p, hipStream_t s) {
     p.spin_limit = 1 << 16;          // ~0.1 s of polling; a wait this long means the control block was not zeroed
     // With at most 32 tokens per call an expert has at most 32 rows: one pass of the register-resident token operand, which is
     // reused across the expert's items.  Beyond that the kernel decides on the device from the average number of rows per expert.
-    p.tiled_min_avg_rows = d.T > 32 ? env_int("TEAM_MOE_FFN_TILED_ROWS", 16) : 0;      // override is a tuning aid only
+    p.tiled_min_avg_rows = d.T > 32 ? env_int("TEAM_MOE_FFN_TILED_ROWS", 18) : 0;      // override is a tuning aid only
     p.wide_min_avg_rows = env_int("TEAM_MOE_FFN_WIDE_ROWS", 56);                    // override is a tuning aid only
     const char* shares = getenv("TEAM_MOE_FFN_SHARES");     // tuning aid: "contiguous" = never deal workgroups out to experts
     p.expert_major = shares && shares[0] == 'c' ? 0 : (shares && shares[0] == 'a' ? 2 : 1);

@@ -221,7 +221,7 @@ def test_bf16_more_than_1024_routed_rows(H, I, body, monkeypatch):
 @pytest.mark.parametrize("H,I,E,k,T,M", [(512, 256, 16, 4, 128, 3), (2048, 768, 32, 8, 96, 9), (256, 128, 8, 2, 200, 1), (1024, 512, 64, 6, 160, 40),
                                          (2048, 768, 128, 8, 64, 16), (1024, 256, 32, 8, 33, 5), (512, 384, 16, 4, 48, 2)])
 def test_bf16_streaming_body_many_rows_per_expert(H, I, E, k, T, M):
-    """Calls of more than 32 tokens that average 16 or more rows per expert run the kernel's streaming body.  Few allowed experts
+    """Calls of more than 32 tokens that average 18 or more rows per expert run the kernel's streaming body.  Few allowed experts
     give experts with more than 64 rows (several passes of 64 token rows over the same weights: 128 rows per expert in the
     first case, 200 in the third) and few items per workgroup (segments of one item, workgroups without work); the last case
     has 24 rows per expert and segments of up to four items.  The last three are calls of 33 to 64 tokens (two candidate branches
