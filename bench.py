@@ -152,6 +152,8 @@ def main() -> int:
                     help="time the layer on 8-bit expert weights (E4M3 codes + row scales) instead of bf16 weights (not the headline)")
     ap.add_argument("--block-x", choices=["structured", "drift"], default="structured",
                     help="block workload: hidden states with a component shared by the rows of the block (default), or independent rows")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="cfg2 / cfg5 only: another number of tokens per call than the configuration's (a look beyond the listed workloads)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     args = ap.parse_args()
@@ -177,6 +179,9 @@ def main() -> int:
         "cfg4": (gen.CFG4, "drift", 0.0552, (24,), 24),
         "cfg5": (gen.CFG5, "iid", 0.0, (256, 96, 48), 96),
     }[wl]
+    if args.tokens > 0:
+        assert wl in ("cfg2", "cfg5") and args.tokens <= 1024, "--tokens: cfg2 / cfg5, at most 1024 tokens per call"
+        shape = gen.scaled(shape, T=args.tokens)
     mask_sizes = tuple(sorted({int(v) for v in args.masks.split(",") if v} | {headline}, reverse=True)) if args.masks else default_masks
     T, H, E, k, I = shape.T, shape.H, shape.E, shape.k, shape.I
     A = T * k
@@ -494,6 +499,8 @@ def main() -> int:
                 f"activated set of {headline} per (layer, step); a step = one pass over the stack",
         "cfg5": f"cfg5: fine-grained layer (H=2048, E=256, top-8, I=512, bf16), 256 tokens, activated set M={headline}, {n_sets} weight sets rotated",
     }[wl]
+    if args.tokens > 0:
+        desc = f"{wl} shape at {T} tokens per call instead of the configuration's (not a listed workload): " + desc
     out = {"metric": "moe_layer_tokens_per_s", "value": T / sec_per_step, "unit": "tokens/s", "n_gpus": 1, "steps": steps,
            "warmup": warmup, "ms_per_step": sec_per_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "bf16", "data": "synthetic" + (" (expert weights stored as E4M3 codes with row scales)" if args.w8 else ""),
