@@ -11,15 +11,17 @@
 //            down   : (expert, 32 output rows of w_down), all I columns
 //   segment  up to TILES consecutive items of a workgroup's share that belong to one expert, worked on together: the token
 //            rows are fetched once per segment, not once per item (that traffic, from L2, is otherwise twice the weights')
-//   pass     64 token rows of the expert (4 token tiles, one per wavefront); experts with more rows take
-//            several passes over the same weight rows (served by the caches after the first pass)
+//   pass     64 token rows of the expert (4 token tiles, one per wavefront), or 128 in the instance with two token tiles per
+//            wavefront (calls with many rows per expert); experts with more rows take several passes over the same weight
+//            rows (served by the caches after the first pass)
 //   stage    64 reduction columns of a segment: 32 weight rows x 128 B = 4 KB per item
 // Weights: a ring of RING_STAGES stages in LDS; every wavefront issues one 1 KB direct-to-LDS load per item and stage (8
 // weight rows), RING_STAGES-1 stages (up to 48 KB per workgroup) ahead of the stage being multiplied, also across segment
-// boundaries.  Tokens: a
-// wavefront owns a token tile and loads its own MFMA operand of a stage (16 bytes per lane and K-step, straight from the
-// L2-resident x or h rows) into registers, X_AHEAD stages ahead.  It multiplies the tile with both 16-row weight tiles of
-// every item of the segment: no reduction across wavefronts, sums in a fixed order.
+// boundaries.  Tokens: a wavefront owns one or two token tiles and loads its own MFMA operands of a stage (16 bytes per lane,
+// tile and K-step, straight from the L2-resident x or h rows) into registers, X_AHEAD stages ahead.  It multiplies them with
+// both 16-row weight tiles of every item of the segment: no reduction across wavefronts, sums in a fixed order.
+// Shares: the phase's item list is cut contiguously over the workgroups, or, where a share is a single segment and such a
+// cut would cross expert boundaries, the workgroups are dealt out to the experts (see ffn_tiled_body).
 //
 // LDS stage layout: rows of 128 B (8 chunks of 16 B); chunk c of row r is stored at chunk c ^ ((r >> 1) & 7),
 // which spreads the 16 rows of an MFMA operand read over all 16 bank groups.  The swizzle is applied to the
