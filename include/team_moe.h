@@ -156,9 +156,9 @@ int team_moe_classify_tokens(const float* conf, const uint8_t* state, int32_t n_
  * Two-round routing of Algorithm 1 ("Limited Activation for cold tokens") in one call.
  *   token_class [T] bytes: non-zero = first-round token (a newly accepted token of D_a or a hot token of H, which may
  *                          activate experts); zero = cold token of C.
- *   round 1: every first-round token is routed over all experts E_0 exactly as team_moe_route with expert_mask == NULL;
+ *   first round: every first-round token is routed over all experts E_0 exactly as team_moe_route with expert_mask == NULL;
  *   E_A     = the union of the experts those tokens selected;
- *   round 2: every cold token is routed exactly as team_moe_route with expert_mask = E_A.
+ *   second round: every cold token is routed exactly as team_moe_route with expert_mask = E_A.
  *   topk_idx / topk_gate [T,k]: W = Concat(W_1, W_2), one row per token in token order, same conventions as
  *                               team_moe_route (cold tokens have min(k, |E_A|) valid slots).
  *   activated_mask_out [E] bytes (1 = in E_A) and n_activated_out [1] (= |E_A|): optional, may be NULL.

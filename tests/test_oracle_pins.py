@@ -186,14 +186,14 @@ def test_two_round_routing_is_algorithm_1(seed, renorm):
     mask, idx, gate = orc.route_two_round(logits, k, first, renorm)
     fr = np.nonzero(first)[0]
     cold = np.nonzero(first == 0)[0]
-    # round 1 = free routing of the first-round tokens (brute force: full sort of their logits)
+    # first round = free routing of the first-round tokens (brute force: full sort of their logits)
     for t in fr:
         assert idx[t].tolist() == sorted(range(E), key=lambda e: (-logits[t, e], e))[:k]
     # E_A = union of their picks, nothing else
     union = np.zeros(E, np.uint8)
     union[np.unique(idx[fr])] = 1
     np.testing.assert_array_equal(mask, union)
-    # round 2 = routing confined to E_A: cold tokens only pick inside it, and pick its best members
+    # second round = routing confined to E_A: cold tokens only pick inside it, and pick its best members
     assert mask[idx[cold][idx[cold] >= 0]].all()
     allowed = [e for e in range(E) if mask[e]]
     for t in cold:
