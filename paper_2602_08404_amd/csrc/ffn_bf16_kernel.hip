@@ -315,9 +315,11 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         // in LDS, instead of waiting for a separate grouping kernel.  Same method and same result as that kernel: a token
         // bitset per expert, popcount histogram, prefix sum, and the row of a pair = offset + number of lower tokens.
         constexpr int BW = FFN_LAYER_MAX_TOKENS / 32;                                     // words of a token bitset
-        static_assert(BW * FFN_MAX_E * 4 + 16 <= LDS_BYTES, "prologue tables fit the weight area");
+        constexpr int BS = BW | 1;                // words from one expert's bitset to the next: odd, so that threads working on
+                                                  // different experts read different LDS banks
+        static_assert(BS * FFN_MAX_E * 4 + 16 <= LDS_BYTES, "prologue tables fit the weight area");
         uint32_t* bits = reinterpret_cast<uint32_t*>(s_mem);                              // [E][BW]
-        uint32_t* wave_total = reinterpret_cast<uint32_t*>(s_mem + BW * FFN_MAX_E * 4);   // [4]
+        uint32_t* wave_total = reinterpret_cast<uint32_t*>(s_mem + BS * FFN_MAX_E * 4);   // [4]
         // the table is requested first; clearing the bitsets and the barrier pass while it is on its way
         int my_e[FFN_LAYER_MAX_ROWS / FFN_THREADS];
 #pragma unroll
@@ -327,14 +329,14 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
             if (e >= E) e = -1;
             my_e[j] = e;
         }
-        for (int i = tid; i < BW * E; i += FFN_THREADS) bits[i] = 0u;
+        for (int i = tid; i < BS * E; i += FFN_THREADS) bits[i] = 0u;
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < FFN_LAYER_MAX_ROWS / FFN_THREADS; ++j) {
             const int r = tid + j * FFN_THREADS;
             if (my_e[j] >= 0) {
                 const int t = r / k;
-                atomicOr(&bits[BW * my_e[j] + (t >> 5)], 1u << (t & 31));
+                atomicOr(&bits[BS * my_e[j] + (t >> 5)], 1u << (t & 31));
             }
         }
         __syncthreads();
@@ -347,7 +349,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
         if (tid < E) {
             unsigned cnt = 0;
 #pragma unroll
-            for (int w = 0; w < BW; ++w) cnt += __popc(bits[BW * tid + w]);
+            for (int w = 0; w < BW; ++w) cnt += __popc(bits[BS * tid + w]);
             c = cnt | ((cnt > 0 ? 1u : 0u) << 16);
         }
         uint32_t incl = c;
@@ -383,7 +385,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                 int rank = 0;                                       // tokens of this expert below t
 #pragma unroll
                 for (int w = 0; w < BW; ++w) {
-                    const uint32_t b = bits[BW * e + w];
+                    const uint32_t b = bits[BS * e + w];
                     rank += w < (t >> 5) ? __popc(b) : (w == (t >> 5) ? __popc(b & ((1u << (t & 31)) - 1u)) : 0);
                 }
                 pos = s_off[e] + rank;
