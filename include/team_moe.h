@@ -136,6 +136,22 @@ int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T,
                            const uint8_t* expert_mask, void* y, void* workspace, size_t ws_bytes, void* stream);
 
 /*
+ * team_moe_layer_forward for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The intermediates live in a static array of
+ * TEAM_MOE_STATIC_SCRATCH_BYTES bytes of device memory that is part of the library's code object (every GPU the library runs
+ * on holds its own copy until the process ends); the call allocates and frees nothing.  Same arguments, results and errors as
+ * team_moe_layer_forward, except: a configuration whose team_moe_workspace_size exceeds TEAM_MOE_STATIC_SCRATCH_BYTES is
+ * rejected with TEAM_ERR_WORKSPACE (the 32-token and 128-token configurations of a 2048 x 768 x 128-expert layer fit; 256
+ * tokens do not), and failing to locate the array on the current device gives TEAM_ERR_HIP.  All calls on one GPU share the
+ * array: calls that overlap in time on one GPU (different streams or threads) race on it and must be serialised by the caller.
+ * Nothing in the array has to survive from one call to the next.
+ */
+#define TEAM_MOE_STATIC_SCRATCH_BYTES (16u << 20)
+int team_moe_layer_forward_static(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router,
+                                  const void* w_gate, const void* w_up, const void* w_down,
+                                  const uint8_t* expert_mask, void* y, void* stream);
+
+/*
  * Step 1 of Algorithm 1: classification of the live tokens of a denoising step (Eq. 4 of Section "Speculative Exploration for
  * Hot Tokens", with the reading of Section "Experimental Setup": "no more than L_h positions away").
  *   conf  [n_rows] float : confidence c_k of the current decoding attempt of every row (read for masked rows only)

@@ -21,6 +21,7 @@ EXPORTS = ["team_moe_workspace_size", "team_moe_route", "team_moe_build_dispatch
            "team_moe_combine", "team_moe_layer_forward", "team_moe_route_two_round", "team_moe_layer_forward_two_round",
            "team_moe_classify_tokens", "team_moe_layer_forward_rows", "team_moe_layer_forward_unique_rows",
            "team_moe_expert_ffn_w8", "team_moe_layer_forward_w8", "team_moe_dequantize_w8", "team_moe_layer_forward_ex",
+           "team_moe_layer_forward_static",
            "team_moe_status_string"]
 
 
@@ -69,6 +70,7 @@ def lib() -> C.CDLL:
         L.team_moe_expert_ffn.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_combine.argtypes = [cfgp, vp, vp, vp, i32, vp, vp]
         L.team_moe_layer_forward.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.team_moe_layer_forward_static.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.team_moe_route_two_round.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_layer_forward_two_round.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_classify_tokens.argtypes = [vp, vp, i32, i32, vp, i32, C.c_float, i32, vp, vp]
@@ -144,6 +146,12 @@ def team_moe_layer_forward(cfg: Config, x, T: int, w_router, w_gate, w_up, w_dow
     _check(lib().team_moe_layer_forward(C.byref(cfg), _ptr(x), T, _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
                                         _ptr(expert_mask), _ptr(y), _ptr(workspace), ws_bytes,
                                         stream if stream is not None else _stream()), "team_moe_layer_forward")
+
+
+def team_moe_layer_forward_static(cfg: Config, x, T: int, w_router, w_gate, w_up, w_down, expert_mask, y, stream=None) -> None:
+    _check(lib().team_moe_layer_forward_static(C.byref(cfg), _ptr(x), T, _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+                                               _ptr(expert_mask), _ptr(y), stream if stream is not None else _stream()),
+           "team_moe_layer_forward_static")
 
 
 def team_moe_route_two_round(cfg: Config, x, T: int, w_router, token_class, activated_mask_out, n_activated_out, topk_idx, topk_gate,

@@ -7,6 +7,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <atomic>
+
 namespace {
 
 using team::Dims;
@@ -320,6 +322,43 @@ int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T,
                            const void* w_up, const void* w_down, const uint8_t* expert_mask, void* y, void* workspace,
                            size_t ws_bytes, void* stream) {
     return layer_forward(cfg, x, T, w_router, w_gate, w_up, w_down, expert_mask, nullptr, nullptr, nullptr, y, workspace, ws_bytes,
+                         stream);
+}
+
+// ---- the layer for callers that cannot allocate: the workspace is a static device array ----------------------------------
+namespace {
+
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)TEAM_MOE_STATIC_SCRATCH_BYTES;
+constexpr int STATIC_MAX_DEVICES = 64;
+// One copy of this array exists on every GPU the library runs on, from the moment its code object is loaded there until the
+// process ends.  In host code the name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+std::atomic<void*> g_scratch_ptr[STATIC_MAX_DEVICES];      // per device: where that device's copy of `scratch` lives
+
+// Address of the current device's copy of `scratch` (looked up once per device, with that device current).
+int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return TEAM_ERR_HIP;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_status(e == hipSuccess ? hipErrorInvalidSymbol : e);
+        g_scratch_ptr[dev].store(p, std::memory_order_release);      // (two first callers store the same address)
+    }
+    *out = p;
+    return TEAM_OK;
+}
+
+}  // namespace
+
+int team_moe_layer_forward_static(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router, const void* w_gate,
+                                  const void* w_up, const void* w_down, const uint8_t* expert_mask, void* y, void* stream) {
+    int st = check_cfg(cfg);
+    if (st != TEAM_OK) return st;
+    if (layout_of(cfg).total > STATIC_SCRATCH_BYTES) return TEAM_ERR_WORKSPACE;     // this configuration needs more than the array holds
+    void* ws = nullptr;
+    if ((st = static_scratch(&ws)) != TEAM_OK) return st;
+    return layer_forward(cfg, x, T, w_router, w_gate, w_up, w_down, expert_mask, nullptr, nullptr, nullptr, y, ws, STATIC_SCRATCH_BYTES,
                          stream);
 }
 
