@@ -57,9 +57,20 @@ void oracle_router_logits(const float *x, const float *w_router, int T, int H, i
         for (int e = 0; e < E; ++e) logits[(size_t)t * E + e] = (float)dot(x + (size_t)t * H, w_router + (size_t)e * H, H);
 }
 
+/* Order of the selection: a larger logit ranks first; a NaN logit ranks below every number, -infinity included (the paper
+ * says nothing about non-finite scores; with this reading a NaN is taken only when fewer than k_eff numbers are allowed, and
+ * the token's gates then come out NaN by the arithmetic below, so a broken input shows in the output instead of vanishing).
+ * Equal logits (+0 and -0 are equal) and two NaNs do not rank before each other: the caller keeps the lower id. */
+static int ranks_before(float a, float b) {
+    if (isnan(b)) return !isnan(a);
+    return a > b;
+}
+
 /* Selection and gates of ONE token from its fp32 logits.
  * idx[k]: selected expert ids in order (logit descending, id ascending), -1 padded.
- * gate[k]: routing weights in the same order, 0 padded.  Returns k_eff. */
+ * gate[k]: routing weights in the same order, 0 padded.  Returns k_eff.
+ * Non-finite logits: the formulas are evaluated as they stand in IEEE arithmetic (exp(inf - inf) and anything with a NaN
+ * give NaN gates for the token). */
 static int route_token(const float *logit, int E, int k, int renormalize, const uint8_t *mask, int32_t *idx, double *gate) {
     int n_allowed = 0;
     for (int e = 0; e < E; ++e) n_allowed += (mask == NULL || mask[e] != 0);
@@ -72,7 +83,7 @@ static int route_token(const float *logit, int E, int k, int renormalize, const 
             int taken = 0;
             for (int j = 0; j < s; ++j) taken |= (idx[j] == e);
             if (taken) continue;
-            if (best < 0 || logit[e] > logit[best]) best = e;   /* strict '>' keeps the lower id on ties */
+            if (best < 0 || ranks_before(logit[e], logit[best])) best = e;   /* strict order keeps the lower id on ties */
         }
         idx[s] = best;
     }

@@ -154,6 +154,70 @@ def test_ties_go_to_lower_id_and_zero_router_gives_uniform_gates():
     assert idx.tolist() == [[1, 2]]
 
 
+def _brute_force_route(logit_row, allowed, k, renorm):
+    """Selection by a full sort on (is NaN, -value, id) and the gate formulas in NumPy fp64 (IEEE propagation)."""
+    z = logit_row.astype(np.float64)
+    cand = [e for e in range(len(z)) if allowed[e]]
+    order = sorted(cand, key=lambda e: (1, 0.0, e) if np.isnan(z[e]) else (0, -z[e], e))[:k]
+    idx = np.full(k, -1, np.int32)
+    idx[:len(order)] = order
+    gate = np.zeros(k)
+    with np.errstate(all="ignore"):
+        if order:
+            sel = z[order]
+            if renorm:
+                w = np.exp(sel - sel[0])
+                gate[:len(order)] = w / w.sum()
+            else:
+                m = z[0]
+                for v in z[1:]:
+                    m = v if v > m else m
+                gate[:len(order)] = np.exp(sel - m) / np.exp(z - m).sum()
+    return idx, gate
+
+
+@pytest.mark.parametrize("renorm", [1, 0])
+def test_non_finite_logits_rank_last_and_show_in_the_gates(renorm):
+    """Reading for scores that are not numbers (the paper is silent): NaN ranks below every number, ties by id, gates by
+    the formulas in IEEE arithmetic.  Pinned by a full sort and by hand cases."""
+    nan, inf = np.float32("nan"), np.float32("inf")
+    # hand cases, k = 3 of 6 experts
+    rows = np.array([[nan, 1.0, 2.0, nan, 0.5, -1.0],          # NaNs first and in the middle: never among 3 of 4 numbers
+                     [nan, nan, 1.0, nan, nan, 2.0],           # two numbers only: then the lowest-id NaN
+                     [nan, nan, nan, nan, nan, nan],           # all NaN: ids 0, 1, 2
+                     [-inf, 3.0, inf, 0.0, -0.0, nan],         # +inf first; -inf still before NaN
+                     [-inf, -inf, nan, -inf, nan, nan],        # -inf ranks before NaN
+                     [0.0, -0.0, 0.0, -0.0, 0.0, -0.0]], np.float32)
+    idx, gate = orc.route_from_logits(rows, 3, renorm, None)
+    assert idx.tolist() == [[2, 1, 4], [5, 2, 0], [0, 1, 2], [2, 1, 3], [0, 1, 3], [0, 1, 2]]
+    assert np.isfinite(gate[0]).all() == (renorm == 1)        # full softmax: a NaN anywhere in the row makes every gate NaN
+    assert np.isnan(gate[1]).all() and np.isnan(gate[2]).all() and np.isnan(gate[3]).all()
+    if renorm:
+        assert np.isnan(gate[4]).all()                         # exp(-inf - (-inf))
+        np.testing.assert_allclose(gate[5], 1.0 / 3.0, rtol=1e-15)
+    # a masked-out NaN does not matter under renormalisation
+    mask = np.array([0, 1, 1, 0, 1, 1], np.uint8)
+    idx_m, gate_m = orc.route_from_logits(rows[:1], 3, 1, mask)
+    assert idx_m.tolist() == [[2, 1, 4]] and np.isfinite(gate_m).all() and abs(gate_m.sum() - 1) < 1e-12
+    # random rows with planted specials against the full sort
+    r = np.random.default_rng(77)
+    E, k = 12, 5
+    logits = r.standard_normal((60, E)).astype(np.float32)
+    specials = np.array([nan, inf, -inf, 0.0, -0.0], np.float32)
+    for t in range(60):
+        n_sp = int(r.integers(0, E + 1)) if t % 3 == 0 else int(r.integers(0, 4))
+        pos = r.choice(E, n_sp, replace=False)
+        logits[t, pos] = specials[r.integers(0, len(specials), n_sp)]
+    for M in (None, 7, 3):
+        mask = None if M is None else gen.random_mask(E, M, seed=M)
+        allowed = np.ones(E, bool) if mask is None else mask != 0
+        idx, gate = orc.route_from_logits(logits, k, renorm, mask)
+        for t in range(60):
+            b_idx, b_gate = _brute_force_route(logits[t], allowed, k, renorm)
+            assert idx[t].tolist() == b_idx.tolist(), (M, t, logits[t])
+            np.testing.assert_allclose(gate[t], b_gate, rtol=1e-12, atol=0, equal_nan=True)
+
+
 # ----------------------------------------------------------------------------- P6 superset invariance (Algorithm 1)
 @pytest.mark.parametrize("renorm", [1, 0])
 def test_superset_invariance(renorm):
