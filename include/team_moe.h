@@ -27,6 +27,17 @@
  *     a launch the runtime rejects -> TEAM_ERR_HIP.  On error nothing has been enqueued.
  *   - Results are deterministic: same inputs give bit-identical outputs (no floating-point atomics).
  *   - Calls that share a workspace must be ordered on one stream (or otherwise serialised).
+ *   - One expert-FFN launch per device at a time.  team_moe_expert_ffn and every team_moe_layer_forward* call run one
+ *     persistent kernel whose grid fills the whole device and whose workgroups wait for each other (the down projection of an
+ *     expert starts when its gate/up projection is complete).  Two such kernels in flight on one device at once - calls on
+ *     different streams, or from different processes - can keep each other's workgroups off the compute units they need.
+ *     The waits are bounded (about 0.1 s): a wait that gives up marks the workspace (team_moe_workspace_status), and the
+ *     rows it could not compute are stored as NaN, so the failure cannot pass for a result.  Order such calls on one stream,
+ *     or serialise them, and they never wait longer than the producers take to run.
+ *   - Router scores that are not numbers.  The paper leaves them undefined; here a NaN score ranks below every number (ties
+ *     by the lower expert id, as for equal numbers), so it is selected only when fewer than top_k numbers are allowed, and
+ *     the gates are the softmax formulas evaluated in IEEE arithmetic: a token that selects a NaN or an infinite score gets
+ *     NaN gates and a NaN row of y; with renormalize == 0 a NaN score anywhere in the token's row does the same.
  *
  * Limits: 1 <= top_k <= 16, top_k <= num_experts <= 256, max_tokens <= 1024.
  *   TEAM_BF16: hidden in {256,512,1024,2048}, inter a multiple of 128 with inter <= 1024.
@@ -47,7 +58,8 @@ typedef enum {
     TEAM_ERR_INVALID_ARG = -1,
     TEAM_ERR_UNSUPPORTED = -2,
     TEAM_ERR_WORKSPACE = -3,
-    TEAM_ERR_HIP = -4
+    TEAM_ERR_HIP = -4,
+    TEAM_ERR_TIMEOUT = -5        /* only from team_moe_workspace_status: a wait inside a kernel gave up */
 } team_status;
 
 typedef enum { TEAM_F32 = 0, TEAM_BF16 = 1 } team_dtype;
@@ -64,8 +76,22 @@ typedef struct {
     int32_t reserved;     /* must be 0 */
 } team_moe_config;
 
-/* Bytes of workspace that team_moe_layer_forward (and every other entry point) needs for `cfg`. */
+/* Bytes of workspace that team_moe_layer_forward (and every other entry point) needs for `cfg`.  The contents of a
+ * workspace need no initialisation. */
 int team_moe_workspace_size(const team_moe_config* cfg, size_t* bytes);
+
+/*
+ * Has a kernel that used `workspace` given up a wait for another workgroup since the last call of this function?  (See
+ * "One expert-FFN launch per device at a time" above; in correct use the answer is always no.)
+ * Unlike every other entry point this one SYNCHRONISES: it waits for the work queued on `stream` (a hipStream_t), reads
+ * the first bytes of the workspace (its status area, the same for every configuration: ws_bytes >= 256), and, if it finds
+ * the failure mark, removes it.  Returns TEAM_OK (no failure), TEAM_ERR_TIMEOUT (a wait gave up: the outputs of that call
+ * hold NaN in the rows that could not be computed; the mark is removed, so a failure is reported once),
+ * TEAM_ERR_WORKSPACE (bad pointer or size) or TEAM_ERR_HIP (the copy failed).  It does not allocate.
+ * workspace == NULL asks about the static array that team_moe_layer_forward_static uses on the current device.
+ * A workspace that was never passed to a kernel holds arbitrary bytes; they are not mistaken for the mark (a 64-bit pattern).
+ */
+int team_moe_workspace_status(void* workspace, size_t ws_bytes, void* stream);
 
 /*
  * Router restricted to the activated-expert set (Algorithm 1, "Router(C, E_A)"; with expert_mask == NULL it
@@ -77,7 +103,9 @@ int team_moe_workspace_size(const team_moe_config* cfg, size_t* bytes);
  *   topk_gate[t, s]        = routing weight of slot s (see cfg->renormalize); 0 in padded slots
  *   logits_out [T,E]       = the logits, if the caller wants them; with NULL they are kept in `workspace`
  *                            (required then: team_moe_workspace_size bytes; may be NULL when logits_out is given)
- * An all-zero mask gives topk_idx = -1 and gates 0 everywhere.  A NaN logit is never selected.
+ * An all-zero mask gives topk_idx = -1 and gates 0 everywhere.  Scores that are not numbers: see the conventions above.
+ * The signature has two arguments more than the five-call outline of the layer (workspace, ws_bytes): the selection kernel
+ * reads the scores back, so they need a place when the caller does not ask for them.
  */
 int team_moe_route(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router,
                    const uint8_t* expert_mask /* [E] bytes or NULL */, int32_t* topk_idx /* [T,k] */,
@@ -85,9 +113,8 @@ int team_moe_route(const team_moe_config* cfg, const void* x, int32_t T, const v
                    size_t ws_bytes, void* stream);
 
 /*
- * Token-to-expert grouping of the routing table (the paper leaves this implicit: "each activated expert is
- * typically responsible for only a small number of tokens", Section "Speculative Exploration for Hot
- * Tokens").  Integer only, bit-exact.
+ * Token-to-expert grouping of the routing table.  The paper leaves this step implicit; Section "Speculative Exploration
+ * for Hot Tokens (SEH)" describes its result, a handful of tokens per activated expert.  Integer only, bit-exact.
  *   expert_offsets[E+1]  exclusive prefix sum of the number of (token,slot) pairs assigned to each expert
  *   sorted_token[T*k]    token id of every row, rows of one expert contiguous and in ascending token id;
  *                        entries beyond expert_offsets[E] are -1
@@ -95,9 +122,7 @@ int team_moe_route(const team_moe_config* cfg, const void* x, int32_t T, const v
  *   active_experts[E]    ids of the experts with at least one row, ascending, padded with -1
  *   n_active[1]          their number
  * Entries of topk_idx outside [0,E) are treated as padding.
- * `workspace` may be NULL.  If it is given (same buffer and size rules as for team_moe_expert_ffn), the call also
- * prepares in it the small control block team_moe_expert_ffn starts from; one preparation serves one
- * team_moe_expert_ffn call.
+ * `workspace` / `ws_bytes` are not used (the grouping works in on-chip memory only); pass NULL / 0 or anything else.
  */
 int team_moe_build_dispatch(const team_moe_config* cfg, const int32_t* topk_idx, int32_t T,
                             int32_t* expert_offsets, int32_t* sorted_token, int32_t* inv_pos,
@@ -105,15 +130,19 @@ int team_moe_build_dispatch(const team_moe_config* cfg, const int32_t* topk_idx,
                             void* stream);
 
 /*
- * Grouped SwiGLU expert FFN over the experts listed in active_experts only.
+ * Grouped SwiGLU expert FFN over the experts listed in active_experts only: the step whose cost the paper's method
+ * reduces.  Section "Delayed Caching for Decoded Tokens" places block decoding in the memory-bound regime and Section
+ * "Speculative Exploration for Hot Tokens (SEH)" attributes the latency to the feed-forward layers, each activated expert
+ * serving few tokens: the time of this call is the time to read the listed experts' weights once.
  * For every row p in [expert_offsets[e], expert_offsets[e+1]) of an active expert e, with t = sorted_token[p]:
  *   g = w_gate[e] x[t],  u = w_up[e] x[t],  h = silu(g) * u  (silu(z) = z / (1 + exp(-z))),
  *   expert_out[p,:] = w_down[e] h                              (float, [T*k, H]; rows >= expert_offsets[E]
  *                                                               are left untouched)
  * TEAM_BF16: products on bf16 MFMA with float accumulation; h is rounded to bf16 between the two GEMMs.
  * Weights of experts that are not listed are not read.
- * `workspace` must be the buffer that the team_moe_build_dispatch call which produced these tables was given
- * (it prepared the control block this call consumes); TEAM_F32 needs no preparation.
+ * `workspace`: team_moe_workspace_size bytes (the call uses its first part: status area, control block, h).  The call
+ * is self-contained: it prepares what it needs in the workspace itself and may be repeated, or follow any other call.
+ * If a wait inside the kernel gives up (see the conventions), the rows of expert_out it could not compute are NaN.
  */
 int team_moe_expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, const int32_t* expert_offsets,
                         const int32_t* sorted_token, const int32_t* active_experts, const int32_t* n_active,
@@ -121,7 +150,7 @@ int team_moe_expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, co
                         void* workspace, size_t ws_bytes, void* stream);
 
 /*
- * Gate-weighted combine: y[t,:] = sum_{s ascending, inv_pos[t,s] >= 0} topk_gate[t,s] * expert_out[inv_pos[t,s],:]
+ * Gate-weighted combine with the routing weights W that Algorithm 1 returns (Concat(W_1, W_2)): y[t,:] = sum_{s ascending, inv_pos[t,s] >= 0} topk_gate[t,s] * expert_out[inv_pos[t,s],:]
  * in float, then cast to cfg->dtype (round to nearest even).  Tokens with no valid slot get y = 0.
  */
 int team_moe_combine(const team_moe_config* cfg, const float* expert_out, const float* topk_gate,
@@ -129,7 +158,9 @@ int team_moe_combine(const team_moe_config* cfg, const float* expert_out, const 
 
 /*
  * The whole layer on one stream: route -> build_dispatch -> expert_ffn -> combine, all intermediates in
- * `workspace`.  y [T,H] in cfg->dtype.
+ * `workspace`.  y [T,H] in cfg->dtype.  This is the MoE layer of one denoising step with routing confined to the
+ * activated set: Algorithm 1's "Router(C, E_A)" followed by the experts of E_A weighted with W (Section "Limited
+ * Activation for Cold Tokens (LAC)"); expert_mask == NULL is the unrestricted layer of the baseline decoder.
  */
 int team_moe_layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const void* w_router,
                            const void* w_gate, const void* w_up, const void* w_down,
@@ -153,7 +184,8 @@ int team_moe_layer_forward_static(const team_moe_config* cfg, const void* x, int
 
 /*
  * Step 1 of Algorithm 1: classification of the live tokens of a denoising step (Eq. 4 of Section "Speculative Exploration for
- * Hot Tokens", with the reading of Section "Experimental Setup": "no more than L_h positions away").
+ * Hot Tokens (SEH)"; where Eq. 4's strict, universally quantified distance condition and the wording of Section "Experimental
+ * Setup" differ, the latter is followed: some decoded row within L_h positions, L_h itself included).
  *   conf  [n_rows] float : confidence c_k of the current decoding attempt of every row (read for masked rows only)
  *   state [n_rows] bytes : 0 = masked, 1 = decoded in an earlier step, 2 = newly accepted in the previous step (D_a)
  *   rows [b*block_len, (b+1)*block_len) form one block (or one speculative branch of it); distances are taken inside a block
@@ -200,8 +232,8 @@ int team_moe_layer_forward_two_round(const team_moe_config* cfg, const void* x, 
 
 /*
  * The layer over the live rows of larger tensors, without a gather by the caller (Section "Delayed Caching for Decoded
- * Tokens": at each iteration only the masked tokens and the tokens newly accepted in the previous step are computed; the
- * other rows of the block keep their cached results).
+ * Tokens": a step computes the masked rows and the rows accepted one step earlier; rows decoded before that keep what was
+ * cached for them).
  *   x_rows, y_rows [n_rows, H] in cfg->dtype; row_index [T] int32 lists the rows this call computes: token t of the call
  *   reads x_rows[row_index[t]] and writes y_rows[row_index[t]].  Rows that are not listed are neither read nor written.
  *   Entries outside [0, n_rows) are clamped into that range on the device; if a row is listed twice, which of the two equal
@@ -297,6 +329,8 @@ typedef struct {
     void* workspace;                /* team_moe_workspace_size(cfg) bytes, 256-byte aligned */
     size_t ws_bytes;
     void* stream;                   /* hipStream_t */
+    void* ffn_begin_event;          /* both NULL, or two hipEvent_t created by the caller: recorded on `stream` directly before and */
+    void* ffn_end_event;            /* after the expert FFN kernel of this call, so that a caller can time that kernel inside the layer */
 } team_moe_layer_args;
 
 /* `args` is a host pointer and is not retained.  Returns a team_status; unsupported combinations: TEAM_ERR_INVALID_ARG. */

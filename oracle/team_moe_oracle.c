@@ -128,8 +128,8 @@ void oracle_route_two_round(const float *logits, int T, int E, int k, int renorm
 }
 
 /* Classification of the live tokens of a step (Algorithm 1, step 1; hot tokens as in Eq. 4 of Section "Speculative Exploration
- * for Hot Tokens", with the wording of Section "Experimental Setup": a masked token is hot if its confidence exceeds tau_h or
- * if it is no more than L_h positions away from a decoded token of its block).
+ * for Hot Tokens"; its distance condition is read with Section "Experimental Setup": a masked token is hot if its confidence
+ * exceeds tau_h or if some decoded token of its block lies within L_h positions, L_h included).
  *   state[p]: 0 masked, 1 decoded in an earlier step, 2 newly accepted in the previous step; conf[p]: confidence of the
  *   current decoding attempt (used for masked positions only); positions p of one block are the rows
  *   [b*block_len, (b+1)*block_len) and distances are taken inside a block.

@@ -21,7 +21,7 @@ EXPORTS = ["team_moe_workspace_size", "team_moe_route", "team_moe_build_dispatch
            "team_moe_combine", "team_moe_layer_forward", "team_moe_route_two_round", "team_moe_layer_forward_two_round",
            "team_moe_classify_tokens", "team_moe_layer_forward_rows", "team_moe_layer_forward_unique_rows",
            "team_moe_expert_ffn_w8", "team_moe_layer_forward_w8", "team_moe_dequantize_w8", "team_moe_layer_forward_ex",
-           "team_moe_layer_forward_static",
+           "team_moe_layer_forward_static", "team_moe_workspace_status", "team_moe_internal_set", "team_moe_internal_get",
            "team_moe_status_string"]
 
 
@@ -33,7 +33,7 @@ class LayerArgs(C.Structure):
                 ("expert_mask", C.c_void_p), ("token_class", C.c_void_p), ("activated_mask_out", C.c_void_p),
                 ("n_activated_out", C.c_void_p), ("unique_rows", C.c_int32), ("reserved", C.c_int32),
                 ("row_rep_out", C.c_void_p), ("n_unique_out", C.c_void_p), ("workspace", C.c_void_p), ("ws_bytes", C.c_size_t),
-                ("stream", C.c_void_p)]
+                ("stream", C.c_void_p), ("ffn_begin_event", C.c_void_p), ("ffn_end_event", C.c_void_p)]
 
 
 class TeamMoeError(RuntimeError):
@@ -70,6 +70,9 @@ def lib() -> C.CDLL:
         L.team_moe_expert_ffn.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_combine.argtypes = [cfgp, vp, vp, vp, i32, vp, vp]
         L.team_moe_layer_forward.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.team_moe_workspace_status.argtypes = [vp, sz, vp]
+        L.team_moe_internal_set.argtypes = [C.c_char_p, C.c_int]
+        L.team_moe_internal_get.argtypes = [C.c_char_p, C.POINTER(C.c_int)]
         L.team_moe_layer_forward_static.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.team_moe_route_two_round.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_layer_forward_two_round.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -154,6 +157,24 @@ def team_moe_layer_forward_static(cfg: Config, x, T: int, w_router, w_gate, w_up
            "team_moe_layer_forward_static")
 
 
+def team_moe_workspace_status(workspace, stream=None) -> int:
+    """Returns the team_status (0: no wait gave up; -5: one did, reported once).  Synchronises the stream.  workspace None: the
+    static array of team_moe_layer_forward_static."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    return int(lib().team_moe_workspace_status(_ptr(workspace), ws_bytes, stream if stream is not None else _stream()))
+
+
+def internal_set(key: str, value: int) -> None:
+    """Tuning / testing knob of include/team_moe_internal.h."""
+    _check(lib().team_moe_internal_set(key.encode(), int(value)), f"team_moe_internal_set({key})")
+
+
+def internal_get(key: str) -> int:
+    v = C.c_int(0)
+    _check(lib().team_moe_internal_get(key.encode(), C.byref(v)), f"team_moe_internal_get({key})")
+    return int(v.value)
+
+
 def team_moe_route_two_round(cfg: Config, x, T: int, w_router, token_class, activated_mask_out, n_activated_out, topk_idx, topk_gate,
                              logits_out=None, workspace=None, stream=None) -> None:
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
@@ -220,11 +241,13 @@ def team_moe_dequantize_w8(codes, scale, rows: int, cols: int, out, stream=None)
 
 def team_moe_layer_forward_ex(cfg: Config, x, y, T: int, w_router, w_gate, w_up, w_down, workspace, *, row_index=None, n_rows: int = 0,
                               scales=None, expert_mask=None, token_class=None, activated_mask_out=None, n_activated_out=None,
-                              unique_rows: bool = False, row_rep_out=None, n_unique_out=None, stream=None) -> None:
-    """Keyword arguments select the variants; `scales` = (scale_gate, scale_up, scale_down) tensors for 8-bit weights."""
+                              unique_rows: bool = False, row_rep_out=None, n_unique_out=None, stream=None, ffn_events=None) -> None:
+    """Keyword arguments select the variants; `scales` = (scale_gate, scale_up, scale_down) tensors for 8-bit weights;
+    `ffn_events` = (begin, end) hipEvent_t handles recorded around the expert FFN kernel."""
     sg, su, sd = scales if scales is not None else (None, None, None)
     a = LayerArgs(_ptr(x), _ptr(y), T, n_rows, _ptr(row_index), _ptr(w_router), _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(sg), _ptr(su),
                   _ptr(sd), _ptr(expert_mask), _ptr(token_class), _ptr(activated_mask_out), _ptr(n_activated_out), 1 if unique_rows else 0, 0,
                   _ptr(row_rep_out), _ptr(n_unique_out), _ptr(workspace),
-                  0 if workspace is None else workspace.numel() * workspace.element_size(), stream if stream is not None else _stream())
+                  0 if workspace is None else workspace.numel() * workspace.element_size(), stream if stream is not None else _stream(),
+                  None if ffn_events is None else ffn_events[0], None if ffn_events is None else ffn_events[1])
     _check(lib().team_moe_layer_forward_ex(C.byref(cfg), C.byref(a)), "team_moe_layer_forward_ex")

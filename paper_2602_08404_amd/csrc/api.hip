@@ -3,6 +3,7 @@
 #include "../../include/team_moe.h"
 
 #include "kernels.hpp"
+#include "tuning.hpp"
 
 #include <stdio.h>
 #include <stdlib.h>
@@ -46,16 +47,18 @@ Dims dims_of(const team_moe_config* c, int32_t T) {
     return d;
 }
 
-// Workspace layout, sized for max_tokens.  The expert FFN's scratch (control block, h) comes first so that
-// team_moe_expert_ffn and team_moe_layer_forward agree on where it is.
+// Workspace layout, sized for max_tokens.  The status area comes first (team_moe_workspace_status reads it without knowing
+// the configuration), then the expert FFN's scratch (control block, h), so that team_moe_expert_ffn and
+// team_moe_layer_forward agree on where it is.
 struct Layout {
-    size_t ctrl, h, logits, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, two_round, x_dense, row_hash, row_rep, n_unique, total;
+    size_t status, ctrl, h, logits, topk_idx, topk_gate, offsets, sorted_token, inv_pos, active, n_active, expert_out, two_round, x_dense, row_hash, row_rep, n_unique, total;
 };
 Layout layout_of(const team_moe_config* c) {
     const size_t A = (size_t)c->max_tokens * c->top_k;
     const size_t elem = c->dtype == TEAM_BF16 ? 2 : 4;
     Layout L;
     size_t off = 0;
+    L.status = off;       off += team::WS_STATUS_BYTES;
     L.ctrl = off;         off += align256(team::ffn_ctrl_bytes());
     L.h = off;            off += align256(A * c->inter * elem);
     L.logits = off;       off += align256((size_t)c->max_tokens * c->num_experts * 4);
@@ -67,7 +70,7 @@ Layout layout_of(const team_moe_config* c) {
     L.active = off;       off += align256((size_t)c->num_experts * 4);
     L.n_active = off;     off += 256;
     L.expert_out = off;   off += align256(A * c->hidden * 4);
-    L.two_round = off;    off += 256;                       // bit set E_A and arrival counter of two-round routing
+    L.two_round = off;    off += 256;                       // bit set E_A of two-round routing (calls of more than 256 tokens)
     L.x_dense = off;      off += align256((size_t)c->max_tokens * c->hidden * elem);   // live rows gathered by the router (row-index calls)
     L.row_hash = off;     off += align256((size_t)c->max_tokens * 8);                  // repeated-row search of the router
     L.row_rep = off;      off += align256((size_t)c->max_tokens * 4);
@@ -87,10 +90,10 @@ inline int hip_status(hipError_t e) {
 
 int run_ffn(const team_moe_config* cfg, const Dims& d, const void* x, const int32_t* offsets, const int32_t* sorted_token,
             const int32_t* active, const int32_t* n_active, const void* wg, const void* wu, const void* wd, float* expert_out,
-            void* ctrl, void* h_ws, hipStream_t s, const team::W8Scales* w8 = nullptr) {
+            void* ctrl, unsigned long long* fail_mark, void* h_ws, hipStream_t s, const team::W8Scales* w8 = nullptr) {
     if (cfg->dtype == TEAM_BF16)
         return hip_status(team::launch_ffn_bf16(d, (const uint16_t*)x, offsets, sorted_token, active, n_active, wg, wu, wd, ctrl,
-                                                (uint16_t*)h_ws, expert_out, s, w8));
+                                                fail_mark, (uint16_t*)h_ws, expert_out, s, w8));
     if (w8) return TEAM_ERR_UNSUPPORTED;
     return hip_status(team::launch_ffn_f32(d, (const float*)x, offsets, sorted_token, active, n_active, (const float*)wg,
                                            (const float*)wu, (const float*)wd, (float*)h_ws, expert_out, s));
@@ -136,16 +139,11 @@ int team_moe_build_dispatch(const team_moe_config* cfg, const int32_t* topk_idx,
     if (st != TEAM_OK) return st;
     if ((st = check_T(cfg, T)) != TEAM_OK) return st;
     if (!topk_idx || !expert_offsets || !sorted_token || !inv_pos || !active_experts || !n_active) return TEAM_ERR_INVALID_ARG;
-    // With a workspace, the same kernel also prepares (clears) the control block the expert FFN starts from.
-    team::CtrlZero cz{nullptr, 0, 0};
-    if (workspace) {
-        const Layout L = layout_of(cfg);
-        if (!aligned16(workspace) || ws_bytes < L.logits) return TEAM_ERR_WORKSPACE;
-        if (cfg->dtype == TEAM_BF16) cz = team::ffn_ctrl_zero((char*)workspace + L.ctrl);
-    }
+    (void)workspace;                     // the grouping needs no scratch outside LDS
+    (void)ws_bytes;
     clear_stale_error();
     return hip_status(team::launch_dispatch(dims_of(cfg, T), topk_idx, expert_offsets, sorted_token, inv_pos, active_experts, n_active,
-                                            cz, (hipStream_t)stream));
+                                            team::CtrlZero{nullptr, 0, 0}, (hipStream_t)stream));
 }
 
 namespace {
@@ -172,8 +170,14 @@ int expert_ffn(const team_moe_config* cfg, const void* x, int32_t T, const int32
     const Layout L = layout_of(cfg);
     if (!workspace || !aligned16(workspace) || ws_bytes < L.logits /* = end of the control block + h segments */) return TEAM_ERR_WORKSPACE;
     clear_stale_error();
+    // The kernel's per-expert counters start from zero: cleared here by a small launch of its own, so that the call depends on
+    // nothing that ran before it (inside team_moe_layer_forward the router's selection kernel does it on the way).
+    if (cfg->dtype == TEAM_BF16 &&
+        (st = hip_status(team::launch_ffn_ctrl_clear((char*)workspace + L.ctrl, cfg->num_experts, (hipStream_t)stream))) != TEAM_OK)
+        return st;
     return run_ffn(cfg, dims_of(cfg, T), x, expert_offsets, sorted_token, active_experts, n_active, w_gate, w_up, w_down, expert_out,
-                   (char*)workspace + L.ctrl, (char*)workspace + L.h, (hipStream_t)stream, w8);
+                   (char*)workspace + L.ctrl, (unsigned long long*)((char*)workspace + L.status), (char*)workspace + L.h,
+                   (hipStream_t)stream, w8);
 }
 }  // namespace
 
@@ -250,7 +254,8 @@ int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const vo
                   const void* w_down, const uint8_t* expert_mask, const uint8_t* token_class, uint8_t* activated_mask_out,
                   int32_t* n_activated_out, void* y, void* workspace, size_t ws_bytes, void* stream,
                   const int32_t* row_index = nullptr, int32_t n_rows = 0, bool unique_rows = false, int32_t* row_rep_out = nullptr,
-                  int32_t* n_unique_out = nullptr, const team::W8Scales* w8 = nullptr) {
+                  int32_t* n_unique_out = nullptr, const team::W8Scales* w8 = nullptr, hipEvent_t ffn_begin = nullptr,
+                  hipEvent_t ffn_end = nullptr) {
     int st = check_cfg(cfg);
     if (st != TEAM_OK) return st;
     if ((st = check_T(cfg, T)) != TEAM_OK) return st;
@@ -283,8 +288,7 @@ int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const vo
         dedup.hash = (unsigned long long*)(ws + L.row_hash);
         dedup.rep = row_rep_out ? row_rep_out : (int32_t*)(ws + L.row_rep);
         dedup.n_unique = n_unique_out ? n_unique_out : (int32_t*)(ws + L.n_unique);
-        const char* bits = getenv("TEAM_MOE_ROW_HASH_BITS");           // testing aid: compare fewer bits of the row hashes
-        const int nb = bits ? atoi(bits) : 64;
+        const int nb = team::tuning().row_hash_bits.load();            // (tests compare fewer bits to force collisions)
         dedup.hash_mask = nb >= 64 ? ~0ull : (nb <= 0 ? 0ull : ((1ull << nb) - 1ull));
         d.row_rep = dedup.rep;
     }
@@ -302,17 +306,19 @@ int layer_forward(const team_moe_config* cfg, const void* x, int32_t T, const vo
     else
         st = hip_status(team::launch_route(d, x, w_router, expert_mask, topk_idx, topk_gate, logits, short_path ? cz : none, s, dedup));
     if (st != TEAM_OK) return st;
-    if (short_path) {
-        if ((st = hip_status(team::launch_ffn_bf16_from_routing(d, (const uint16_t*)x_ffn, topk_idx, inv_pos, w_gate, w_up, w_down,
-                                                                ws + L.ctrl, (uint16_t*)(ws + L.h), expert_out, s, w8))) != TEAM_OK)
-            return st;
-        return hip_status(team::launch_combine(d, expert_out, topk_gate, inv_pos, y, s));
-    }
-    if ((st = hip_status(team::launch_dispatch(d, topk_idx, offsets, sorted_token, inv_pos, active, n_active, cz, s))) != TEAM_OK)
+    unsigned long long* fail_mark = (unsigned long long*)(ws + L.status);
+    if (!short_path &&
+        (st = hip_status(team::launch_dispatch(d, topk_idx, offsets, sorted_token, inv_pos, active, n_active, cz, s))) != TEAM_OK)
         return st;
-    if ((st = run_ffn(cfg, d, x_ffn, offsets, sorted_token, active, n_active, w_gate, w_up, w_down, expert_out, ws + L.ctrl,
-                      ws + L.h, s, w8)) != TEAM_OK)
-        return st;
+    if (ffn_begin && (st = hip_status(hipEventRecord(ffn_begin, s))) != TEAM_OK) return st;
+    if (short_path)
+        st = hip_status(team::launch_ffn_bf16_from_routing(d, (const uint16_t*)x_ffn, topk_idx, inv_pos, w_gate, w_up, w_down, ws + L.ctrl,
+                                                           fail_mark, (uint16_t*)(ws + L.h), expert_out, s, w8));
+    else
+        st = run_ffn(cfg, d, x_ffn, offsets, sorted_token, active, n_active, w_gate, w_up, w_down, expert_out, ws + L.ctrl, fail_mark,
+                     ws + L.h, s, w8);
+    if (st != TEAM_OK) return st;
+    if (ffn_end && (st = hip_status(hipEventRecord(ffn_end, s))) != TEAM_OK) return st;
     return hip_status(team::launch_combine(d, expert_out, topk_gate, inv_pos, y, s));
 }
 
@@ -404,11 +410,35 @@ int team_moe_layer_forward_ex(const team_moe_config* cfg, const team_moe_layer_a
     if (a->unique_rows != 0 && a->unique_rows != 1) return TEAM_ERR_INVALID_ARG;
     if (!a->unique_rows && (a->row_rep_out || a->n_unique_out)) return TEAM_ERR_INVALID_ARG;
     if (!a->token_class && (a->activated_mask_out || a->n_activated_out)) return TEAM_ERR_INVALID_ARG;
+    if ((a->ffn_begin_event == nullptr) != (a->ffn_end_event == nullptr)) return TEAM_ERR_INVALID_ARG;      // both events or none
     const bool any_scale = a->scale_gate || a->scale_up || a->scale_down;
     const team::W8Scales w8{a->scale_gate, a->scale_up, a->scale_down};
     return layer_forward(cfg, a->x, a->T, a->w_router, a->w_gate, a->w_up, a->w_down, a->expert_mask, a->token_class,
                          a->activated_mask_out, a->n_activated_out, a->y, a->workspace, a->ws_bytes, a->stream, a->row_index, a->n_rows,
-                         a->unique_rows != 0, a->row_rep_out, a->n_unique_out, any_scale ? &w8 : nullptr);
+                         a->unique_rows != 0, a->row_rep_out, a->n_unique_out, any_scale ? &w8 : nullptr, (hipEvent_t)a->ffn_begin_event,
+                         (hipEvent_t)a->ffn_end_event);
+}
+
+int team_moe_workspace_status(void* workspace, size_t ws_bytes, void* stream) {
+    void* ws = workspace;
+    if (!ws) {                                         // the static array of team_moe_layer_forward_static on the current device
+        int st = static_scratch(&ws);
+        if (st != TEAM_OK) return st;
+    } else if (!aligned16(ws) || ws_bytes < team::WS_STATUS_BYTES) {
+        return TEAM_ERR_WORKSPACE;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    clear_stale_error();
+    unsigned long long mark = 0ull;
+    hipError_t e = hipMemcpyAsync(&mark, ws, sizeof(mark), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_status(e);
+    if (mark != team::WS_FAIL_MARK) return TEAM_OK;
+    const unsigned long long zero = 0ull;              // reported once: the mark is taken off again
+    e = hipMemcpyAsync(ws, &zero, sizeof(zero), hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_status(e);
+    return TEAM_ERR_TIMEOUT;
 }
 
 const char* team_moe_status_string(int status) {
@@ -418,6 +448,7 @@ const char* team_moe_status_string(int status) {
         case TEAM_ERR_UNSUPPORTED: return "unsupported shape or dtype";
         case TEAM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case TEAM_ERR_HIP: return "HIP runtime rejected a launch";
+        case TEAM_ERR_TIMEOUT: return "a wait inside a kernel gave up; the affected outputs hold NaN";
         default: return "unknown status";
     }
 }

@@ -1,7 +1,7 @@
 // Classification of the live tokens of a denoising step into first-round tokens and cold tokens.
 // Paper: Algorithm 1 step 1 and Eq. 4 (Section "Speculative Exploration for Hot Tokens"): a masked token is hot if its
-// confidence exceeds tau_h or if a decoded token of its block is no more than L_h positions away (the wording of Section
-// "Experimental Setup"); newly accepted tokens and hot tokens take part in the first routing round, the rest are cold.
+// confidence exceeds tau_h or if some decoded token of its block lies within L_h positions, L_h included (where Eq. 4 and
+// Section "Experimental Setup" differ on the distance condition, the latter is followed); newly accepted tokens and hot tokens take part in the first routing round, the rest are cold.
 // One thread per live token, a scan of at most 2*L_h+1 neighbours; integer and one float comparison, no arithmetic.
 #include "kernels.hpp"
 

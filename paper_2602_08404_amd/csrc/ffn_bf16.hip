@@ -2,24 +2,22 @@
 #include "ffn_bf16.hpp"
 
 #include <stddef.h>
-#include <stdlib.h>
+
+#include <atomic>
+
+#include "tuning.hpp"
 
 namespace team {
 
-static int env_int(const char* name, int dflt) {
-    const char* v = getenv(name);
-    if (!v || !*v) return dflt;
-    int x = atoi(v);
-    return x > 0 ? x : dflt;
-}
-
-static int compute_units() {
-    static int n_cu = 0;
+// Compute units of a device, asked once per device.
+static int compute_units(int dev) {
+    static std::atomic<int> n_cu_of[FFN_MAX_DEVICES];
+    int n_cu = n_cu_of[dev].load(std::memory_order_relaxed);
     if (n_cu == 0) {
-        int dev = 0;
         hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
+        if (hipGetDeviceProperties(&prop, dev) == hipSuccess) n_cu = prop.multiProcessorCount;
         if (n_cu <= 0) n_cu = 256;
+        n_cu_of[dev].store(n_cu, std::memory_order_relaxed);
     }
     return n_cu;
 }
@@ -42,15 +40,22 @@ bool ffn_bf16_groups_itself(const Dims& d) {
 
 static hipError_t launch_common(const Dims& d, FfnArgs& p, hipStream_t s) {
     p.T = d.T; p.k = d.k; p.E = d.E;
-    p.n_cu = compute_units();
-    p.grid_override = env_int("TEAM_MOE_FFN_GRID", 0);      // tuning aid only; never raises the grid above what is resident
-    p.spin_limit = 1 << 16;          // ~0.1 s of polling; a wait this long means the control block was not zeroed
+    if (!p.fail_mark) return hipErrorInvalidValue;
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= FFN_MAX_DEVICES) return hipErrorInvalidDevice;
+    p.device = dev;
+    p.n_cu = compute_units(dev);
+    const Tuning& tn = tuning();
+    p.grid_override = tn.ffn_grid.load();             // tuning aid only; never raises the grid above what is resident
+    p.spin_limit = tn.ffn_spin_limit.load();          // ~0.1 s of polling by default; see the waits in the kernel
+    p.skip_publish = tn.ffn_skip_publish.load();
     // With at most 32 tokens per call an expert has at most 32 rows: one pass of the register-resident token operand, which is
     // reused across the expert's items.  Beyond that the kernel decides on the device from the average number of rows per expert.
-    p.tiled_min_avg_rows = d.T > 32 ? env_int("TEAM_MOE_FFN_TILED_ROWS", 18) : 0;      // override is a tuning aid only
-    p.wide_min_avg_rows = env_int("TEAM_MOE_FFN_WIDE_ROWS", 56);                    // override is a tuning aid only
-    const char* shares = getenv("TEAM_MOE_FFN_SHARES");     // tuning aid: "contiguous" = never deal workgroups out to experts
-    p.expert_major = shares && shares[0] == 'c' ? 0 : (shares && shares[0] == 'a' ? 2 : 1);
+    p.tiled_min_avg_rows = d.T > 32 ? tn.ffn_tiled_rows.load() : 0;
+    p.wide_min_avg_rows = tn.ffn_wide_rows.load();
+    p.expert_major = tn.ffn_shares.load() == 0 ? 0 : (tn.ffn_shares.load() == 2 ? 2 : 1);
     p.stream = s;
     if (p.sg) {                       // 8-bit weights
         if (!p.su || !p.sd || !ffn_w8_supported(d.H, d.I)) return hipErrorInvalidValue;
@@ -67,26 +72,39 @@ static hipError_t launch_common(const Dims& d, FfnArgs& p, hipStream_t s) {
 
 hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offsets, const int32_t* sorted_token, const int32_t* active,
                            const int32_t* n_active, const void* wg, const void* wu, const void* wd, void* ctrl,
-                           uint16_t* h_ws, float* expert_out, hipStream_t s, const W8Scales* w8) {
+                           unsigned long long* fail_mark, uint16_t* h_ws, float* expert_out, hipStream_t s, const W8Scales* w8) {
     if (!ffn_bf16_supported(d.H, d.I) || d.E > FFN_MAX_E) return hipErrorInvalidValue;
     FfnArgs p;
     if (w8) { p.sg = w8->gate; p.su = w8->up; p.sd = w8->down; }
     p.x = x; p.offsets = offsets; p.sorted_token = sorted_token; p.active = active; p.n_active = n_active;
-    p.wg = wg; p.wu = wu; p.wd = wd; p.h = h_ws; p.out = expert_out; p.ctrl = (FfnCtrl*)ctrl;
+    p.wg = wg; p.wu = wu; p.wd = wd; p.h = h_ws; p.out = expert_out; p.ctrl = (FfnCtrl*)ctrl; p.fail_mark = fail_mark;
     p.topk_idx = nullptr; p.inv_pos_out = nullptr;
     return launch_common(d, p, s);
 }
 
 hipError_t launch_ffn_bf16_from_routing(const Dims& d, const uint16_t* x, const int32_t* topk_idx, int32_t* inv_pos_out,
-                                        const void* wg, const void* wu, const void* wd, void* ctrl, uint16_t* h_ws,
-                                        float* expert_out, hipStream_t s, const W8Scales* w8) {
+                                        const void* wg, const void* wu, const void* wd, void* ctrl, unsigned long long* fail_mark,
+                                        uint16_t* h_ws, float* expert_out, hipStream_t s, const W8Scales* w8) {
     if (!ffn_bf16_groups_itself(d)) return hipErrorInvalidValue;
     FfnArgs p;
     if (w8) { p.sg = w8->gate; p.su = w8->up; p.sd = w8->down; }
     p.x = x; p.offsets = nullptr; p.sorted_token = nullptr; p.active = nullptr; p.n_active = nullptr;
-    p.wg = wg; p.wu = wu; p.wd = wd; p.h = h_ws; p.out = expert_out; p.ctrl = (FfnCtrl*)ctrl;
+    p.wg = wg; p.wu = wu; p.wd = wd; p.h = h_ws; p.out = expert_out; p.ctrl = (FfnCtrl*)ctrl; p.fail_mark = fail_mark;
     p.topk_idx = topk_idx; p.inv_pos_out = inv_pos_out;
     return launch_common(d, p, s);
+}
+
+// ---- control block cleared by a launch of its own (staged calls, where no other kernel of the call precedes the FFN kernel)
+__global__ __launch_bounds__(FFN_MAX_E) void ffn_ctrl_clear_kernel(CtrlZero cz, int E) {
+    const int tid = threadIdx.x;
+    if (tid < cz.header) cz.words[tid] = 0;
+    if (tid < E) cz.words[cz.header + tid * cz.stride] = 0;
+}
+
+hipError_t launch_ffn_ctrl_clear(void* ctrl, int E, hipStream_t s) {
+    if (E < 1 || E > FFN_MAX_E) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(ffn_ctrl_clear_kernel, dim3(1), dim3(FFN_MAX_E), 0, s, ffn_ctrl_zero(ctrl), E);
+    return hipGetLastError();
 }
 
 // ---- the 8-bit weight format as this library reads it (also what the FFN kernel's operands are widened with)

@@ -12,13 +12,13 @@ constexpr int FFN_MAX_E = 256;
 constexpr int FFN_LAYER_MAX_TOKENS = 128;    // up to this many tokens (and FFN_LAYER_MAX_ROWS pairs) the kernel can group the routing table itself
 constexpr int FFN_LAYER_MAX_ROWS = 1024;
 static_assert(FFN_THREADS == FFN_MAX_E && FFN_LAYER_MAX_ROWS % FFN_THREADS == 0, "the in-kernel grouping maps one thread to one expert");
+constexpr int FFN_MAX_DEVICES = 64;      // devices the per-device launch tables hold
 constexpr int FFN_DONE_STRIDE = 64;      // one counter per 256 bytes: polled counters sit in different memory channels
 
-// Control block of one FFN launch (in the caller's workspace); must be all zero when the kernel starts.
+// Control block of one FFN launch (in the caller's workspace); must be all zero when the kernel starts (the words
+// ffn_ctrl_zero() names: a kernel earlier in the same call clears them).
 struct FfnCtrl {
-    int32_t reserved0;
-    int32_t error;              // set if a bounded wait gave up (never in correct operation)
-    int32_t pad[14];
+    int32_t reserved[16];
     int32_t done[FFN_MAX_E][FFN_DONE_STRIDE];   // [slot][0]: gate/up items of the slot that have published their part of h
 };
 
@@ -40,9 +40,12 @@ struct FfnArgs {
     const int32_t* topk_idx;    // non-null: group this routing table in the kernel (offsets .. n_active are then unused)
     int32_t* inv_pos_out;       // with topk_idx: [T,k] rows of the pairs, written for the combine kernel
     int T, k, E;
-    int n_cu;                   // compute units of the current device
+    int device;                 // current device (index into the per-device tables of the launchers)
+    int n_cu;                   // compute units of that device
     int grid_override;          // > 0: use a smaller grid than the resident maximum (tuning aid)
     int spin_limit;
+    int skip_publish;           // tests only: gate/up items do not publish, so every wait for them gives up
+    unsigned long long* fail_mark;   // workspace word that receives WS_FAIL_MARK when a wait gives up (see kernels.hpp)
     int tiled_min_avg_rows;     // > 0: switch to the streaming variant when the call averages at least this many rows per expert
     int wide_min_avg_rows;      // streaming variant: above this many rows per expert on average, two token tiles per wavefront
     int expert_major;           // 1: shares that would cross expert boundaries are replaced by whole workgroups per expert (see the kernel)

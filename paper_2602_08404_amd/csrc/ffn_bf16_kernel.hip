@@ -38,6 +38,8 @@
 // team_moe_layer_forward, every workgroup groups the routing table itself in LDS during its prologue (the same
 // bitset / popcount / prefix-sum method as the dispatch kernel, which is then not launched).  (2) When a call
 // averages many rows per expert, all workgroups switch to the streaming body in ffn_bf16_tiled.hpp.
+#include <atomic>
+
 #include "ffn_bf16.hpp"
 #include "ffn_bf16_tiled.hpp"
 
@@ -268,7 +270,8 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                                                                    const unsigned char* __restrict__ wg, const unsigned char* __restrict__ wu,
                                                                    const unsigned char* __restrict__ wd, uint16_t* __restrict__ h,
                                                                    float* __restrict__ out, FfnCtrl* __restrict__ ctrl, int T, int k, int E,
-                                                                   int spin_limit, int tiled_min_avg_rows, int expert_major_ok, int wide_min_avg_rows,
+                                                                   int spin_limit, int skip_publish, unsigned long long* __restrict__ fail_mark,
+                                                                   int tiled_min_avg_rows, int expert_major_ok, int wide_min_avg_rows,
                                                                    const int32_t* __restrict__ topk_idx, int32_t* __restrict__ inv_pos_out,
                                                                    const float* __restrict__ sg, const float* __restrict__ su,
                                                                    const float* __restrict__ sd) {
@@ -289,6 +292,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     __shared__ uint16_t s_sorted[FFN_LAYER_MAX_ROWS];    // token of every row (0xffff: none), when the table fits
     __shared__ uint32_t s_hbuf[H_BUF_ITEMS][NT][WAVE];   // h of the gate/up items of the current slot run, until it is published
     __shared__ int32_t s_nact;
+    __shared__ uint32_t s_wait_failed;                   // set by thread 0 when a wait for another workgroup gave up
 
     const int tid = threadIdx.x;
     const int lane = tid & (WAVE - 1);
@@ -296,6 +300,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     const int A = T * k;
     const int G = gridDim.x;
 
+    if (tid == 0) s_wait_failed = 0u;                    // (a workgroup barrier follows in every path before the first wait)
     int n_act;
     const bool own_tables = topk_idx != nullptr;
     // the token of every row sits in LDS when the table fits (always, when the kernel groups the routing table itself)
@@ -410,13 +415,15 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                 if (wide) {
                     tiled::ffn_tiled_body<tiled::RING_STAGES, tiled::X_AHEAD, WB, 2>(s_mem, s_slot_e, s_off, lds_tokens ? s_sorted : nullptr, n_act, x,
                                                                                      sorted_token, wg, wu, wd, h, out, ctrl, T, E, H, I, spin_limit,
-                                                                                     expert_major_ok, sg, su, sd);
+                                                                                     expert_major_ok, sg, su, sd, skip_publish, fail_mark,
+                                                                                     tiled::lds_addr(&s_wait_failed));
                     return;
                 }
             }
             tiled::ffn_tiled_body<tiled::RING_STAGES, tiled::X_AHEAD, WB, 1>(s_mem, s_slot_e, s_off, lds_tokens ? s_sorted : nullptr, n_act, x,
                                                                              sorted_token, wg, wu, wd, h, out, ctrl, T, E, H, I, spin_limit,
-                                                                             expert_major_ok, sg, su, sd);
+                                                                             expert_major_ok, sg, su, sd, skip_publish, fail_mark,
+                                                                             tiled::lds_addr(&s_wait_failed));
             return;
         }
     }
@@ -438,6 +445,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     int ready_slot = -1;                     // slot whose h this workgroup has already acquired
     int pend = 0;                            // finished gate/up items of the current slot not yet published
     int held = 0, held_it0 = 0;              // items whose h is still in s_hbuf, and the tile index of the first of them
+    bool wait_failed = false;                // a wait of this workgroup gave up: its down items from then on store NaN
     const uint32_t hbuf_base = tiled::lds_addr(s_hbuf);
 
     // While direct-to-LDS loads of the NEXT item are in flight, every LDS read below is written as explicit
@@ -624,7 +632,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
             // write-through stores and every wavefront has waited for its own before the barrier.
             ++pend;
             if (publish_now) {
-                if (tid == 0) __hip_atomic_fetch_add(&ctrl->done[a][0], pend, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (tid == 0 && !skip_publish) __hip_atomic_fetch_add(&ctrl->done[a][0], pend, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 pend = 0;
             }
         } else {
@@ -639,14 +647,21 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                     int spins = 0;
                     while (__hip_atomic_load(&ctrl->done[a][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < TILES_A) {
                         __builtin_amdgcn_s_sleep(8);      // ~0.2 us between polls; the counters sit in different memory channels
-                        if (++spins > spin_limit) {          // cannot happen with a control block zeroed before the launch
-                            ctrl->error = 1;
+                        // Giving up: only when the producers cannot run (another launch holds the compute units they need) or
+                        // the control block was not cleared.  The workspace gets its failure mark, and this workgroup stores
+                        // NaN instead of products of an incomplete h from here on.
+                        if (++spins > spin_limit) {
+                            // (the mark is put together behind an opaque value, inside this branch: as a plain constant the
+                            // compiler loads it into registers in front of the item loop and keeps it there)
+                            __hip_atomic_store(fail_mark, WS_FAIL_MARK + (unsigned long long)opaque(0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            lds_write_u32(tiled::lds_addr(&s_wait_failed), 1u);
                             break;
                         }
                     }
                 }
                 lds_barrier();
                 ready_slot = a;
+                wait_failed = wait_failed || __builtin_amdgcn_readfirstlane((int)lds_read_u32(tiled::lds_addr(&s_wait_failed))) != 0;
             }
             for (int ch = 0; ch < chunks; ++ch) {
                 const int row_base = ch * 16 * NT;
@@ -705,6 +720,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                             const int qs = opaque(q);       // as in the gate/up epilogue
                             v[0] *= pick4(sc_d, qs, 0); v[1] *= pick4(sc_d, qs, 1); v[2] *= pick4(sc_d, qs, 2); v[3] *= pick4(sc_d, qs, 3);
                         }
+                        if (wait_failed) v = f32x4_t{__builtin_nanf(""), __builtin_nanf(""), __builtin_nanf(""), __builtin_nanf("")};
                         *reinterpret_cast<f32x4_t*>(out + (size_t)(r0 + row) * H + it * 16 * RB + rb * 16 + 4 * q) = v;
                     }
                 }
@@ -721,18 +737,21 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
 template <int KSA, int KSB, int WB>
 hipError_t launch_ffn_fused(const FfnArgs& p) {
     constexpr int RB = KSB <= 6 ? 2 : 1;      // two sub-tiles per down item while the partial sums fit the register budget
-    static int resident = 0;         // per instantiation; same value for every caller, so a benign race
-    if (resident == 0) {
-        int per_cu = 0;
+    // Workgroups of this instantiation that fit one compute unit of the current device, asked once per device.
+    static std::atomic<int> per_cu_of[FFN_MAX_DEVICES];
+    if (p.device < 0 || p.device >= FFN_MAX_DEVICES) return hipErrorInvalidDevice;
+    int per_cu = per_cu_of[p.device].load(std::memory_order_relaxed);
+    if (per_cu == 0) {
         hipError_t err = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, ffn_fused_kernel<KSA, KSB, RB, WB>, FFN_THREADS, 0);
         if (err != hipSuccess) return err;
         if (per_cu < 1) return hipErrorLaunchOutOfResources;
-        resident = per_cu * p.n_cu;
+        per_cu_of[p.device].store(per_cu, std::memory_order_relaxed);      // (two first callers store the same value)
     }
+    const int resident = per_cu * p.n_cu;
     const int grid = p.grid_override > 0 && p.grid_override < resident ? p.grid_override : resident;
     hipLaunchKernelGGL((ffn_fused_kernel<KSA, KSB, RB, WB>), dim3(grid), dim3(FFN_THREADS), 0, p.stream, p.x, p.offsets, p.sorted_token,
                        p.active, p.n_active, (const unsigned char*)p.wg, (const unsigned char*)p.wu, (const unsigned char*)p.wd, p.h, p.out,
-                       p.ctrl, p.T, p.k, p.E, p.spin_limit, p.tiled_min_avg_rows, p.expert_major, p.wide_min_avg_rows, p.topk_idx, p.inv_pos_out, p.sg, p.su,
+                       p.ctrl, p.T, p.k, p.E, p.spin_limit, p.skip_publish, p.fail_mark, p.tiled_min_avg_rows, p.expert_major, p.wide_min_avg_rows, p.topk_idx, p.inv_pos_out, p.sg, p.su,
                        p.sd);
     return hipGetLastError();
 }

@@ -212,7 +212,8 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                                                const unsigned char* __restrict__ wg, const unsigned char* __restrict__ wu,
                                                const unsigned char* __restrict__ wd, uint16_t* __restrict__ h, float* __restrict__ out,
                                                FfnCtrl* __restrict__ ctrl, int T, int E, int H, int I, int spin_limit, int expert_major_ok,
-                                               const float* __restrict__ sg, const float* __restrict__ su, const float* __restrict__ sd) {
+                                               const float* __restrict__ sg, const float* __restrict__ su, const float* __restrict__ sd,
+                                               int skip_publish, unsigned long long* __restrict__ fail_mark, uint32_t fail_addr) {
     asm volatile("; team_tiled_body_begin" ::: "memory");   // (marks for the checks of the generated code: a kernel holds two instances)
     constexpr int KCOL = ROW_BYTES / WB;          // reduction columns per stage
     // NT token tiles per wavefront: a pass covers MTT = NT x 64 rows of the expert (tile j of wavefront w: rows 64 j + 16 w ..).
@@ -229,6 +230,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
     const int n = lane & 15, q = lane >> 4;
     const int G = gridDim.x;
     const int tiles_a = I / 16, tiles_b = H / W_ROWS;
+    bool wait_failed = false;             // a wait of this workgroup gave up: the down results it stores from then on are NaN
 
     // ---- lane constants
     // weight loads: lane fetches row (l / 8) of an 8-row slab, stored chunk (l % 8)
@@ -357,13 +359,17 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                     int spins = 0;
                     while (__hip_atomic_load(&ctrl->done[px.a][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < tiles_a) {
                         __builtin_amdgcn_s_sleep(8);
-                        if (++spins > spin_limit) {                  // cannot happen with a control block zeroed before the launch
-                            ctrl->error = 1;
+                        if (++spins > spin_limit) {                  // giving up: see the same wait in ffn_bf16_kernel.hip
+                            int zero = 0;
+                            asm volatile("" : "+v"(zero));             // (keeps the constant below out of the loop's registers)
+                            __hip_atomic_store(fail_mark, WS_FAIL_MARK + (unsigned long long)zero, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            asm volatile("ds_write_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" ::"v"(fail_addr), "v"(1u) : "memory");
                             break;
                         }
                     }
                 }
                 wg_barrier();
+                wait_failed = wait_failed || __builtin_amdgcn_readfirstlane(lds_read_i32(fail_addr)) != 0;
                 ready_slot = px.a;
             }
             const int key = px.a * 64 + px.pass;
@@ -468,7 +474,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                 // (2) a run of gate/up items whose h stores are older than loads that have completed is complete in every
                 //     wavefront (operations complete in issue order): publish it
                 if (pub_slot >= 0 && mark_w[u % DW] > pub_mark) {
-                    if (tid == 0) __hip_atomic_fetch_add(&ctrl->done[pub_slot][0], pub_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (tid == 0 && !skip_publish) __hip_atomic_fetch_add(&ctrl->done[pub_slot][0], pub_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     pub_slot = -1;
                 }
                 // (3) refill the ring slot that the previous iteration has finished reading
@@ -555,8 +561,11 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                             }
                         } else {
 #pragma unroll
-                            for (int rt = 0; rt < 2; ++rt)   // lane holds output rows it*32 + rt*16 + 4*q + (0..3) of token row `row`
-                                *reinterpret_cast<f32x4_t*>(out + (size_t)(cs.r0 + row) * H + it * W_ROWS + rt * 16 + 4 * q) = ac[rt];
+                            for (int rt = 0; rt < 2; ++rt) { // lane holds output rows it*32 + rt*16 + 4*q + (0..3) of token row `row`
+                                const float nan = __builtin_nanf("");
+                                *reinterpret_cast<f32x4_t*>(out + (size_t)(cs.r0 + row) * H + it * W_ROWS + rt * 16 + 4 * q) =
+                                    wait_failed ? f32x4_t{nan, nan, nan, nan} : ac[rt];
+                            }
                         }
                     }
                     ac[0] = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -571,7 +580,7 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
                         if (pub_slot >= 0) {                            // an older run is still waiting (only with very few stages per
                             wait_outstanding<0>();                      // item): acknowledge everything now and publish it at once
                             wg_barrier();
-                            if (tid == 0)
+                            if (tid == 0 && !skip_publish)
                                 __hip_atomic_fetch_add(&ctrl->done[pub_slot][0], pub_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         }
                         pub_slot = prev_a;
@@ -586,7 +595,8 @@ __device__ __forceinline__ void ffn_tiled_body(char* s_ring, const int32_t* s_sl
         // ---- end of phase: everything this workgroup stored is acknowledged, then the last run is published
         wait_outstanding<0>();
         wg_barrier();
-        if (pub_slot >= 0 && tid == 0) __hip_atomic_fetch_add(&ctrl->done[pub_slot][0], pub_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (pub_slot >= 0 && tid == 0 && !skip_publish)
+            __hip_atomic_fetch_add(&ctrl->done[pub_slot][0], pub_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     asm volatile("; team_tiled_body_end" ::: "memory");
 }

@@ -34,6 +34,13 @@ struct RowDedup {
     unsigned long long hash_mask = ~0ull; // bits of the hash that are compared (fewer bits: more byte-wise confirmations)
 };
 
+// The first WS_STATUS_BYTES of a workspace are its status area.  Word 0 is the failure mark: a kernel whose bounded wait
+// for another workgroup gives up stores WS_FAIL_MARK there (and fills the outputs it could not compute with NaN); nothing
+// but team_moe_workspace_status ever resets it, so the mark survives later calls.  A workspace that was never used holds
+// arbitrary bytes there; the mark is a 64-bit pattern so that such bytes are not mistaken for it.
+constexpr size_t WS_STATUS_BYTES = 256;
+constexpr unsigned long long WS_FAIL_MARK = 0x5445414d4641494cull;
+
 // Words of the FFN control block that must be zero before an FFN launch: `header` leading words, then one word
 // every `stride` words for each of the E expert slots.
 struct CtrlZero {
@@ -77,14 +84,19 @@ hipError_t launch_dequantize_w8(const uint8_t* codes, const float* scale, long l
 bool ffn_bf16_supported(int H, int I);
 size_t ffn_ctrl_bytes();
 CtrlZero ffn_ctrl_zero(void* ctrl);
+// fail_mark: the workspace's failure mark (see WS_FAIL_MARK).
 hipError_t launch_ffn_bf16(const Dims& d, const uint16_t* x, const int32_t* offsets, const int32_t* sorted_token,
                            const int32_t* active, const int32_t* n_active, const void* wg, const void* wu,
-                           const void* wd, void* ctrl, uint16_t* h_ws, float* expert_out, hipStream_t s, const W8Scales* w8 = nullptr);
+                           const void* wd, void* ctrl, unsigned long long* fail_mark, uint16_t* h_ws, float* expert_out, hipStream_t s,
+                           const W8Scales* w8 = nullptr);
+// Clears the words ffn_ctrl_zero() names with a one-workgroup launch of its own (the staged team_moe_expert_ffn: no other
+// kernel of that call runs before the FFN kernel).
+hipError_t launch_ffn_ctrl_clear(void* ctrl, int E, hipStream_t s);
 // Whole-layer form for small calls: the FFN kernel groups the routing table (topk_idx) itself and writes inv_pos for
 // the combine kernel; no dispatch kernel is needed.  ffn_bf16_groups_itself says whether a call qualifies.
 bool ffn_bf16_groups_itself(const Dims& d);
 hipError_t launch_ffn_bf16_from_routing(const Dims& d, const uint16_t* x, const int32_t* topk_idx, int32_t* inv_pos_out,
-                                        const void* wg, const void* wu, const void* wd, void* ctrl, uint16_t* h_ws,
-                                        float* expert_out, hipStream_t s, const W8Scales* w8 = nullptr);
+                                        const void* wg, const void* wu, const void* wd, void* ctrl, unsigned long long* fail_mark,
+                                        uint16_t* h_ws, float* expert_out, hipStream_t s, const W8Scales* w8 = nullptr);
 
 }  // namespace team

@@ -19,12 +19,13 @@
 //            Calls of at most 256 tokens (a block, or a few): no workgroup depends on another.  Every workgroup rebuilds E_A itself:
 //            a wavefront finds the k picks of a first-round token with k rounds of a cross-lane maximum over the same
 //            (logit, id) keys the selection uses, four tokens at a time, which is cheaper than one exchange through memory.
-//            Larger calls: workgroups are ordered first-round tokens (newly accepted and hot) before cold tokens.  A
-//            first-round workgroup selects over all experts, ORs its picks into a device-wide bit set E_A and counts
-//            itself done; a cold workgroup waits until every first-round workgroup is counted, then selects inside E_A.
-//            Workgroups start in index order and first-round ones never wait, so a waiting workgroup can only wait for
-//            workgroups that already run.
-#include <stdlib.h>
+//            Larger calls: two launches of one kernel, so that no workgroup ever waits for another.  The first routes the
+//            first-round tokens (newly accepted and hot) over all experts and ORs their picks into a bit set E_A in device
+//            memory; the second routes the cold tokens inside that set.
+// Scores that are not numbers: a NaN ranks below every number (ties by the lower id, as for equal numbers), so it is selected
+// only when fewer than k numbers are allowed; the gates are the softmax formulas in IEEE arithmetic, so a token that selects a
+// NaN or an infinite score gets NaN gates and a NaN output row.
+#include "tuning.hpp"
 
 #include "device_utils.hpp"
 #include "kernels.hpp"
@@ -43,12 +44,10 @@ constexpr int TWO_ROUND_STATE_WORDS = 64;               // 256 bytes of device s
 
 struct TwoRound {
     const uint8_t* token_class;    // [T] non-zero: first-round token
-    uint32_t* mask_bits;           // E_A as a bit set, built with device-scope atomics
-    uint32_t* arrived;             // first-round workgroups that have added their picks
-    uint32_t* error;               // set when a wait ran into its limit
+    uint32_t* mask_bits;           // E_A as a bit set, built with device-scope atomics by the first launch
     uint8_t* mask_out;             // [E] or null
     int32_t* n_activated_out;      // [1] or null
-    int spin_limit;
+    int phase;                     // 0: the launch that routes the first-round tokens; 1: the one that routes the cold tokens
 };
 
 template <typename ST> struct Chunk;
@@ -248,10 +247,12 @@ __global__ __launch_bounds__(LOGIT_THREADS) void route_logits_mfma_kernel(const 
 }
 
 // Selection key: larger logit wins, equal logits go to the lower expert id.  The float is mapped to an unsigned
-// integer with the same order; the id is stored complemented in the low word; 0 = not a candidate.
+// integer with the same order (minus infinity maps to 0x007fffff, the smallest image of a number); a NaN maps to 1, below
+// every number; the id is stored complemented in the low word; 0 = not a candidate.
 __device__ __forceinline__ unsigned long long select_key(float v, int e) {
     const uint32_t b = __float_as_uint(v);
-    const uint32_t ord = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    uint32_t ord = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    if (v != v) ord = 1u;
     return ((unsigned long long)ord << 32) | (uint32_t)(0xffffffffu - (uint32_t)e);
 }
 
@@ -382,7 +383,7 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_kernel(const floa
     bool ok = false;
     if (e < E) {
         v = logits[(size_t)t * E + e] + 0.f;                         // -0 -> +0 so that equal logits compare equal
-        ok = (mask == nullptr || mask[e] != 0) && v == v;            // a NaN logit is never selected
+        ok = mask == nullptr || mask[e] != 0;
     }
     select_rank(sm, v, ok, e, E, k);
     if (e < WAVE) write_gates(sm, t, e, E, k, renormalize, topk_idx, topk_gate);
@@ -399,12 +400,11 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_two_round_kernel(
     __shared__ SelectLds sm;
     __shared__ unsigned long long s_cls[MAX_TOKENS_2R / WAVE];   // bit t: token t is a first-round token
     __shared__ uint32_t s_bits[TWO_ROUND_MASK_WORDS];
-    __shared__ int s_last;
     const int b = blockIdx.x;
     const int e = threadIdx.x;
     const int lane = e & (WAVE - 1);
     const int wave = e / WAVE;
-    if (ctrl.words && b == 0) clear_ffn_ctrl(ctrl, e, E);
+    if (ctrl.words && b == 0 && tr.phase == 0) clear_ffn_ctrl(ctrl, e, E);
 
     // ---- which token is this workgroup's: the b-th in the order (first-round tokens ascending, then cold tokens ascending)
 #pragma unroll
@@ -442,6 +442,21 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_two_round_kernel(
         t = word * WAVE + (bits ? __builtin_ctzll(bits) : 0);
     }
     const bool is_first = b < n_first;
+    // ---- the launch this workgroup has nothing to route in: workgroup 0 publishes E_A where it is known, the others leave
+    if (is_first != (tr.phase == 0)) {
+        if (b == 0) {                                  // phase 0 without first-round tokens: E_A is empty; phase 1: E_A is complete
+            if (e < TWO_ROUND_MASK_WORDS) s_bits[e] = tr.phase == 0 ? 0u : load_agent(tr.mask_bits + e);
+            __syncthreads();
+            if (tr.mask_out && e < E) tr.mask_out[e] = (uint8_t)((s_bits[e >> 5] >> (e & 31)) & 1u);
+            if (tr.n_activated_out && e == 0) {
+                int n = 0;
+#pragma unroll
+                for (int w = 0; w < TWO_ROUND_MASK_WORDS; ++w) n += __popc(s_bits[w]);
+                *tr.n_activated_out = n;
+            }
+        }
+        return;
+    }
     // A repeated row is routed and computed once, for its first occurrence.  As a first-round token it still adds its picks to
     // E_A (its first occurrence may be a cold token; the picks then lie inside E_A, so that token's restricted routing is the
     // free one and serves both); as a cold token it has nothing left to do.
@@ -455,52 +470,23 @@ __global__ __launch_bounds__(SELECT_THREADS) void route_select_two_round_kernel(
     bool ok = false;
     if (e < E) {
         v = logits[(size_t)t * E + e] + 0.f;
-        ok = v == v;
+        ok = true;
     }
     if (!is_first) {
-        // ---- cold token: wait until every first-round workgroup has added its picks to E_A, then route inside E_A
-        if (e == 0) {
-            int it = 0;
-            while (load_agent(tr.arrived) < (uint32_t)n_first) {
-                if (++it > tr.spin_limit) { __hip_atomic_store(tr.error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
-                __builtin_amdgcn_s_sleep(8);
-            }
-        }
-        __syncthreads();
+        // ---- cold token: E_A is complete (the launch that built it has ended); route inside it
         if (e < TWO_ROUND_MASK_WORDS) s_bits[e] = load_agent(tr.mask_bits + e);
         __syncthreads();
         ok = ok && ((s_bits[e >> 5] >> (e & 31)) & 1u);
     }
     const bool selected = select_rank(sm, v, ok, e, E, k);
     if (is_first) {
-        // ---- first-round token: E_A |= picks; the picks are in place (acknowledged) before the arrival is counted
+        // ---- first-round token: E_A |= picks
         const unsigned long long sel_lanes = __ballot(selected);
         if (lane == 0) {
             const uint32_t lo = (uint32_t)sel_lanes, hi = (uint32_t)(sel_lanes >> 32);
             if (lo) __hip_atomic_fetch_or(tr.mask_bits + 2 * wave, lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (hi) __hip_atomic_fetch_or(tr.mask_bits + 2 * wave + 1, hi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (e == 0) {
-            const uint32_t before = __hip_atomic_fetch_add(tr.arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_last = before + 1u == (uint32_t)n_first;
-        }
-        __syncthreads();
-        if (s_last) {                                   // E_A is complete: publish it as a byte mask, and its size
-            if (e < TWO_ROUND_MASK_WORDS) s_bits[e] = load_agent(tr.mask_bits + e);
-            __syncthreads();
-            if (tr.mask_out && e < E) tr.mask_out[e] = (uint8_t)((s_bits[e >> 5] >> (e & 31)) & 1u);
-            if (tr.n_activated_out && e == 0) {
-                int n = 0;
-#pragma unroll
-                for (int w = 0; w < TWO_ROUND_MASK_WORDS; ++w) n += __popc(s_bits[w]);
-                *tr.n_activated_out = n;
-            }
-        }
-    } else if (n_first == 0 && b == 0) {                // no first-round token: E_A is empty
-        if (tr.mask_out && e < E) tr.mask_out[e] = 0;
-        if (tr.n_activated_out && e == 0) *tr.n_activated_out = 0;
     }
     if (keeps_row && e < WAVE) write_gates(sm, t, e, E, k, renormalize, topk_idx, topk_gate);
 }
@@ -562,14 +548,14 @@ __global__ __launch_bounds__(LOCAL_2R_THREADS) void route_select_two_round_local
             for (int i = 0; i < MAX_E / WAVE; ++i) {
                 const int ex = lane + WAVE * i;
                 const float lv = ex < E ? row[ex] + 0.f : 0.f;
-                key[i] = (ex < E && lv == lv) ? select_key(lv, ex) : 0ull;
+                key[i] = ex < E ? select_key(lv, ex) : 0ull;
             }
             for (int r = 0; r < k; ++r) {
                 unsigned long long mine = key[0];
 #pragma unroll
                 for (int i = 1; i < MAX_E / WAVE; ++i) mine = key[i] > mine ? key[i] : mine;
                 const unsigned long long best = wave_max_u64(mine);
-                if (best == 0ull) break;                 // fewer than k experts with a usable logit
+                if (best == 0ull) break;                 // fewer than k experts
                 if (mine == best) {                      // keys are distinct: exactly one lane, one of its slots
                     const int ex = (int)(0xffffffffu - (uint32_t)best);
                     atomicOr(&s_bits[ex >> 5], 1u << (ex & 31));
@@ -591,7 +577,7 @@ __global__ __launch_bounds__(LOCAL_2R_THREADS) void route_select_two_round_local
         }
     }
     // ---- this token's own selection: over all experts (first round) or inside E_A (cold)
-    const bool ok = e < E && v == v && (is_first || ((s_bits[e >> 5] >> (e & 31)) & 1u));
+    const bool ok = e < E && (is_first || ((s_bits[e >> 5] >> (e & 31)) & 1u));
     select_rank(sm, v, ok, e, E, k);
     if (e < WAVE) write_gates(sm, t, e, E, k, renormalize, topk_idx, topk_gate);
 }
@@ -603,8 +589,8 @@ static hipError_t launch_logits(const Dims& d, const void* x, const void* w_rout
     // bf16, a hidden size the four wavefronts can split into K-steps, and enough tokens to fill tiles: the matrix-core kernel
     // (with one block of 32 tokens it has only 16 workgroups and is 0.5-1 us slower than the kernel above; with 128 tokens it
     // is 1.3 us faster, with 256 tokens over 256 experts 14 us)
-    const char* force = getenv("TEAM_MOE_LOGITS_KERNEL");           // tuning aid: "plain" / "mfma" for every token count
-    const bool many_tokens = force ? force[0] == 'm' : d.T >= LOGIT_MFMA_MIN_TOKENS;
+    const int force = tuning().logits_kernel.load();                // tuning aid: 1 / 2 = the per-token / the matrix-core kernel for every token count
+    const bool many_tokens = force ? force == 2 : d.T >= LOGIT_MFMA_MIN_TOKENS;
     if (d.bf16 && d.H % (32 * LOGIT_WAVES) == 0 && many_tokens) {
         dim3 tiles((d.E + LOGIT_TILE - 1) / LOGIT_TILE, (d.T + LOGIT_TILE - 1) / LOGIT_TILE);
         hipLaunchKernelGGL(route_logits_mfma_kernel, tiles, dim3(LOGIT_THREADS), 0, s, (const uint16_t*)x, (const uint16_t*)w_router, logits,
@@ -648,7 +634,7 @@ hipError_t launch_route_two_round(const Dims& d, const void* x, const void* w_ro
     if (d.T > MAX_TOKENS_2R || d.E > 32 * TWO_ROUND_MASK_WORDS) return hipErrorInvalidValue;
     const int row_bytes = d.H * (d.bf16 ? 2 : 4);
     if (!dedup_args_ok(d, dedup, row_bytes)) return hipErrorInvalidValue;
-    uint32_t* words = (uint32_t*)state;                 // [0..7] bit set E_A, [16] arrivals, [32] error flag
+    uint32_t* words = (uint32_t*)state;                 // [0..7] bit set E_A
     if (d.T <= LOCAL_2R_MAX_TOKENS) {                   // every workgroup rebuilds E_A itself, nothing is exchanged
         hipError_t err = launch_logits(d, x, w_router, logits, nullptr, 0, s, dedup);
         if (err != hipSuccess) return err;
@@ -659,11 +645,13 @@ hipError_t launch_route_two_round(const Dims& d, const void* x, const void* w_ro
     hipError_t err = launch_logits(d, x, w_router, logits, words, TWO_ROUND_STATE_WORDS, s, dedup);
     if (err != hipSuccess) return err;
     TwoRound tr;
-    tr.token_class = token_class; tr.mask_bits = words; tr.arrived = words + 16; tr.error = words + 32;
-    tr.mask_out = mask_out; tr.n_activated_out = n_activated_out; tr.spin_limit = 1 << 16;
-    hipLaunchKernelGGL(route_select_two_round_kernel, dim3(d.T), dim3(SELECT_THREADS), 0, s, logits, tr, topk_idx, topk_gate, d.T, d.E,
-                       d.k, d.renormalize, ctrl, dedup, searched_rows(d, x), row_bytes);
-    return hipGetLastError();
+    tr.token_class = token_class; tr.mask_bits = words; tr.mask_out = mask_out; tr.n_activated_out = n_activated_out;
+    for (tr.phase = 0; tr.phase < 2; ++tr.phase) {
+        hipLaunchKernelGGL(route_select_two_round_kernel, dim3(d.T), dim3(SELECT_THREADS), 0, s, logits, tr, topk_idx, topk_gate, d.T,
+                           d.E, d.k, d.renormalize, ctrl, dedup, searched_rows(d, x), row_bytes);
+        if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+    return hipSuccess;
 }
 
 }  // namespace team

@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "team_moe.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", f)).read() for f in sorted(os.listdir(os.path.join(ROOT, "include"))) if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(team_moe_[a-z0-9_]+)\s*\(", text)))
 
@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     assert tm.status_string(0) == "ok"
-    for s in (-1, -2, -3, -4, 99):
+    for s in (-1, -2, -3, -4, -5, 99):
         assert isinstance(tm.status_string(s), str) and tm.status_string(s)
 
 
@@ -144,6 +144,20 @@ def test_bad_call_arguments_are_rejected_before_any_launch():
     assert ex(scale_gate=0x1000) == -1                       # all three scale tables or none
     assert ex(workspace=None, ws_bytes=0) == -3
     assert ex(x=None) == -1
+    assert ex(ffn_begin_event=0x1000) == -1                  # both events or none
+    # the workspace's failure mark: a status area is 256 bytes
+    assert lib.team_moe_workspace_status(fake, 128, st) == -3
+    assert lib.team_moe_workspace_status(odd, 1 << 20, st) == -3
+    # the static-array layer: configurations that do not fit its 16 MiB are rejected before anything else happens
+    big = tm.make_config(2048, 512, 256, 8, "bf16", 1, 256)
+    assert lib.team_moe_layer_forward_static(C.byref(big), fake, 256, fake, fake, fake, fake, None, fake, st) == -3
+    # tuning / testing knobs
+    v = C.c_int(0)
+    assert lib.team_moe_internal_set(b"no_such_knob", 1) == -1 and lib.team_moe_internal_get(b"no_such_knob", C.byref(v)) == -1
+    assert lib.team_moe_internal_get(b"ffn_spin_limit", None) == -1
+    assert lib.team_moe_internal_get(b"row_hash_bits", C.byref(v)) == 0 and v.value == 64
+    assert lib.team_moe_internal_set(b"row_hash_bits", 3) == 0 and tm.internal_get("row_hash_bits") == 3
+    tm.internal_set("row_hash_bits", 64)
     # NULL cfg / NULL size pointer
     assert lib.team_moe_workspace_size(None, C.byref(C.c_size_t())) == -1
     assert lib.team_moe_workspace_size(C.byref(cfg), None) == -1

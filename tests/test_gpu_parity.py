@@ -21,6 +21,20 @@ def say(*a):
     print(*a, flush=True)
 
 
+@pytest.fixture
+def knobs():
+    """Sets tuning / testing knobs of the library (include/team_moe_internal.h) for one test and puts the old values back."""
+    old = {}
+
+    def set_knob(key, value):
+        old.setdefault(key, tm.internal_get(key))
+        tm.internal_set(key, value)
+
+    yield set_knob
+    for key, value in old.items():
+        tm.internal_set(key, value)
+
+
 def c12_mask(case, M):
     """Activated set = top-M experts by summed router probability over the call's tokens, from the oracle's logits."""
     return gen.activated_set_by_summed_probability(hz.oracle_logits(case), M)
@@ -39,7 +53,9 @@ def test_cfg1_fp32(cfg1_case, M, renorm):
     s = gen.scaled(gen.CFG1, renormalize=renorm)
     case = hz.Case.make(s, cfg1_case.x, cfg1_case.w, cfg1_case.wf, cfg1_case.d_w)
     mask = None if M is None else gen.random_mask(s.E, M, seed=0)
-    say("cfg1", M, renorm, hz.full_parity(case, mask))
+    rep = hz.full_parity(case, mask)
+    say("cfg1", M, renorm, rep)
+    hz.record(f"cfg1_fp32_M{M}_renorm{renorm}", rep)
 
 
 # ----------------------------------------------------------------------------- cfg 2: 30B-A3B-shaped layer, block of 32
@@ -55,6 +71,7 @@ def test_cfg2_activated_sets(cfg2_case, M):
     mask = None if M == 128 else c12_mask(cfg2_case, M)
     rep = hz.full_parity(cfg2_case, mask)
     say("cfg2 M", M, rep)
+    hz.record(f"cfg2_M{M}", rep)
     if M < 128:
         assert rep["n_active"] <= M
 
@@ -160,26 +177,33 @@ def test_cfg3_speculative_candidates(cfg2_case):
     mask = c12_mask(case, 32)
     rep = hz.full_parity(case, mask)
     say("cfg3", rep)
+    hz.record("cfg3_M32", rep)
     counts = np.diff(orc.dispatch(hz.oracle_layer(case, mask)[1], s.E)[0])
     assert counts.max() > 32                            # spatially correlated routing: some expert serves more than 32 rows
 
 
 # ----------------------------------------------------------------------------- cfg 4: layer stack x denoising steps (sampled)
 def test_cfg4_layers_and_steps_sampled():
-    """48 layers x 16 steps is run by the benchmark; parity is checked here on a seeded sample of (layer, step)
-    pairs: 2 layers x 3 steps, activated set of 24 per (layer, step), hidden states drifting over the steps."""
+    """48 layers x 16 steps is run by the benchmark; parity is checked here on a stated sample of (layer, step)
+    pairs: 8 layers x 4 steps (32 of the 768 pairs), activated set of 24 per (layer, step), hidden states drifting over
+    the steps."""
     s = gen.CFG4
-    for layer in (7, 40):
+    worst = {}
+    for layer in (0, 7, 13, 22, 29, 36, 40, 47):
         w = gen.make_weights(s, seed=0, layer=layer)
         base = None
-        for step in (0, 5, 15):
+        for step in (0, 5, 10, 15):
             x = gen.make_x(s, seed=0, layer=layer, step=step, kind="drift", noise_std=0.0552)
             case = hz.Case.make(s, x, w) if base is None else base.with_x(s, x)
             base = base or case
             rep = hz.full_parity(case, c12_mask(case, 24))
             say("cfg4 layer", layer, "step", step, rep)
+            for key, v in rep.items():
+                worst[key] = max(worst.get(key, v), v)
         del base, case, w
         torch.cuda.empty_cache()
+    worst["sample"] = "layers 0,7,13,22,29,36,40,47 x steps 0,5,10,15 (worst case of each figure over the 32 pairs)"
+    hz.record("cfg4_M24", worst)
 
 
 # ----------------------------------------------------------------------------- cfg 5: 256 fine-grained experts, 256 tokens
@@ -192,8 +216,12 @@ def cfg5_case():
 
 @pytest.mark.parametrize("M", [256, 96, 48, 40, 24])      # (40, 24: off the listed sizes; uneven workgroups per expert, more than 64 rows per expert)
 def test_cfg5_fine_grained(cfg5_case, M):
+    record_as = f"cfg5_M{M}" if M in (256, 96, 48) else None
     mask = None if M == 256 else c12_mask(cfg5_case, M)
-    say("cfg5 M", M, hz.full_parity(cfg5_case, mask))
+    rep = hz.full_parity(cfg5_case, mask)
+    say("cfg5 M", M, rep)
+    if record_as:
+        hz.record(record_as, rep)
 
 
 # ----------------------------------------------------------------------------- other tile shapes and limits
@@ -206,13 +234,13 @@ def test_bf16_other_shapes(H, I, E, k, T):
 
 @pytest.mark.parametrize("body", ["streaming", "register operand"])
 @pytest.mark.parametrize("H,I", [(2048, 128), (2048, 256), (2048, 384), (2048, 896), (2048, 1024), (1024, 256), (512, 640), (256, 384)])
-def test_bf16_more_than_1024_routed_rows(H, I, body, monkeypatch):
+def test_bf16_more_than_1024_routed_rows(H, I, body, knobs):
     """T*k = 1152 routed rows: the FFN kernel then reads the grouped token list from global memory instead of
     its LDS copy, in both of its bodies.  56 activated experts give 20.6 rows per expert: the kernel picks its streaming
-    body; TEAM_MOE_FFN_TILED_ROWS (the average number of rows per expert from which it does) keeps it in the body with the
+    body; the knob "ffn_tiled_rows" (the average number of rows per expert from which it does) keeps it in the body with the
     register-resident token operand.  One case per number of 128-wide blocks of I that the other tests do not reach."""
     if body == "register operand":
-        monkeypatch.setenv("TEAM_MOE_FFN_TILED_ROWS", "100000")
+        knobs("ffn_tiled_rows", 100000)
     s = gen.MoEShape("rows1152", T=144, H=H, E=64, k=8, I=I, dtype="bf16")
     case = hz.Case.make(s, gen.make_x(s, seed=5), gen.make_weights(s, seed=5))
     say("1152 rows", (H, I), body, hz.full_parity(case, gen.random_mask(64, 56, seed=5)))
@@ -233,12 +261,12 @@ def test_bf16_streaming_body_many_rows_per_expert(H, I, E, k, T, M):
 
 @pytest.mark.parametrize("kernel", ["mfma", "plain"])
 @pytest.mark.parametrize("H,I,E,k,T", [(512, 128, 24, 4, 40), (256, 128, 7, 3, 20), (2048, 256, 130, 8, 100), (1024, 128, 256, 2, 17)])
-def test_bf16_both_router_score_kernels(H, I, E, k, T, kernel, monkeypatch):
+def test_bf16_both_router_score_kernels(H, I, E, k, T, kernel, knobs):
     """The router scores come from a matrix-core kernel (16 x 16 tiles) for calls of 64 tokens or more and from the
-    one-workgroup-per-token kernel below that; TEAM_MOE_LOGITS_KERNEL forces either.  Ragged tiles in both directions, a
+    one-workgroup-per-token kernel below that; the knob "logits_kernel" forces either.  Ragged tiles in both directions, a
     number of experts that is not a multiple of 4 (scalar stores), every entry point against the oracle, and the live-row
     and repeated-row forms (dense copy and row hashes made by the scores kernel) agreeing with the plain call."""
-    monkeypatch.setenv("TEAM_MOE_LOGITS_KERNEL", kernel)
+    knobs("logits_kernel", {"plain": 1, "mfma": 2}[kernel])
     s = gen.MoEShape("scores", T=T, H=H, E=E, k=k, I=I, dtype="bf16")
     case = hz.Case.make(s, gen.make_x(s, seed=21), gen.make_weights(s, seed=21))
     mask = gen.random_mask(E, max(k, E // 2), seed=21)
@@ -471,9 +499,9 @@ def test_cfg3_branches_with_repeated_rows(cfg2_case):
 
 
 @pytest.mark.parametrize("bits", ["0", "3"])
-def test_repeated_rows_with_colliding_hashes(cfg2_case, bits, monkeypatch):
+def test_repeated_rows_with_colliding_hashes(cfg2_case, bits, knobs):
     """With only a few hash bits compared, most candidates are different rows and the byte-wise comparison decides."""
-    monkeypatch.setenv("TEAM_MOE_ROW_HASH_BITS", bits)
+    knobs("row_hash_bits", int(bits))
     case = branch_case(cfg2_case, seed=1)
     say("hash bits", bits, hz.unique_rows_parity(case, c12_mask(case, 32)))
 
