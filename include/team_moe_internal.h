@@ -23,12 +23,23 @@
 #ifndef TEAM_MOE_INTERNAL_H
 #define TEAM_MOE_INTERNAL_H
 
+#include <stddef.h>
+#include <stdint.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
 
 int team_moe_internal_set(const char* key, int value);
 int team_moe_internal_get(const char* key, int* value);
+
+/*
+ * A plain read-only stream over `bytes` of device memory at `src` (16-byte aligned, a multiple of 16): `workgroups` workgroups of
+ * 256 threads read 64 KB pieces with non-temporal 16-byte loads, as the expert FFN reads its weights, and discard the data.
+ * `sink`: `workgroups` 32-bit words of device memory (practically never written).  Enqueued on `stream`; returns a team_status.
+ * The benchmark times it on buffers of the sizes the expert FFN streams: the practical ceiling of such a stream on the device.
+ */
+int team_moe_internal_stream_read(const void* src, size_t bytes, uint32_t* sink, int32_t workgroups, void* stream);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,7 @@ EXPORTS = ["team_moe_workspace_size", "team_moe_route", "team_moe_build_dispatch
            "team_moe_combine", "team_moe_layer_forward", "team_moe_route_two_round", "team_moe_layer_forward_two_round",
            "team_moe_classify_tokens", "team_moe_layer_forward_rows", "team_moe_layer_forward_unique_rows",
            "team_moe_expert_ffn_w8", "team_moe_layer_forward_w8", "team_moe_dequantize_w8", "team_moe_layer_forward_ex",
-           "team_moe_layer_forward_static", "team_moe_workspace_status", "team_moe_internal_set", "team_moe_internal_get",
+           "team_moe_layer_forward_static", "team_moe_workspace_status", "team_moe_internal_set", "team_moe_internal_get", "team_moe_internal_stream_read",
            "team_moe_status_string"]
 
 
@@ -73,6 +73,7 @@ def lib() -> C.CDLL:
         L.team_moe_workspace_status.argtypes = [vp, sz, vp]
         L.team_moe_internal_set.argtypes = [C.c_char_p, C.c_int]
         L.team_moe_internal_get.argtypes = [C.c_char_p, C.POINTER(C.c_int)]
+        L.team_moe_internal_stream_read.argtypes = [vp, sz, vp, i32, vp]
         L.team_moe_layer_forward_static.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
         L.team_moe_route_two_round.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.team_moe_layer_forward_two_round.argtypes = [cfgp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -167,6 +168,11 @@ def team_moe_workspace_status(workspace, stream=None) -> int:
 def internal_set(key: str, value: int) -> None:
     """Tuning / testing knob of include/team_moe_internal.h."""
     _check(lib().team_moe_internal_set(key.encode(), int(value)), f"team_moe_internal_set({key})")
+
+
+def internal_stream_read(src, nbytes: int, sink, workgroups: int, stream=None) -> None:
+    _check(lib().team_moe_internal_stream_read(_ptr(src), nbytes, _ptr(sink), workgroups, stream if stream is not None else _stream()),
+           "team_moe_internal_stream_read")
 
 
 def internal_get(key: str) -> int:

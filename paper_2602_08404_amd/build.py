@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libteam_moe.so")
 # (source, object suffix, extra defines); the FFN kernel file is compiled once per supported hidden size
-SOURCES = [("api.hip", "", []), ("route.hip", "", []), ("dispatch.hip", "", []), ("combine.hip", "", []), ("classify.hip", "", []), ("ffn_f32.hip", "", []), ("tuning.hip", "", []),
+SOURCES = [("api.hip", "", []), ("route.hip", "", []), ("dispatch.hip", "", []), ("combine.hip", "", []), ("classify.hip", "", []), ("ffn_f32.hip", "", []), ("tuning.hip", "", []), ("stream_read.hip", "", []),
            ("ffn_bf16.hip", "", [])] + [("ffn_bf16_kernel.hip", f"_ksa{ksa}", [f"-DFFN_KSA_THIS_FILE={ksa}"]) for ksa in (16, 8, 4, 2)] \
           + [("ffn_bf16_kernel.hip", f"_w8_ksa{ksa}", [f"-DFFN_KSA_THIS_FILE={ksa}", "-DFFN_W8_THIS_FILE=1"]) for ksa in (16, 8)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

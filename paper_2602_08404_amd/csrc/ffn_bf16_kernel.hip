@@ -270,7 +270,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                                                                    const unsigned char* __restrict__ wg, const unsigned char* __restrict__ wu,
                                                                    const unsigned char* __restrict__ wd, uint16_t* __restrict__ h,
                                                                    float* __restrict__ out, FfnCtrl* __restrict__ ctrl, int T, int k, int E,
-                                                                   int spin_limit, int skip_publish, unsigned long long* __restrict__ fail_mark,
+                                                                   int spin_limit, int skip_publish, unsigned long long* __restrict__ fail_mark, int down_rotate,
                                                                    int tiled_min_avg_rows, int expert_major_ok, int wide_min_avg_rows,
                                                                    const int32_t* __restrict__ topk_idx, int32_t* __restrict__ inv_pos_out,
                                                                    const float* __restrict__ sg, const float* __restrict__ su,
@@ -436,7 +436,9 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     const uint32_t Gu = (uint32_t)G;
     const int base_a = (int)(total_a / Gu), rem_a = (int)(total_a % Gu), base_b = (int)(total_b / Gu), rem_b = (int)(total_b % Gu);
     const int a_begin = bx * base_a + min(bx, rem_a), a_end = a_begin + base_a + (bx < rem_a ? 1 : 0);
-    const int b_begin = bx * base_b + min(bx, rem_b), b_end = b_begin + base_b + (bx < rem_b ? 1 : 0);
+    // The down list is dealt out with the workgroup index rotated by down_rotate (see the host side: half the grid).
+    const int bxd = (int)(((uint32_t)bx + (uint32_t)down_rotate) % Gu);
+    const int b_begin = bxd * base_b + min(bxd, rem_b), b_end = b_begin + base_b + (bxd < rem_b ? 1 : 0);
     const int n_a = a_end - a_begin, n_mine = n_a + (b_end - b_begin);
     __syncthreads();
 
@@ -751,7 +753,7 @@ hipError_t launch_ffn_fused(const FfnArgs& p) {
     const int grid = p.grid_override > 0 && p.grid_override < resident ? p.grid_override : resident;
     hipLaunchKernelGGL((ffn_fused_kernel<KSA, KSB, RB, WB>), dim3(grid), dim3(FFN_THREADS), 0, p.stream, p.x, p.offsets, p.sorted_token,
                        p.active, p.n_active, (const unsigned char*)p.wg, (const unsigned char*)p.wu, (const unsigned char*)p.wd, p.h, p.out,
-                       p.ctrl, p.T, p.k, p.E, p.spin_limit, p.skip_publish, p.fail_mark, p.tiled_min_avg_rows, p.expert_major, p.wide_min_avg_rows, p.topk_idx, p.inv_pos_out, p.sg, p.su,
+                       p.ctrl, p.T, p.k, p.E, p.spin_limit, p.skip_publish, p.fail_mark, p.down_rotate >= 0 ? p.down_rotate : grid / 2, p.tiled_min_avg_rows, p.expert_major, p.wide_min_avg_rows, p.topk_idx, p.inv_pos_out, p.sg, p.su,
                        p.sd);
     return hipGetLastError();
 }
