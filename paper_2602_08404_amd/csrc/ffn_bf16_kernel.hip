@@ -69,15 +69,13 @@ __device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt
 __device__ __forceinline__ void store_coherent(uint32_t* p, uint32_t v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ bf16x8_t load_coherent_16(const uint16_t* p) {
-    union {
-        unsigned long long u[2];
-        bf16x8_t v;
-    } r;
-    const unsigned long long* p64 = reinterpret_cast<const unsigned long long*>(p);
-    r.u[0] = __hip_atomic_load(p64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    r.u[1] = __hip_atomic_load(p64 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return r.v;
+// 16 bytes of h at byte offset `off` of the buffer `rsrc` describes, as one device-scope load (a buffer load can carry the
+// scope in its cache-policy bits; 16 is the device-scope bit of this architecture's encoding).  Offsets beyond the
+// descriptor's size read as zero.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_bits;
+__device__ __forceinline__ bf16x8_t load_coherent_16(__amdgpu_buffer_rsrc_t rsrc, uint32_t off) {
+    const u32x4_bits v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)off, 0, /*sc1*/ 16);
+    return __builtin_bit_cast(bf16x8_t, v);
 }
 // Returns v, but opaque to the optimiser: values derived from the result are recomputed where they are used
 // instead of being hoisted out of the item loop and kept in registers (the token operand needs those registers).
@@ -525,12 +523,22 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     const uint32_t red_base = tiled::lds_addr(s_mem + LDS_BYTES - RED_A);     // red_a; red_b ends at the same address
     const uint32_t redb_base = tiled::lds_addr(s_mem + LDS_BYTES - RED_B);
 
+    // h as a buffer (raw, no swizzle, 32-bit data format), for its device-scope gather in the down phase
+    const __amdgpu_buffer_rsrc_t h_rsrc = __builtin_amdgcn_make_buffer_rsrc(h, 0, (int)min((size_t)A * I * 2, (size_t)0x7fffffff), 0x00020000);
+
     Item cur{};
     if (n_mine > 0) cur = item_at(0);
     bool ahead = false;                      // the current item's weights were requested during the previous item
     for (int step = 0; step < n_mine; ++step) {   // this workgroup's gate/up items, then its down items
         const bool has_next = step + 1 < n_mine;
         const Item nxt = item_at(has_next ? step + 1 : step);
+        // First down item of an expert with nothing requested yet (the publication of this workgroup's own h has just drained
+        // its loads): thread 0 looks at the expert's counter BEFORE the item's weights are requested.  Loads return in
+        // order, so behind the weights the first look would take as long as the weights do; on its own it is one round trip,
+        // and in most launches it already finds the expert complete.
+        bool seen_complete = false;
+        if (!cur.is_a && cur.a != ready_slot && !ahead && tid == 0)
+            seen_complete = __hip_atomic_load(&ctrl->done[cur.a][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= TILES_A;
         if (!ahead) issue_loads(cur);
         ahead = false;
         const bool is_a = cur.is_a;
@@ -645,7 +653,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                 if (m > 0 && wave < RB * NT) load_uniform(sd + (size_t)cur.e * H + it * 16 * RB + (wave / NT) * 16, sc_d);
             }
             if (a != ready_slot) {       // wait until every gate/up item of this expert has published h
-                if (tid == 0) {
+                if (tid == 0 && !seen_complete) {
                     int spins = 0;
                     while (__hip_atomic_load(&ctrl->done[a][0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < TILES_A) {
                         __builtin_amdgcn_s_sleep(8);      // ~0.2 us between polls; the counters sit in different memory channels
@@ -673,10 +681,10 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                     for (int nt = 0; nt < NT; ++nt) {
                         const int row = row_base + nt * 16 + n;
                         const bool valid = token_of_row(r0, m, row) >= 0;
-                        const uint16_t* hp = h + (size_t)(valid ? r0 + row : 0) * I + wave * KSLICE_B + q * (16 / WB);
+                        const uint32_t hoff = (uint32_t)(((valid ? r0 + row : 0) * I + wave * KSLICE_B + q * (16 / WB)) * 2);
                         if (valid) {
 #pragma unroll
-                            for (int s = 0; s < KSB; ++s) opr[nt][s] = load_coherent_16(hp + kstep_col(s));
+                            for (int s = 0; s < KSB; ++s) opr[nt][s] = load_coherent_16(h_rsrc, hoff + 2u * (uint32_t)kstep_col(s));
                         } else {
 #pragma unroll
                             for (int s = 0; s < KSB; ++s) opr[nt][s] = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
@@ -751,10 +759,25 @@ hipError_t launch_ffn_fused(const FfnArgs& p) {
     }
     const int resident = per_cu * p.n_cu;
     const int grid = p.grid_override > 0 && p.grid_override < resident ? p.grid_override : resident;
+    const int down_rotate = p.down_rotate >= 0 ? p.down_rotate : grid / 2;
+    if (p.cooperative) {
+        // Measurement aid: the same launch through the runtime's cooperative path, which refuses a grid that cannot be resident
+        // at once.  (It does not reserve the device either: workgroups of a kernel from another stream can still hold compute units.)
+        const uint16_t* x = p.x; const int32_t *offsets = p.offsets, *sorted_token = p.sorted_token, *active = p.active, *n_active = p.n_active;
+        const unsigned char *wg = (const unsigned char*)p.wg, *wu = (const unsigned char*)p.wu, *wd = (const unsigned char*)p.wd;
+        uint16_t* h = p.h; float* out = p.out; FfnCtrl* ctrl = p.ctrl; int T = p.T, k = p.k, E = p.E, spin_limit = p.spin_limit;
+        int skip_publish = p.skip_publish; unsigned long long* fail_mark = p.fail_mark; int rot = down_rotate;
+        int tiled_rows = p.tiled_min_avg_rows, expert_major = p.expert_major, wide_rows = p.wide_min_avg_rows;
+        const int32_t* topk_idx = p.topk_idx; int32_t* inv_pos_out = p.inv_pos_out; const float *sg = p.sg, *su = p.su, *sd = p.sd;
+        void* args[] = {&x, &offsets, &sorted_token, &active, &n_active, &wg, &wu, &wd, &h, &out, &ctrl, &T, &k, &E, &spin_limit, &skip_publish,
+                        &fail_mark, &rot, &tiled_rows, &expert_major, &wide_rows, &topk_idx, &inv_pos_out, &sg, &su, &sd};
+        return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(&ffn_fused_kernel<KSA, KSB, RB, WB>), dim3(grid), dim3(FFN_THREADS), args, 0,
+                                          p.stream);
+    }
     hipLaunchKernelGGL((ffn_fused_kernel<KSA, KSB, RB, WB>), dim3(grid), dim3(FFN_THREADS), 0, p.stream, p.x, p.offsets, p.sorted_token,
                        p.active, p.n_active, (const unsigned char*)p.wg, (const unsigned char*)p.wu, (const unsigned char*)p.wd, p.h, p.out,
-                       p.ctrl, p.T, p.k, p.E, p.spin_limit, p.skip_publish, p.fail_mark, p.down_rotate >= 0 ? p.down_rotate : grid / 2, p.tiled_min_avg_rows, p.expert_major, p.wide_min_avg_rows, p.topk_idx, p.inv_pos_out, p.sg, p.su,
-                       p.sd);
+                       p.ctrl, p.T, p.k, p.E, p.spin_limit, p.skip_publish, p.fail_mark, down_rotate, p.tiled_min_avg_rows, p.expert_major,
+                       p.wide_min_avg_rows, p.topk_idx, p.inv_pos_out, p.sg, p.su, p.sd);
     return hipGetLastError();
 }
 
