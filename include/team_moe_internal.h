@@ -14,8 +14,6 @@
  *   "logits_kernel"    [TEAM_MOE_LOGITS_KERNEL]    0: by token count; 1: per-token kernel; 2: matrix-core kernel
  *   "row_hash_bits"    [TEAM_MOE_ROW_HASH_BITS]    bits of the row hashes that the repeated-row search compares (64)
  *   "ffn_spin_limit"   [TEAM_MOE_FFN_SPIN_LIMIT]   polls after which a wait inside the expert FFN kernel gives up (65536)
- *   "ffn_down_rotate"  [TEAM_MOE_FFN_DOWN_ROTATE]  workgroup b takes share (b + this) mod grid of the down-projection items (0, the
- *                                                  default: the same share as of the gate/up items; -1: half the grid)
  *   "ffn_cooperative"  [TEAM_MOE_FFN_COOPERATIVE]  1: launch the expert FFN kernel through hipLaunchCooperativeKernel (a measurement)
  *   "ffn_skip_publish" (none)                      1: gate/up items do not announce their results, so every wait for them
  *                                                  gives up after ffn_spin_limit polls: the failure path (NaN rows, the

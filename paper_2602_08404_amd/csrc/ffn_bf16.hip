@@ -51,7 +51,6 @@ static hipError_t launch_common(const Dims& d, FfnArgs& p, hipStream_t s) {
     p.grid_override = tn.ffn_grid.load();             // tuning aid only; never raises the grid above what is resident
     p.spin_limit = tn.ffn_spin_limit.load();          // ~0.1 s of polling by default; see the waits in the kernel
     p.skip_publish = tn.ffn_skip_publish.load();
-    p.down_rotate = tn.ffn_down_rotate.load();
     p.cooperative = tn.ffn_cooperative.load();
     // With at most 32 tokens per call an expert has at most 32 rows: one pass of the register-resident token operand, which is
     // reused across the expert's items.  Beyond that the kernel decides on the device from the average number of rows per expert.

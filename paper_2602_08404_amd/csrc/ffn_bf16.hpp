@@ -44,7 +44,6 @@ struct FfnArgs {
     int n_cu;                   // compute units of that device
     int grid_override;          // > 0: use a smaller grid than the resident maximum (tuning aid)
     int spin_limit;
-    int down_rotate;            // workgroup b takes share (b + down_rotate) mod grid of the down list; < 0: half the grid
     int cooperative;            // measurement aid: launch through hipLaunchCooperativeKernel
     int skip_publish;           // tests only: gate/up items do not publish, so every wait for them gives up
     unsigned long long* fail_mark;   // workspace word that receives WS_FAIL_MARK when a wait gives up (see kernels.hpp)

@@ -268,7 +268,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
                                                                    const unsigned char* __restrict__ wg, const unsigned char* __restrict__ wu,
                                                                    const unsigned char* __restrict__ wd, uint16_t* __restrict__ h,
                                                                    float* __restrict__ out, FfnCtrl* __restrict__ ctrl, int T, int k, int E,
-                                                                   int spin_limit, int skip_publish, unsigned long long* __restrict__ fail_mark, int down_rotate,
+                                                                   int spin_limit, int skip_publish, unsigned long long* __restrict__ fail_mark,
                                                                    int tiled_min_avg_rows, int expert_major_ok, int wide_min_avg_rows,
                                                                    const int32_t* __restrict__ topk_idx, int32_t* __restrict__ inv_pos_out,
                                                                    const float* __restrict__ sg, const float* __restrict__ su,
@@ -434,9 +434,7 @@ __global__ __launch_bounds__(FFN_THREADS, 2) void ffn_fused_kernel(const uint16_
     const uint32_t Gu = (uint32_t)G;
     const int base_a = (int)(total_a / Gu), rem_a = (int)(total_a % Gu), base_b = (int)(total_b / Gu), rem_b = (int)(total_b % Gu);
     const int a_begin = bx * base_a + min(bx, rem_a), a_end = a_begin + base_a + (bx < rem_a ? 1 : 0);
-    // The down list is dealt out with the workgroup index rotated by down_rotate (see the host side: half the grid).
-    const int bxd = (int)(((uint32_t)bx + (uint32_t)down_rotate) % Gu);
-    const int b_begin = bxd * base_b + min(bxd, rem_b), b_end = b_begin + base_b + (bxd < rem_b ? 1 : 0);
+    const int b_begin = bx * base_b + min(bx, rem_b), b_end = b_begin + base_b + (bx < rem_b ? 1 : 0);
     const int n_a = a_end - a_begin, n_mine = n_a + (b_end - b_begin);
     __syncthreads();
 
@@ -759,24 +757,23 @@ hipError_t launch_ffn_fused(const FfnArgs& p) {
     }
     const int resident = per_cu * p.n_cu;
     const int grid = p.grid_override > 0 && p.grid_override < resident ? p.grid_override : resident;
-    const int down_rotate = p.down_rotate >= 0 ? p.down_rotate : grid / 2;
     if (p.cooperative) {
         // Measurement aid: the same launch through the runtime's cooperative path, which refuses a grid that cannot be resident
         // at once.  (It does not reserve the device either: workgroups of a kernel from another stream can still hold compute units.)
         const uint16_t* x = p.x; const int32_t *offsets = p.offsets, *sorted_token = p.sorted_token, *active = p.active, *n_active = p.n_active;
         const unsigned char *wg = (const unsigned char*)p.wg, *wu = (const unsigned char*)p.wu, *wd = (const unsigned char*)p.wd;
         uint16_t* h = p.h; float* out = p.out; FfnCtrl* ctrl = p.ctrl; int T = p.T, k = p.k, E = p.E, spin_limit = p.spin_limit;
-        int skip_publish = p.skip_publish; unsigned long long* fail_mark = p.fail_mark; int rot = down_rotate;
+        int skip_publish = p.skip_publish; unsigned long long* fail_mark = p.fail_mark;
         int tiled_rows = p.tiled_min_avg_rows, expert_major = p.expert_major, wide_rows = p.wide_min_avg_rows;
         const int32_t* topk_idx = p.topk_idx; int32_t* inv_pos_out = p.inv_pos_out; const float *sg = p.sg, *su = p.su, *sd = p.sd;
         void* args[] = {&x, &offsets, &sorted_token, &active, &n_active, &wg, &wu, &wd, &h, &out, &ctrl, &T, &k, &E, &spin_limit, &skip_publish,
-                        &fail_mark, &rot, &tiled_rows, &expert_major, &wide_rows, &topk_idx, &inv_pos_out, &sg, &su, &sd};
+                        &fail_mark, &tiled_rows, &expert_major, &wide_rows, &topk_idx, &inv_pos_out, &sg, &su, &sd};
         return hipLaunchCooperativeKernel(reinterpret_cast<const void*>(&ffn_fused_kernel<KSA, KSB, RB, WB>), dim3(grid), dim3(FFN_THREADS), args, 0,
                                           p.stream);
     }
     hipLaunchKernelGGL((ffn_fused_kernel<KSA, KSB, RB, WB>), dim3(grid), dim3(FFN_THREADS), 0, p.stream, p.x, p.offsets, p.sorted_token,
                        p.active, p.n_active, (const unsigned char*)p.wg, (const unsigned char*)p.wu, (const unsigned char*)p.wd, p.h, p.out,
-                       p.ctrl, p.T, p.k, p.E, p.spin_limit, p.skip_publish, p.fail_mark, down_rotate, p.tiled_min_avg_rows, p.expert_major,
+                       p.ctrl, p.T, p.k, p.E, p.spin_limit, p.skip_publish, p.fail_mark, p.tiled_min_avg_rows, p.expert_major,
                        p.wide_min_avg_rows, p.topk_idx, p.inv_pos_out, p.sg, p.su, p.sd);
     return hipGetLastError();
 }

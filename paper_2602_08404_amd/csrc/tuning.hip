@@ -29,7 +29,6 @@ std::atomic<int>* knob(Tuning& t, const char* key) {
     if (!strcmp(key, "row_hash_bits")) return &t.row_hash_bits;
     if (!strcmp(key, "ffn_spin_limit")) return &t.ffn_spin_limit;
     if (!strcmp(key, "ffn_skip_publish")) return &t.ffn_skip_publish;
-    if (!strcmp(key, "ffn_down_rotate")) return &t.ffn_down_rotate;
     if (!strcmp(key, "ffn_cooperative")) return &t.ffn_cooperative;
     return nullptr;
 }
@@ -49,7 +48,6 @@ Tuning& tuning() {
         t.logits_kernel = lk && lk[0] == 'p' ? 1 : (lk && lk[0] == 'm' ? 2 : 0);
         t.row_hash_bits = env_int("TEAM_MOE_ROW_HASH_BITS", 64);
         t.ffn_spin_limit = env_int("TEAM_MOE_FFN_SPIN_LIMIT", 1 << 16);
-        t.ffn_down_rotate = env_int("TEAM_MOE_FFN_DOWN_ROTATE", 0);
         t.ffn_cooperative = env_int("TEAM_MOE_FFN_COOPERATIVE", 0);
     });
     return t;

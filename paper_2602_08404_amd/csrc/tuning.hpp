@@ -14,7 +14,6 @@ struct Tuning {
     std::atomic<int> logits_kernel{0};       // TEAM_MOE_LOGITS_KERNEL: 0 by token count, 1 per-token kernel, 2 matrix-core kernel
     std::atomic<int> row_hash_bits{64};      // TEAM_MOE_ROW_HASH_BITS: bits of the row hashes the repeated-row search compares (tests force collisions with fewer)
     std::atomic<int> ffn_spin_limit{1 << 16};// TEAM_MOE_FFN_SPIN_LIMIT: polls before a wait inside the FFN kernel gives up (about 0.1 s by default)
-    std::atomic<int> ffn_down_rotate{0};     // TEAM_MOE_FFN_DOWN_ROTATE: rotation of the workgroup index for the down list (0: none; -1: half the grid)
     std::atomic<int> ffn_cooperative{0};     // TEAM_MOE_FFN_COOPERATIVE: 1: launch the FFN kernel through hipLaunchCooperativeKernel (measurement aid)
     std::atomic<int> ffn_skip_publish{0};    // tests only: gate/up items do not announce their results, so every wait for them gives up
 };
