@@ -20,7 +20,8 @@ def kernel_functions(asm_text: str) -> Dict[str, List[str]]:
     """name -> instruction/marker lines of every `team::ffn_fused_kernel` instantiation in the file."""
     out = {}
     for m in re.finditer(r"^(_ZN4team16ffn_fused_kernel[^:\n]*):", asm_text, re.M):
-        end = asm_text.find("s_endpgm", m.end())
+        end = asm_text.find(".Lfunc_end", m.end())          # (a function may hold several s_endpgm: one per early exit)
+        assert end > 0, m.group(1)
         out[m.group(1)] = [l.strip() for l in asm_text[m.end():end].split("\n")]
     return out
 
