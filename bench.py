@@ -40,9 +40,9 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per ffn_fused_kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and the file under profiles/ that holds the
 # counter runs, keyed by (workload, activated-set size); counters cannot be read from inside this script.
-PMC_TRAFFIC = {("cfg2", 32): (306609997 + 2900434, "profiles/moe_layer_kernels_cfg2_M32.md"),
-               ("cfg3", 32): (319283000 + 11553000, "profiles/expert_ffn_cfg3_cfg4_cfg5.md"),
-               ("cfg5", 96): (625746000 + 20990000, "profiles/expert_ffn_cfg3_cfg4_cfg5.md")}
+PMC_TRAFFIC = {("cfg2", 32): (306700000 + 2900000, "profiles/moe_layer_kernels_cfg2_M32.md"),
+               ("cfg3", 32): (319400000 + 11600000, "profiles/expert_ffn_cfg3_cfg4_cfg5.md"),
+               ("cfg5", 96): (625800000 + 21000000, "profiles/expert_ffn_cfg3_cfg4_cfg5.md")}
 
 
 def log(*a):
