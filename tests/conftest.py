@@ -19,7 +19,8 @@ def golden_dir():
 
 @pytest.fixture(scope="session", autouse=True)
 def parity_error_report():
-    """Writes the errors the GPU parity tests achieved (tests/harness.py: record) to gpurun_out/parity_errors.json."""
+    """Writes the errors the GPU parity tests achieved (tests/harness.py: record) to parity_errors.json in the directory
+    TEAM_MOE_REPORT_DIR names (default: test_reports/ at the repository root)."""
     yield
     try:
         import harness
@@ -27,7 +28,7 @@ def parity_error_report():
         return
     if harness.RECORDS:
         import json
-        out = os.path.join(ROOT, "gpurun_out")
+        out = os.environ.get("TEAM_MOE_REPORT_DIR") or os.path.join(ROOT, "test_reports")
         os.makedirs(out, exist_ok=True)
         with open(os.path.join(out, "parity_errors.json"), "w") as f:
             json.dump({"row_rel": "per row max|gpu-ref| / max|ref|, max over rows", "elem": "max |gpu-ref| / max(|ref|, 1e-3 rms(ref))",

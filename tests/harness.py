@@ -9,7 +9,7 @@ Bars (stated here, used by every parity test):
   * tokens inside the gap band are checked against the oracle's FFN + combine run on the GPU's own selection.
 Also reported, without a bar of its own (the stated bar is the row form): the element-wise error
 max |gpu - ref| / max(|ref|, 1e-3 * rms(ref)).  The achieved errors of the tests that call record() are written to
-gpurun_out/parity_errors.json when the test session ends (tests/conftest.py).
+parity_errors.json when the test session ends (tests/conftest.py says where).
 """
 from __future__ import annotations
 
